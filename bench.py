@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the BLR linear forward path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1] [--sweep] [--no-cpu]
+
+A step is one forward call of the workload's layer (every kernel of the call) on inputs that are
+already resident in HBM. The default workload is the ViT-B-width BLAST layer (768x768, b=16,
+r=96, T=6304, bf16). Prints ONE JSON line on stdout. `--sweep` additionally measures every
+configuration at every T against the same-shape dense GEMM and writes the table to
+gpurun_out/sweep.json (and to stderr).
+
+Static factors are re-laid out once before the timed region (the paper's offline weight
+re-layout); the timed call receives the packed factors.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+import blr_inputs as bi  # noqa: E402
+from paper_2512_20861_amd import roofline as rf  # noqa: E402
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def to_dev(ht):
+    import torch
+    if ht.dtype == "bf16":
+        return torch.from_numpy(ht.bits.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return torch.from_numpy(ht.bits.copy()).cuda()
+
+
+class GpuLayer:
+    """Device-resident factors of one layer plus a closure that enqueues its forward."""
+
+    def __init__(self, cfg, T, seed=bi.BASE_SEED, random_x=True):
+        import torch
+        from paper_2512_20861_amd import binding as B
+        self.B, self.cfg, self.T = B, cfg, T
+        self.op, self.n_in, self.n_out = cfg["op"], cfg["n_in"], cfg["n_out"]
+        self.dtype = cfg["dtype"]
+        td = torch.bfloat16 if self.dtype == "bf16" else torch.float32
+        lay = bi.make_layer(cfg, seed)
+        self.host = lay
+        # activations: values do not affect run time; draw them on the device for the big sweeps
+        if random_x:
+            self.X = (torch.randn((T, self.n_in), device="cuda", dtype=torch.float32) * cfg["x_scale"]).to(td)
+        self.Y = torch.empty((T, self.n_out), device="cuda", dtype=td)
+        dt = B.BF16 if self.dtype == "bf16" else B.F32
+        if self.op == "monarch":
+            self.R, self.L = to_dev(lay.R), to_dev(lay.L)
+            self.nb, self.r = cfg["nblocks"], cfg["r"]
+            self.ws = torch.empty(max(B.monarch_workspace_bytes(T, self.n_in, self.n_out, self.nb, self.r, dt), 16),
+                                  dtype=torch.uint8, device="cuda")
+            self.flags = 0
+        else:
+            self.U, self.S, self.V = to_dev(lay.U), to_dev(lay.S), to_dev(lay.V)
+            self.b, self.r = cfg["b"], cfg["r"]
+            self.flags = 0
+            if self.dtype == "bf16" and (self.n_in // self.b) % 8 == 0 and self.r % 8 == 0 and self.b <= 16:
+                self.Sp, self.Vp = B.blast_pack(self.S, self.V, self.n_in, self.n_out, self.b, self.r)
+                self.flags = B.BLAST_PACKED
+            self.ws = torch.empty(max(B.blast_workspace_bytes(T, self.n_in, self.n_out, self.b, self.r, dt, self.flags), 16),
+                                  dtype=torch.uint8, device="cuda")
+
+    def set_x(self, X):
+        self.X = X
+
+    def forward(self, extra_flags=0):
+        B = self.B
+        if self.op == "monarch":
+            B.monarch_forward(self.X, self.R, self.L, self.Y, self.nb, self.r, self.flags | extra_flags, self.ws)
+        elif self.flags & B.BLAST_PACKED:
+            B.blast_forward(self.X, self.U, self.Sp, self.Vp, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
+        else:
+            B.blast_forward(self.X, self.U, self.S, self.V, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
+
+    def shape_args(self):
+        c = self.cfg
+        return dict(n_in=c["n_in"], n_out=c["n_out"], r=c["r"], b=c.get("b", c.get("nblocks", 1)))
+
+
+def time_calls(fn, steps, warmup):
+    """Mean milliseconds per call over `steps` back-to-back calls, HIP events on the launch stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def stage_times(layer, steps, warmup):
+    """Per-stage mean launch duration (ms): (first, last), or None if the call is a single kernel."""
+    B = layer.B
+    try:
+        t1 = time_calls(lambda: layer.forward(B.ONLY_FIRST_STAGE), steps, warmup)
+        t2 = time_calls(lambda: layer.forward(B.ONLY_LAST_STAGE), steps, warmup)
+        return t1, t2
+    except B.BlrError as e:
+        if e.status == B.ERR_UNSUPPORTED:
+            return None
+        raise
+
+
+def cpu_baseline(cfg, T_cpu):
+    """The fp64 oracle as it stands, timed on this machine's host cores (baseline only)."""
+    import oracle
+    lay = bi.make_layer(cfg)
+    X = bi.activations(T_cpu, cfg["n_in"], cfg["dtype"], scale=cfg["x_scale"])
+    nthreads = oracle.binding.default_threads()
+    if cfg["op"] == "monarch":
+        fn = lambda: oracle.monarch_forward(X.f64, lay.R.f64, lay.L.f64, nthreads=nthreads)
+    else:
+        fn = lambda: oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64, nthreads=nthreads)
+    fn()
+    best = 1e30
+    for _ in range(3):
+        t0 = time.perf_counter()
+        fn()
+        best = min(best, time.perf_counter() - t0)
+    return {"value": T_cpu / best, "unit": "tokens/s", "cores": nthreads, "kind": "oracle",
+            "sample": f"{T_cpu} of the workload's tokens, fp64, best of 3 after one warm-up ({best:.2f} s per pass)"}
+
+
+def dominant_roofline(layer, ms_total, stages):
+    """Roofline entry of the kernel that takes the most time in the call.
+
+    The bytes/FLOPs are the ALGORITHMIC ones of the part of the path that kernel covers:
+    inputs + factors it reads + outputs it writes, each once."""
+    cfg, T = layer.cfg, layer.T
+    sa = layer.shape_args()
+    n_in, n_out, r, b = sa["n_in"], sa["n_out"], sa["r"], sa["b"]
+    es = 2 if cfg["dtype"] == "bf16" else 4
+    if stages is None:
+        kern, ms = "whole call (one kernel)", ms_total
+        byt = rf.algorithmic_bytes(cfg["op"], T, n_in, n_out, r, b, es)
+        flo = rf.flops(cfg["op"], T, n_in, n_out, r, b)
+    else:
+        first_dom = stages[0] >= stages[1]
+        ms = stages[0] if first_dom else stages[1]
+        inter = T * b * r * es                       # Z' (Monarch) or A (BLAST), written by the first, read by the last
+        if cfg["op"] == "monarch":
+            if first_dom:
+                kern, byt, flo = "stage 1 (block-diagonal R + permutation)", es * (T * n_in + r * n_in) + inter, 2 * T * r * n_in
+            else:
+                kern, byt, flo = "stage 2 (block-diagonal L)", inter + es * (r * n_out + T * n_out), 2 * T * r * n_out
+        else:
+            if first_dom:
+                kern, byt, flo = "stage 1+2 (X V and coupling)", es * (T * n_in + r * n_in + r * b * b) + inter, 2 * T * r * (n_in + b * b)
+            else:
+                kern, byt, flo = "stage 3 (A U^T)", inter + es * (r * n_out + T * n_out), 2 * T * r * n_out
+    t = ms * 1e-3
+    if byt / rf.HBM_PEAK >= flo / rf.MFMA_BF16_PEAK or cfg["dtype"] != "bf16":
+        ach = byt / t / 1e9
+        return {"bound": "hbm", "achieved": ach, "peak": rf.HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (rf.HBM_PEAK / 1e9),
+                "traffic": None, "kernel": kern, "kernel_ms": ms, "algorithmic_bytes": byt}
+    ach = flo / t / 1e12
+    return {"bound": "mfma", "achieved": ach, "peak": rf.MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": ach / (rf.MFMA_BF16_PEAK / 1e12),
+            "traffic": None, "kernel": kern, "kernel_ms": ms, "algorithmic_flops": flo}
+
+
+def run_sweep(steps, warmup):
+    import torch
+    from paper_2512_20861_amd import binding as B
+    rows = []
+    for name in ("C1", "C2a", "C2b", "C3a", "C3b"):
+        cfg = bi.CONFIGS[name]
+        W = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
+        for T in cfg["T"]:
+            layer = GpuLayer(cfg, T)
+            ms = time_calls(layer.forward, steps, warmup)
+            st = stage_times(layer, steps, warmup)
+            Yd = torch.empty_like(layer.Y)
+            ms_dense = time_calls(lambda: B.dense_reference_forward(layer.X, W, Yd), steps, warmup)
+            sa = layer.shape_args()
+            mem, mfma = rf.floors(cfg["op"], T, **sa)
+            dmem, dmfma = rf.floors("dense", T, cfg["n_in"], cfg["n_out"])
+            row = {"config": name, "op": cfg["op"], "T": T, "ms": ms, "tokens_per_s": T / (ms * 1e-3),
+                   "stage_ms": st, "floor_hbm_us": mem * 1e6, "floor_mfma_us": mfma * 1e6,
+                   "bound": "hbm" if mem >= mfma else "mfma", "frac_of_floor": max(mem, mfma) / (ms * 1e-3),
+                   "dense_ms": ms_dense, "dense_frac_of_floor": max(dmem, dmfma) / (ms_dense * 1e-3),
+                   "speedup_vs_dense": ms_dense / ms}
+            rows.append(row)
+            log(f"{name:4s} {cfg['op']:7s} T={T:5d}  {ms*1e3:9.1f} us  stages={None if st is None else [round(x*1e3,1) for x in st]}  "
+                f"floor {max(mem, mfma)*1e6:7.1f} us ({row['bound']}) frac {row['frac_of_floor']:.3f} | "
+                f"dense {ms_dense*1e3:9.1f} us frac {row['dense_frac_of_floor']:.3f} | speedup {row['speedup_vs_dense']:.2f}x")
+            del layer, Yd
+        del W
+        torch.cuda.empty_cache()
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "sweep.json"), "w") as f:
+        json.dump(rows, f, indent=1)
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C1", choices=sorted(bi.CONFIGS))
+    ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
+    ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (token-parallel sharding needs no exchange and is not "
+              "implemented); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_20861_amd import binding as B
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.manual_seed(0)
+    cfg = bi.CONFIGS[args.workload]
+    T = args.tokens or cfg["T"][-1]
+    layer = GpuLayer(cfg, T)
+    layer.set_x(to_dev(bi.activations(T, cfg["n_in"], cfg["dtype"], scale=cfg["x_scale"])))
+
+    torch.cuda.synchronize()
+    ms = time_calls(layer.forward, args.steps, args.warmup)
+    torch.cuda.synchronize()
+    stages = stage_times(layer, args.steps, args.warmup)
+    roof = dominant_roofline(layer, ms, stages)
+
+    W = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
+    Yd = torch.empty_like(layer.Y)
+    ms_dense = time_calls(lambda: B.dense_reference_forward(layer.X, W, Yd), args.steps, args.warmup)
+
+    sa = layer.shape_args()
+    out = {
+        "metric": "BLR linear tokens/s", "value": T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {cfg['op']} linear {cfg['n_in']}->{cfg['n_out']}, "
+                               f"b={sa['b']}, r={sa['r']}, T={T}, {cfg['dtype']} storage / fp32 accumulate",
+                   "factors": "packed once before timing" if getattr(layer, "flags", 0) & B.BLAST_PACKED else "canonical"},
+        "roofline": roof,
+        "dense_same_shape": {"ms_per_step": ms_dense, "tokens_per_s": T / (ms_dense * 1e-3), "speedup_of_blr": ms_dense / ms},
+    }
+    if not args.no_cpu:
+        T_cpu = min(T, {"C1": 6304, "C0": 8}.get(args.workload, 512))
+        out["cpu_baseline"] = cpu_baseline(cfg, T_cpu)
+    if args.sweep:
+        out["sweep"] = run_sweep(max(args.steps // 4, 20), max(args.warmup // 2, 5))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

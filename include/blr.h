@@ -1,0 +1,123 @@
+/*
+ * blr.h - C ABI of the block low-rank (BLR) linear forward library for AMD MI355X (gfx950).
+ *
+ * The library evaluates Y = X W^T for a weight W[n_out][n_in] that is never formed, but given
+ * by Monarch or BLAST factors (paper Section 2.1, "Weight Structures"), plus a plain dense
+ * product that serves as the speed-up denominator.
+ *
+ * Conventions shared by every entry point
+ *   - All pointers are DEVICE pointers (HIP global memory), 16-byte aligned, to dense row-major
+ *     tensors without padding. Storage type `dt`: BLR_BF16 (bfloat16 bit patterns, arithmetic in
+ *     bf16 x bf16 -> fp32 MFMA, intermediates that leave the chip rounded to bf16, Y rounded to
+ *     bf16) or BLR_F32 (everything fp32).
+ *   - Ownership: the caller owns every buffer, including the workspace. The library allocates
+ *     nothing, frees nothing and never synchronises; it only enqueues kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream). Buffers must stay alive and
+ *     unmodified until the stream has passed the call. Inputs are read-only; Y and the workspace
+ *     are overwritten; Y and the workspace must not alias any input or each other.
+ *   - Errors: the return code only. No exceptions, no abort, no output to stderr. All argument
+ *     checks happen on the host before anything is enqueued, so an error return means nothing
+ *     was launched (except BLR_ERR_LAUNCH, which reports hipGetLastError() after a launch).
+ *     T == 0 returns BLR_OK without launching (X and Y may then be null; the factors may not).
+ *   - Calls on different streams may overlap as long as their Y/workspace buffers are distinct.
+ */
+#ifndef BLR_H
+#define BLR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BLR_OK = 0,
+    BLR_ERR_INVALID_ARG = 1,   /* null pointer, negative T, non-positive or non-divisible sizes, bad dtype/flags */
+    BLR_ERR_UNSUPPORTED = 2,   /* valid by the mathematics but no kernel covers it */
+    BLR_ERR_WORKSPACE = 3,     /* workspace missing or smaller than blr_*_workspace_bytes() */
+    BLR_ERR_LAUNCH = 4         /* the HIP runtime reported an error when launching */
+} blr_status;
+
+typedef enum { BLR_F32 = 0, BLR_BF16 = 1 } blr_dtype;
+
+typedef void* blr_stream;      /* a hipStream_t */
+
+/* flags of blr_monarch_forward: order of the output features (paper Section 4, optimisation 3).
+ * INTERLEAVED is the (n, q, b2) order of the full operator P L P^T R: Y[t][j*nblocks + k].
+ * BLOCKED is the cheaper (n, b2, q) order, Y[t][k*q + j], usable when the consumer's weight rows
+ * are permuted offline. */
+#define BLR_MONARCH_OUT_INTERLEAVED 0u
+#define BLR_MONARCH_OUT_BLOCKED     1u
+/* flag of blr_blast_forward: S and V are the re-laid-out tensors written by blr_blast_pack (the
+ * one-time offline weight re-layout of paper Section 4, optimisations 1 and 5), not the canonical ones. */
+#define BLR_BLAST_PACKED            2u
+/* flag of every forward: run the portable scalar-ALU kernels even where an MFMA kernel exists
+ * (used by the tests to cross-check the two GPU paths). */
+#define BLR_FORCE_GENERIC           0x100u
+/* measurement aids of the two BLR forwards: enqueue only the kernels up to and including the one
+ * that writes the workspace intermediate (FIRST), or only the kernel that consumes it (LAST; the
+ * workspace must hold the intermediate of an earlier call with identical arguments). Mutually
+ * exclusive; BLR_ERR_UNSUPPORTED where the call is a single kernel. */
+#define BLR_ONLY_FIRST_STAGE        0x200u
+#define BLR_ONLY_LAST_STAGE         0x400u
+
+/*
+ * Monarch forward (paper Section 2.1 "Monarch"; Section 4 "Monarch", optimisations 1-3).
+ * With b = nblocks, p = n_in/b, q = n_out/b, r' = r/b:
+ *   Z'[t][k][l*r'+rho] = sum_a X[t][l*p+a] * R[l][rho*b+k][a]     (block-diagonal R, permutation folded into the store)
+ *   Y[t][o(k,j)]       = sum_m Z'[t][k][m] * L[k][j][m]           (block-diagonal L), o = j*b+k or k*q+j by flags
+ * X[T][n_in]; R[b][r][p] (the paper's first stored factor, middle dimension ordered b2-fastest);
+ * L[b][q][r] (second stored factor, innermost dimension ordered r'-fastest then b1); Y[T][n_out].
+ * r is the width of one middle block (r = r'*b); nblocks must divide n_in, n_out and r.
+ * workspace: at least blr_monarch_workspace_bytes(...) bytes (holds Z').
+ */
+size_t     blr_monarch_workspace_bytes(int64_t T, int n_in, int n_out, int nblocks, int r, blr_dtype dt);
+blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void* Y,
+                               int64_t T, int n_in, int n_out, int nblocks, int r,
+                               blr_dtype dt, unsigned flags,
+                               void* workspace, size_t workspace_bytes, blr_stream stream);
+
+/*
+ * BLAST forward (paper Section 2.1 "BLAST"; Section 4 "BLAST", optimisations 4-5).
+ * With q = n_in/b, p = n_out/b:
+ *   Z[t][j][rho]  = sum_c X[t][j*q+c] * V[j][c][rho]
+ *   A[t][i][rho]  = sum_j S[i][j][rho] * Z[t][j][rho]
+ *   Y[t][i*p+a]   = sum_rho A[t][i][rho] * U[i][a][rho]
+ * X[T][n_in]; U[b][p][r]; S[b][b][r] indexed [output block i][input block j]; V[b][q][r]; Y[T][n_out].
+ * b must divide n_in and n_out. With BLR_BLAST_PACKED, `S` and `V` point to the tensors produced
+ * by blr_blast_pack (bf16 only). workspace: at least blr_blast_workspace_bytes(...) bytes with the
+ * same flags (holds A; without BLR_BLAST_PACKED also the per-call re-layout of S and V).
+ */
+size_t     blr_blast_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags);
+blr_status blr_blast_forward(const void* X, const void* U, const void* S, const void* V, void* Y,
+                             int64_t T, int n_in, int n_out, int b, int r,
+                             blr_dtype dt, unsigned flags,
+                             void* workspace, size_t workspace_bytes, blr_stream stream);
+
+/*
+ * One-time re-layout of the static BLAST factors (paper Section 4: weights are static, so their
+ * layout is changed once before inference). bf16 only.
+ *   V_packed[j][rho][c] = V[j][c][rho]                      (contraction index contiguous)
+ *   S_packed[rho][i][j] = S[i][j][rho], i and j padded with zeros to 16   (one 16x16 tile per rho)
+ * Sizes in bytes from blr_blast_packed_v_bytes / blr_blast_packed_s_bytes. b <= 16 required.
+ */
+size_t     blr_blast_packed_v_bytes(int n_in, int b, int r, blr_dtype dt);
+size_t     blr_blast_packed_s_bytes(int b, int r, blr_dtype dt);
+blr_status blr_blast_pack(const void* S, const void* V, void* S_packed, void* V_packed,
+                          int n_in, int n_out, int b, int r, blr_dtype dt, blr_stream stream);
+
+/*
+ * Dense reference (paper Section 2.1 "Dense"): Y[t][o] = sum_a X[t][a] * W[o][a], W[n_out][n_in].
+ * A hand-written GEMM of the same family as the BLR kernels; the denominator of every speed-up.
+ */
+blr_status blr_dense_reference_forward(const void* X, const void* W, void* Y,
+                                       int64_t T, int n_in, int n_out, blr_dtype dt,
+                                       unsigned flags, blr_stream stream);
+
+const char* blr_status_string(blr_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLR_H */

@@ -1,0 +1,157 @@
+"""Thin Python binding of the C-ABI library (include/blr.h): argument marshalling only.
+
+Every function has the name of the C entry point without the `blr_` prefix, takes torch tensors
+that live on the GPU (PyTorch is used for device memory and streams, nothing else), and passes
+their device pointers, the sizes read off their shapes, and the current HIP stream to the library.
+Nothing is computed here. If the shared library has not been built the import of the library
+fails loudly; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libblr.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, 1, 2, 3, 4
+F32, BF16 = 0, 1
+MONARCH_OUT_INTERLEAVED, MONARCH_OUT_BLOCKED, BLAST_PACKED, FORCE_GENERIC = 0, 1, 2, 0x100
+ONLY_FIRST_STAGE, ONLY_LAST_STAGE = 0x200, 0x400
+
+EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forward",
+           "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_v_bytes",
+           "blr_blast_packed_s_bytes", "blr_blast_pack", "blr_dense_reference_forward")
+
+_lib = None
+
+
+class BlrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libblr.so (built by paper_2512_20861_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_20861_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci, cu, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint, ctypes.c_size_t
+        L.blr_status_string.restype = ctypes.c_char_p
+        L.blr_status_string.argtypes = [ci]
+        L.blr_monarch_workspace_bytes.restype = sz
+        L.blr_monarch_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci]
+        L.blr_monarch_forward.restype = ci
+        L.blr_monarch_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, cu, vp, sz, vp]
+        L.blr_blast_workspace_bytes.restype = sz
+        L.blr_blast_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
+        L.blr_blast_forward.restype = ci
+        L.blr_blast_forward.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, cu, vp, sz, vp]
+        L.blr_blast_packed_v_bytes.restype = sz
+        L.blr_blast_packed_v_bytes.argtypes = [ci, ci, ci, ci]
+        L.blr_blast_packed_s_bytes.restype = sz
+        L.blr_blast_packed_s_bytes.argtypes = [ci, ci, ci]
+        L.blr_blast_pack.restype = ci
+        L.blr_blast_pack.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.blr_dense_reference_forward.restype = ci
+        L.blr_dense_reference_forward.argtypes = [vp, vp, vp, i64, ci, ci, ci, cu, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().blr_status_string(status).decode()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported storage type {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous GPU tensors")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise BlrError(status, where)
+
+
+def monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt) -> int:
+    return lib().blr_monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt)
+
+
+def monarch_forward(X, R, L, Y, nblocks, r, flags=0, workspace=None, stream=None):
+    """Y[T][n_out] <- Monarch(X[T][n_in]; R[nblocks][r][n_in/nblocks], L[nblocks][n_out/nblocks][r])."""
+    T, n_in = X.shape
+    n_out = Y.shape[1]
+    dt = _dt(X)
+    if workspace is None:
+        workspace = torch.empty(max(monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt), 16),
+                                dtype=torch.uint8, device=X.device)
+    _check(lib().blr_monarch_forward(_ptr(X), _ptr(R), _ptr(L), _ptr(Y), T, n_in, n_out, nblocks, r, dt, flags,
+                                     _ptr(workspace), workspace.numel(), _stream(stream)), "blr_monarch_forward")
+    return Y
+
+
+def blast_workspace_bytes(T, n_in, n_out, b, r, dt, flags=0) -> int:
+    return lib().blr_blast_workspace_bytes(T, n_in, n_out, b, r, dt, flags)
+
+
+def blast_forward(X, U, S, V, Y, b, r, flags=0, workspace=None, stream=None):
+    """Y[T][n_out] <- BLAST(X[T][n_in]; U[b][n_out/b][r], S[b][b][r], V[b][n_in/b][r]);
+    with BLAST_PACKED in flags, S and V are the outputs of blast_pack."""
+    T, n_in = X.shape
+    n_out = Y.shape[1]
+    dt = _dt(X)
+    if workspace is None:
+        workspace = torch.empty(max(blast_workspace_bytes(T, n_in, n_out, b, r, dt, flags), 16),
+                                dtype=torch.uint8, device=X.device)
+    _check(lib().blr_blast_forward(_ptr(X), _ptr(U), _ptr(S), _ptr(V), _ptr(Y), T, n_in, n_out, b, r, dt, flags,
+                                   _ptr(workspace), workspace.numel(), _stream(stream)), "blr_blast_forward")
+    return Y
+
+
+def blast_packed_v_bytes(n_in, b, r, dt=BF16) -> int:
+    return lib().blr_blast_packed_v_bytes(n_in, b, r, dt)
+
+
+def blast_packed_s_bytes(b, r, dt=BF16) -> int:
+    return lib().blr_blast_packed_s_bytes(b, r, dt)
+
+
+def blast_pack(S, V, n_in, n_out, b, r, stream=None):
+    """One-time re-layout of the BLAST factors; returns (S_packed, V_packed) as byte buffers."""
+    dt = _dt(V)
+    Sp = torch.empty(max(blast_packed_s_bytes(b, r, dt), 16), dtype=torch.uint8, device=V.device)
+    Vp = torch.empty(max(blast_packed_v_bytes(n_in, b, r, dt), 16), dtype=torch.uint8, device=V.device)
+    _check(lib().blr_blast_pack(_ptr(S), _ptr(V), _ptr(Sp), _ptr(Vp), n_in, n_out, b, r, dt, _stream(stream)),
+           "blr_blast_pack")
+    return Sp, Vp
+
+
+def dense_reference_forward(X, W, Y, flags=0, stream=None):
+    """Y[T][n_out] <- X[T][n_in] W[n_out][n_in]^T."""
+    T, n_in = X.shape
+    n_out = Y.shape[1]
+    _check(lib().blr_dense_reference_forward(_ptr(X), _ptr(W), _ptr(Y), T, n_in, n_out, _dt(X), flags,
+                                             _stream(stream)), "blr_dense_reference_forward")
+    return Y

@@ -1,0 +1,71 @@
+// One-time re-layout of the static BLAST factors (bf16):
+//   Vt[j][rho][c] = V[j][c][rho]      contraction index of stage 1 made contiguous
+//   Sp[rho][i][j] = S[i][j][rho]      one zero-padded 16x16 coupling tile per rank index
+#include "blr_common.h"
+
+namespace blr {
+namespace {
+
+__global__ __launch_bounds__(256) void pack_v_kernel(const bf16_t* V, bf16_t* Vt, int q, int r) {
+    __shared__ bf16_t tile[32][34];
+    const int j = blockIdx.z;
+    const int rho0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const bf16_t* Vj = V + (int64_t)j * q * r;
+    bf16_t* Vtj = Vt + (int64_t)j * q * r;
+    for (int cc = ty; cc < 32; cc += 8) {
+        const int c = c0 + cc, rho = rho0 + tx;
+        tile[cc][tx] = (c < q && rho < r) ? Vj[(int64_t)c * r + rho] : (bf16_t)0;
+    }
+    __syncthreads();
+    for (int rr = ty; rr < 32; rr += 8) {
+        const int rho = rho0 + rr, c = c0 + tx;
+        if (rho < r && c < q) Vtj[(int64_t)rho * q + c] = tile[tx][rr];
+    }
+}
+
+__global__ __launch_bounds__(256) void pack_s_kernel(const bf16_t* S, bf16_t* Sp, int b, int r) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)r * 256) return;
+    const int j = (int)(e & 15), i = (int)((e >> 4) & 15);
+    const int rho = (int)(e >> 8);
+    Sp[e] = (i < b && j < b) ? S[((int64_t)i * b + j) * r + rho] : (bf16_t)0;
+}
+
+// stand-alone coupling from the packed tiles: A[t][i][rho] = sum_j Sp[rho][i][j] * Z[t][j][rho]
+__global__ __launch_bounds__(256) void coupling_packed_kernel(const bf16_t* Z, const bf16_t* Sp, bf16_t* A, int64_t T, int b, int r) {
+    const int64_t total = T * b * r;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int rho = (int)(e % r);
+        const int i = (int)((e / r) % b);
+        const int64_t t = e / ((int64_t)r * b);
+        float acc = 0.f;
+        for (int j = 0; j < b; ++j)
+            acc = fmaf(bf16_to_float(Sp[(int64_t)rho * 256 + i * 16 + j]), bf16_to_float(Z[(t * b + j) * r + rho]), acc);
+        A[e] = float_to_bf16(acc);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_coupling_packed(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
+    const int64_t total = T * b * r;
+    if (total <= 0) return hipSuccess;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536 * 16) blocks = 65536 * 16;
+    hipLaunchKernelGGL(coupling_packed_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                       (const bf16_t*)Z, (const bf16_t*)Sp, (bf16_t*)A, T, b, r);
+    return hipGetLastError();
+}
+
+hipError_t launch_blast_pack(const void* S, const void* V, void* Sp, void* Vt, int n_in, int b, int r, hipStream_t s) {
+    const int q = n_in / b;
+    dim3 gv((unsigned)((r + 31) / 32), (unsigned)((q + 31) / 32), (unsigned)b);
+    hipLaunchKernelGGL(pack_v_kernel, gv, dim3(256), 0, s, (const bf16_t*)V, (bf16_t*)Vt, q, r);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(pack_s_kernel, dim3((unsigned)r), dim3(256), 0, s, (const bf16_t*)S, (bf16_t*)Sp, b, r);
+    return hipGetLastError();
+}
+
+}  // namespace blr

@@ -1,0 +1,234 @@
+// C-ABI front end: argument validation, workspace planning, kernel selection. Host code only.
+#include "../../include/blr.h"
+#include "blr_common.h"
+
+using namespace blr;
+
+namespace {
+
+inline size_t elem_size(blr_dtype dt) { return dt == BLR_BF16 ? 2 : 4; }
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+inline bool dtype_ok(blr_dtype dt) { return dt == BLR_F32 || dt == BLR_BF16; }
+inline blr_status from_hip(hipError_t e) { return e == hipSuccess ? BLR_OK : BLR_ERR_LAUNCH; }
+
+blr_status run_gemm(const GemmDesc& d, blr_dtype dt, bool allow_mfma, hipStream_t s) {
+    if (allow_mfma && dt == BLR_BF16 && mfma_gemm_supported(d)) return from_hip(launch_gemm_mfma(d, s));
+    return from_hip(launch_gemm_valu(d, dt == BLR_BF16 ? DType::BF16 : DType::F32, s));
+}
+
+bool monarch_shape_ok(int64_t T, int n_in, int n_out, int nblocks, int r) {
+    return T >= 0 && n_in > 0 && n_out > 0 && nblocks > 0 && r > 0 && n_in % nblocks == 0 &&
+           n_out % nblocks == 0 && r % nblocks == 0;
+}
+
+bool blast_shape_ok(int64_t T, int n_in, int n_out, int b, int r) {
+    return T >= 0 && n_in > 0 && n_out > 0 && b > 0 && r > 0 && n_in % b == 0 && n_out % b == 0;
+}
+
+// How a BLAST call is executed and where its temporaries live in the workspace.
+struct BlastPlan {
+    enum Path { GENERIC, MFMA_UNFUSED, MFMA_STAGE12, MFMA_FULL } path;
+    size_t off_A, off_Z, off_Vt, off_Sp, total;
+};
+
+BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
+    BlastPlan pl{};
+    const int q = n_in / b;
+    const bool packed = flags & BLR_BLAST_PACKED;
+    const bool mfma = dt == BLR_BF16 && !(flags & BLR_FORCE_GENERIC) && b <= 16 && q % 8 == 0 && r % 8 == 0;
+    const size_t inter = (size_t)T * b * r * elem_size(dt);
+    size_t off = 0;
+    if (!mfma) {
+        pl.path = BlastPlan::GENERIC;
+        pl.off_A = off; off += align_up(inter);
+        pl.off_Z = off; off += align_up(inter);
+    } else {
+        if (blast_full_fusion_supported(T, n_in, n_out, b, r)) pl.path = BlastPlan::MFMA_FULL;
+        else if (blast_fused_supported(T, n_in, b, r)) pl.path = BlastPlan::MFMA_STAGE12;
+        else pl.path = BlastPlan::MFMA_UNFUSED;
+        if (pl.path != BlastPlan::MFMA_FULL) { pl.off_A = off; off += align_up(inter); }
+        if (pl.path == BlastPlan::MFMA_UNFUSED) { pl.off_Z = off; off += align_up(inter); }
+        if (!packed) {
+            pl.off_Vt = off; off += align_up((size_t)b * q * r * 2);
+            pl.off_Sp = off; off += align_up((size_t)r * 256 * 2);
+        }
+    }
+    pl.total = off;
+    return pl;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* blr_status_string(blr_status s) {
+    switch (s) {
+        case BLR_OK: return "ok";
+        case BLR_ERR_INVALID_ARG: return "invalid argument";
+        case BLR_ERR_UNSUPPORTED: return "unsupported configuration";
+        case BLR_ERR_WORKSPACE: return "workspace missing or too small";
+        case BLR_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+size_t blr_monarch_workspace_bytes(int64_t T, int n_in, int n_out, int nblocks, int r, blr_dtype dt) {
+    if (!monarch_shape_ok(T, n_in, n_out, nblocks, r) || !dtype_ok(dt)) return 0;
+    return align_up((size_t)T * nblocks * r * elem_size(dt));
+}
+
+blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void* Y,
+                               int64_t T, int n_in, int n_out, int nblocks, int r,
+                               blr_dtype dt, unsigned flags,
+                               void* workspace, size_t workspace_bytes, blr_stream stream) {
+    if (!monarch_shape_ok(T, n_in, n_out, nblocks, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_MONARCH_OUT_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if (!R || !L) return BLR_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(R) || !aligned16(L) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
+    if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null
+    if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < blr_monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt)) return BLR_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int b = nblocks, p = n_in / b, q = n_out / b, rp = r / b;
+    const bool allow_mfma = !(flags & BLR_FORCE_GENERIC);
+
+    // stage 1: block-diagonal R; tile column n' = k*r' + rho reads row rho*b + k of R[l] (the
+    // re-layout of the first factor done in the load index) and lands at Z'[t][k][l*r' + rho]
+    GemmDesc s1{};
+    s1.A = X; s1.a_gs = p; s1.a_rs = n_in;
+    s1.B = R; s1.b_gs = (int64_t)r * p; s1.b_rs = p; s1.b_ks = 1; s1.b_div = rp; s1.b_mul = b;
+    s1.C = workspace; s1.c_rs = (int64_t)b * r; s1.c_gs = rp; s1.c_div = rp; s1.c_hi = r; s1.c_lo = 1;
+    s1.M = T; s1.N = r; s1.K = p; s1.G = b;
+    if (!(flags & BLR_ONLY_LAST_STAGE)) {
+        blr_status st = run_gemm(s1, dt, allow_mfma, s);
+        if (st != BLR_OK || (flags & BLR_ONLY_FIRST_STAGE)) return st;
+    }
+
+    // stage 2: block-diagonal L; the output order is a column map of the store
+    GemmDesc s2{};
+    s2.A = workspace; s2.a_gs = r; s2.a_rs = (int64_t)b * r;
+    s2.B = L; s2.b_gs = (int64_t)q * r; s2.b_rs = r; s2.b_ks = 1; s2.b_div = 0; s2.b_mul = 0;
+    s2.C = Y; s2.c_rs = n_out; s2.c_div = 1; s2.c_lo = 0;
+    if (flags & BLR_MONARCH_OUT_BLOCKED) { s2.c_gs = q; s2.c_hi = 1; }
+    else { s2.c_gs = 1; s2.c_hi = b; }
+    s2.M = T; s2.N = q; s2.K = r; s2.G = b;
+    return run_gemm(s2, dt, allow_mfma, s);
+}
+
+size_t blr_blast_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
+    if (!blast_shape_ok(T, n_in, n_out, b, r) || !dtype_ok(dt)) return 0;
+    return blast_plan(T, n_in, n_out, b, r, dt, flags).total;
+}
+
+size_t blr_blast_packed_v_bytes(int n_in, int b, int r, blr_dtype dt) {
+    if (dt != BLR_BF16 || n_in <= 0 || b <= 0 || r <= 0 || n_in % b) return 0;
+    return align_up((size_t)n_in * r * 2);
+}
+
+size_t blr_blast_packed_s_bytes(int b, int r, blr_dtype dt) {
+    if (dt != BLR_BF16 || b <= 0 || b > 16 || r <= 0) return 0;
+    return align_up((size_t)r * 256 * 2);
+}
+
+blr_status blr_blast_pack(const void* S, const void* V, void* S_packed, void* V_packed,
+                          int n_in, int n_out, int b, int r, blr_dtype dt, blr_stream stream) {
+    if (!S || !V || !S_packed || !V_packed) return BLR_ERR_INVALID_ARG;
+    if (!blast_shape_ok(0, n_in, n_out, b, r) || dt != BLR_BF16 || b > 16) return BLR_ERR_INVALID_ARG;
+    if (!aligned16(S) || !aligned16(V) || !aligned16(S_packed) || !aligned16(V_packed)) return BLR_ERR_INVALID_ARG;
+    return from_hip(launch_blast_pack(S, V, S_packed, V_packed, n_in, b, r, (hipStream_t)stream));
+}
+
+blr_status blr_blast_forward(const void* X, const void* U, const void* S, const void* V, void* Y,
+                             int64_t T, int n_in, int n_out, int b, int r,
+                             blr_dtype dt, unsigned flags,
+                             void* workspace, size_t workspace_bytes, blr_stream stream) {
+    if (!U || !S || !V) return BLR_ERR_INVALID_ARG;
+    if (!blast_shape_ok(T, n_in, n_out, b, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_BLAST_PACKED) && (dt != BLR_BF16 || b > 16 || (flags & BLR_FORCE_GENERIC))) return BLR_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(U) || !aligned16(S) || !aligned16(V) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
+    if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null
+    if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    const BlastPlan pl = blast_plan(T, n_in, n_out, b, r, dt, flags);
+    if ((flags & BLR_BLAST_PACKED) && pl.path == BlastPlan::GENERIC) return BLR_ERR_UNSUPPORTED;
+    if (pl.total > 0 && (!workspace || workspace_bytes < pl.total)) return BLR_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int q = n_in / b, p = n_out / b;
+    unsigned char* ws = (unsigned char*)workspace;
+    void* Aws = ws + pl.off_A;
+    void* Zws = ws + pl.off_Z;
+
+    // stage 3 (all multi-kernel paths): Y[t][i*p + a] = sum_rho A[t][i][rho] U[i][a][rho]
+    GemmDesc s3{};
+    s3.A = Aws; s3.a_gs = r; s3.a_rs = (int64_t)b * r;
+    s3.B = U; s3.b_gs = (int64_t)p * r; s3.b_rs = r; s3.b_ks = 1; s3.b_div = 0;
+    s3.C = Y; s3.c_rs = n_out; s3.c_gs = p; s3.c_div = 1; s3.c_hi = 1; s3.c_lo = 0;
+    s3.M = T; s3.N = p; s3.K = r; s3.G = b;
+
+    // stage 1 as a stand-alone product: Z[t][j][rho]
+    GemmDesc s1{};
+    s1.A = X; s1.a_gs = q; s1.a_rs = n_in;
+    s1.C = Zws; s1.c_rs = (int64_t)b * r; s1.c_gs = r; s1.c_div = 1; s1.c_hi = 1; s1.c_lo = 0;
+    s1.M = T; s1.N = r; s1.K = q; s1.G = b;
+
+    const bool first = !(flags & BLR_ONLY_LAST_STAGE), last = !(flags & BLR_ONLY_FIRST_STAGE);
+    if (pl.path == BlastPlan::GENERIC) {
+        if (first) {
+            s1.B = V; s1.b_gs = (int64_t)q * r; s1.b_rs = 1; s1.b_ks = r; s1.b_div = 0;   // V[j][c][rho]: rho contiguous
+            blr_status st = run_gemm(s1, dt, false, s);
+            if (st != BLR_OK) return st;
+            st = from_hip(launch_coupling_valu(Zws, S, Aws, T, b, r, dt == BLR_BF16 ? DType::BF16 : DType::F32, s));
+            if (st != BLR_OK) return st;
+        }
+        return last ? run_gemm(s3, dt, false, s) : BLR_OK;
+    }
+
+    const void* Vt = V;
+    const void* Sp = S;
+    if (!(flags & BLR_BLAST_PACKED) && first) {
+        blr_status st = from_hip(launch_blast_pack(S, V, ws + pl.off_Sp, ws + pl.off_Vt, n_in, b, r, s));
+        if (st != BLR_OK) return st;
+        Vt = ws + pl.off_Vt;
+        Sp = ws + pl.off_Sp;
+    }
+    if (pl.path == BlastPlan::MFMA_FULL) {
+        if (!first || !last) return BLR_ERR_UNSUPPORTED;   // one kernel: there are no stages to select
+        return from_hip(launch_blast_full(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s));
+    }
+    if (first) {
+        if (pl.path == BlastPlan::MFMA_STAGE12) {
+            blr_status st = from_hip(launch_blast_stage12(X, Vt, Sp, Aws, T, n_in, b, r, s));
+            if (st != BLR_OK) return st;
+        } else {
+            // unfused: both intermediates go through the workspace
+            s1.B = Vt; s1.b_gs = (int64_t)q * r; s1.b_rs = q; s1.b_ks = 1; s1.b_div = 0;
+            blr_status st = run_gemm(s1, dt, true, s);
+            if (st != BLR_OK) return st;
+            st = from_hip(launch_coupling_packed(Zws, Sp, Aws, T, b, r, s));
+            if (st != BLR_OK) return st;
+        }
+    }
+    return last ? run_gemm(s3, dt, true, s) : BLR_OK;
+}
+
+blr_status blr_dense_reference_forward(const void* X, const void* W, void* Y,
+                                       int64_t T, int n_in, int n_out, blr_dtype dt,
+                                       unsigned flags, blr_stream stream) {
+    if (!W) return BLR_ERR_INVALID_ARG;
+    if (T < 0 || n_in <= 0 || n_out <= 0 || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~BLR_FORCE_GENERIC) return BLR_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return BLR_ERR_INVALID_ARG;
+    if (T == 0) return BLR_OK;
+    if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    GemmDesc d{};
+    d.A = X; d.a_gs = 0; d.a_rs = n_in;
+    d.B = W; d.b_gs = 0; d.b_rs = n_in; d.b_ks = 1; d.b_div = 0;
+    d.C = Y; d.c_rs = n_out; d.c_gs = 0; d.c_div = 1; d.c_hi = 1; d.c_lo = 0;
+    d.M = T; d.N = n_out; d.K = n_in; d.G = 1;
+    return run_gemm(d, dt, !(flags & BLR_FORCE_GENERIC), (hipStream_t)stream);
+}
+
+}  // extern "C"

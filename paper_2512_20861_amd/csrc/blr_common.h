@@ -1,0 +1,64 @@
+// Internal declarations shared by the kernel translation units and the C-ABI front end.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace blr {
+
+typedef unsigned short bf16_t;  // bfloat16 bit pattern
+
+__host__ __device__ inline float bf16_to_float(bf16_t v) {
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)v << 16;
+    return c.f;
+}
+// round to nearest even (inputs are finite)
+__host__ __device__ inline bf16_t float_to_bf16(float f) {
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    uint32_t u = c.u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// A batched "NT" product with index maps, general enough for every contraction of the path:
+//   C(g, m, n) = sum_k A(g, m, k) * B(g, n, k),  g < G, m < M, n < N, k < K
+// element addresses (in elements of the storage type):
+//   A(g,m,k) = A + g*a_gs + m*a_rs + k
+//   B(g,n,k) = B + g*b_gs + brow(n)*b_rs + k*b_ks,  brow(n) = (n % b_div)*b_mul + n / b_div   (row gather)
+//   C(g,m,n) = C + m*c_rs + g*c_gs + (n / c_div)*c_hi + (n % c_div)*c_lo                       (column scatter)
+// b_div = N, b_mul = 1... is written as b_div = 0 meaning brow(n) = n.
+struct GemmDesc {
+    const void* A; int64_t a_gs; int64_t a_rs;
+    const void* B; int64_t b_gs; int64_t b_rs; int64_t b_ks; int b_div; int b_mul;
+    void* C; int64_t c_rs; int64_t c_gs; int c_div; int64_t c_hi; int64_t c_lo;
+    int64_t M; int N; int K; int G;
+};
+
+enum class DType { F32 = 0, BF16 = 1 };
+
+// portable scalar-ALU kernels (any shape, any stride, fp32 accumulation)
+hipError_t launch_gemm_valu(const GemmDesc& d, DType dt, hipStream_t s);
+// A[t][i][rho] = sum_j S[i][j][rho] * Z[t][j][rho], Z and A are [T][b][r]
+hipError_t launch_coupling_valu(const void* Z, const void* S, void* A, int64_t T, int b, int r, DType dt, hipStream_t s);
+
+// bf16 MFMA kernels; `mfma_gemm_supported` states the alignment contract
+bool mfma_gemm_supported(const GemmDesc& d);
+hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s);
+
+// BLAST: fused stage 1 + coupling on MFMA. X[T][n_in], Vt[b][r][q], Sp[r][16][16] -> A[T][b][r] (bf16)
+bool blast_fused_supported(int64_t T, int n_in, int b, int r);
+hipError_t launch_blast_stage12(const void* X, const void* Vt, const void* Sp, void* A,
+                                int64_t T, int n_in, int b, int r, hipStream_t s);
+// BLAST: whole layer in one kernel for small b*r. U[b][p][r]
+bool blast_full_fusion_supported(int64_t T, int n_in, int n_out, int b, int r);
+hipError_t launch_blast_full(const void* X, const void* U, const void* Sp, const void* Vt, void* Y,
+                             int64_t T, int n_in, int n_out, int b, int r, hipStream_t s);
+
+// stand-alone coupling reading the packed tiles Sp[r][16][16] (bf16)
+hipError_t launch_coupling_packed(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s);
+
+// BLAST weight re-layout (bf16)
+hipError_t launch_blast_pack(const void* S, const void* V, void* Sp, void* Vt, int n_in, int b, int r, hipStream_t s);
+
+}  // namespace blr

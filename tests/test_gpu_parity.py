@@ -1,0 +1,147 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle, element by
+element on identical seeded inputs. Tolerance: max|delta| / max|Y_ref| <= 2e-2 for bf16 storage
+(bf16 x bf16 -> fp32 MFMA, bf16 intermediates and output), <= 1e-5 for the fp32 path."""
+import numpy as np
+import pytest
+
+import blr_inputs as bi
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2512_20861_amd import binding
+    binding.lib()      # fails loudly if the HIP library is not built
+
+
+def _gu():
+    import gpu_util
+    return gpu_util
+
+
+# ---------------------------------------------------------------- Monarch
+MONARCH_CASES = [
+    # T, n_in, n_out, nblocks, r, dtype
+    (8, 256, 256, 4, 64, "f32"),         # the fp32 check configuration
+    (8, 256, 256, 4, 64, "bf16"),
+    (300, 512, 768, 4, 256, "bf16"),     # several 128-row tiles and a ragged token tail; p != q != r
+    (77, 512, 1376, 4, 128, "bf16"),     # q = 344: a ragged column tail
+    (130, 384, 384, 2, 96, "bf16"),      # K = 192 and 96: not multiples of 64
+    (37, 36, 60, 3, 9, "bf16"),          # rows not 16-byte aligned: portable kernels
+    (37, 36, 60, 3, 9, "f32"),
+    (1, 512, 512, 4, 128, "bf16"),
+    (65, 1024, 1024, 16, 256, "bf16"),   # 16 blocks as in the paper's Llama settings, r' = 16
+]
+
+
+@pytest.mark.parametrize("T,n_in,n_out,nb,r,dtype", MONARCH_CASES)
+@pytest.mark.parametrize("order", ["interleaved", "blocked"])
+@pytest.mark.parametrize("generic", [False, True])
+def test_monarch_parity(T, n_in, n_out, nb, r, dtype, order, generic):
+    gu = _gu()
+    lay = bi.monarch_layer(n_in, n_out, nb, r, dtype)
+    X = bi.activations(T, n_in, dtype)
+    flags = (gu.B.MONARCH_OUT_BLOCKED if order == "blocked" else 0) | (gu.B.FORCE_GENERIC if generic else 0)
+    Y = gu.to_f64(gu.run_monarch(X, lay, flags))
+    Yref = oracle.monarch_forward(X.f64, lay.R.f64, lay.L.f64,
+                                  oracle.OUT_BLOCKED if order == "blocked" else oracle.OUT_INTERLEAVED)
+    err = gu.rel_err(Y, Yref)
+    print(f"monarch {T}x{n_in}->{n_out} b={nb} r={r} {dtype} {order} generic={generic}: rel err {err:.3e}")
+    assert err <= gu.TOL[dtype]
+
+
+# ---------------------------------------------------------------- BLAST
+BLAST_CASES = [
+    # T, n_in, n_out, b, r, dtype
+    (333, 768, 768, 16, 96, "bf16"),     # ViT-B-width configuration at a ragged token count
+    (130, 1024, 512, 8, 72, "bf16"),     # q = 128, p = 64, r not a multiple of 16
+    (70, 512, 2048, 16, 256, "bf16"),
+    (50, 36, 30, 3, 10, "bf16"),         # misaligned: portable kernels
+    (50, 36, 30, 3, 10, "f32"),
+    (9, 256, 256, 4, 64, "f32"),
+    (1, 768, 768, 16, 96, "bf16"),
+    (200, 1152, 1152, 9, 128, "bf16"),   # b = 9 (DiT-XL/2 rows of the paper's layer table)
+]
+
+
+@pytest.mark.parametrize("T,n_in,n_out,b,r,dtype", BLAST_CASES)
+@pytest.mark.parametrize("mode", ["canonical", "packed", "generic"])
+def test_blast_parity(T, n_in, n_out, b, r, dtype, mode):
+    gu = _gu()
+    if mode == "packed" and (dtype != "bf16" or (n_in // b) % 8 or r % 8):
+        pytest.skip("packed factors exist only for the bf16 MFMA path")
+    lay = bi.blast_layer(n_in, n_out, b, r, dtype)
+    X = bi.activations(T, n_in, dtype)
+    Y = gu.to_f64(gu.run_blast(X, lay, gu.B.FORCE_GENERIC if mode == "generic" else 0, packed=(mode == "packed")))
+    Yref = oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64)
+    err = gu.rel_err(Y, Yref)
+    print(f"blast {T}x{n_in}->{n_out} b={b} r={r} {dtype} {mode}: rel err {err:.3e}")
+    assert err <= gu.TOL[dtype]
+
+
+# ---------------------------------------------------------------- dense
+@pytest.mark.parametrize("T,n_in,n_out,dtype", [(200, 320, 200, "bf16"), (200, 320, 200, "f32"),
+                                                (129, 1024, 130, "bf16"), (5, 100, 7, "bf16"), (1, 64, 64, "f32")])
+@pytest.mark.parametrize("generic", [False, True])
+def test_dense_parity(T, n_in, n_out, dtype, generic):
+    gu = _gu()
+    W = bi.dense_weight(n_in, n_out, dtype)
+    X = bi.activations(T, n_in, dtype)
+    Y = gu.empty_out(T, n_out, dtype)
+    gu.B.dense_reference_forward(gu.to_dev(X), gu.to_dev(W), Y, gu.B.FORCE_GENERIC if generic else 0)
+    torch.cuda.synchronize()
+    err = gu.rel_err(gu.to_f64(Y), oracle.dense_forward(X.f64, W.f64))
+    print(f"dense {T}x{n_in}->{n_out} {dtype} generic={generic}: rel err {err:.3e}")
+    assert err <= gu.TOL[dtype]
+
+
+# ---------------------------------------------------------------- edge cases and properties
+def test_zero_tokens_and_status_codes():
+    gu = _gu()
+    B = gu.B
+    lay = bi.monarch_layer(64, 64, 4, 16, "bf16")
+    Rd, Ld = gu.to_dev(lay.R), gu.to_dev(lay.L)
+    X0 = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    Y0 = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    B.monarch_forward(X0, Rd, Ld, Y0, 4, 16)                      # T = 0: ok, nothing launched
+    X = gu.to_dev(bi.activations(4, 64, "bf16"))
+    Y = gu.empty_out(4, 64, "bf16")
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.BlrError) as e:
+        B.monarch_forward(X, Rd, Ld, Y, 4, 16, workspace=small)
+    assert e.value.status == B.ERR_WORKSPACE
+    with pytest.raises(B.BlrError) as e:
+        B.monarch_forward(X, Rd, Ld, Y, 3, 16)                    # 3 does not divide 64
+    assert e.value.status == B.ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.isnan(Y.float()).all()                           # failed calls launched nothing
+
+
+def test_run_to_run_bit_identical():
+    gu = _gu()
+    lay = bi.monarch_layer(512, 768, 4, 256, "bf16")
+    X = bi.activations(300, 512, "bf16")
+    a = gu.run_monarch(X, lay).view(torch.int16).cpu()
+    b = gu.run_monarch(X, lay).view(torch.int16).cpu()
+    assert torch.equal(a, b)
+    bl = bi.blast_layer(768, 768, 16, 96, "bf16")
+    Xb = bi.activations(333, 768, "bf16")
+    a = gu.run_blast(Xb, bl).view(torch.int16).cpu()
+    b = gu.run_blast(Xb, bl, packed=True).view(torch.int16).cpu()
+    assert torch.equal(a, b)                                      # per-call re-layout == offline re-layout
+
+
+def test_linearity_on_gpu():
+    gu = _gu()
+    lay = bi.blast_layer(256, 256, 4, 64, "f32")
+    X1 = bi.activations(33, 256, "f32")
+    X2 = bi.gaussian(99, bi.TID_X, (33, 256), 1.0, "f32")
+    X3 = bi.store(2.0 * X1.f64 - 0.5 * X2.f64, "f32")
+    f = lambda X: gu.to_f64(gu.run_blast(X, lay))
+    np.testing.assert_allclose(f(X3), 2.0 * f(X1) - 0.5 * f(X2), rtol=0, atol=2e-5 * np.abs(f(X1)).max())
