@@ -76,14 +76,22 @@ class GpuLayer:
     def set_x(self, X):
         self.X = X
 
-    def forward(self, extra_flags=0):
+    def call_args(self, extra_flags=0):
         B = self.B
         if self.op == "monarch":
-            B.monarch_forward(self.X, self.R, self.L, self.Y, self.nb, self.r, self.flags | extra_flags, self.ws)
-        elif self.flags & B.BLAST_PACKED:
-            B.blast_forward(self.X, self.U, self.Sp, self.Vp, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
-        else:
-            B.blast_forward(self.X, self.U, self.S, self.V, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
+            return (B.monarch_forward, self.X, self.R, self.L, self.Y, self.nb, self.r, self.flags | extra_flags, self.ws)
+        if self.flags & B.BLAST_PACKED:
+            return (B.blast_forward, self.X, self.U, self.Sp, self.Vp, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
+        return (B.blast_forward, self.X, self.U, self.S, self.V, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
+
+    def forward(self, extra_flags=0):
+        a = self.call_args(extra_flags)
+        a[0](*a[1:])
+
+    def prepared(self, extra_flags=0):
+        """Zero-argument callable that re-issues the C call with pre-marshalled arguments on the
+        stream that is current now."""
+        return self.B.prepared(*self.call_args(extra_flags))
 
     def shape_args(self):
         c = self.cfg
@@ -105,12 +113,43 @@ def time_calls(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def time_graph(make_call, steps, warmup, replays=3):
+    """Mean milliseconds per call with the `steps` calls captured once into a HIP graph and replayed:
+    the host enqueues one graph launch, so the figure is the GPU's own back-to-back rate rather than
+    the speed of the Python launch loop. `make_call()` is evaluated on the capture stream."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call = make_call()
+        for _ in range(max(warmup, 1)):
+            call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        call = make_call()
+        for _ in range(steps):
+            call()
+    g.replay()
+    torch.cuda.synchronize()
+    best = 1e30
+    for _ in range(replays):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) / steps)
+    return best
+
+
 def stage_times(layer, steps, warmup):
     """Per-stage mean launch duration (ms): (first, last), or None if the call is a single kernel."""
     B = layer.B
     try:
-        t1 = time_calls(lambda: layer.forward(B.ONLY_FIRST_STAGE), steps, warmup)
-        t2 = time_calls(lambda: layer.forward(B.ONLY_LAST_STAGE), steps, warmup)
+        t1 = time_graph(lambda: layer.prepared(B.ONLY_FIRST_STAGE), steps, warmup, 1)
+        t2 = time_graph(lambda: layer.prepared(B.ONLY_LAST_STAGE), steps, warmup, 1)
         return t1, t2
     except B.BlrError as e:
         if e.status == B.ERR_UNSUPPORTED:
@@ -184,10 +223,10 @@ def run_sweep(steps, warmup):
         W = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
         for T in cfg["T"]:
             layer = GpuLayer(cfg, T)
-            ms = time_calls(layer.forward, steps, warmup)
+            ms = time_graph(layer.prepared, steps, warmup)
             st = stage_times(layer, steps, warmup)
             Yd = torch.empty_like(layer.Y)
-            ms_dense = time_calls(lambda: B.dense_reference_forward(layer.X, W, Yd), steps, warmup)
+            ms_dense = time_graph(lambda: B.prepared(B.dense_reference_forward, layer.X, W, Yd), steps, warmup)
             sa = layer.shape_args()
             mem, mfma = rf.floors(cfg["op"], T, **sa)
             dmem, dmfma = rf.floors("dense", T, cfg["n_in"], cfg["n_out"])
@@ -218,6 +257,7 @@ def main():
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="report the eager Python launch loop instead of the graph replay")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (token-parallel sharding needs no exchange and is not "
@@ -234,15 +274,20 @@ def main():
     layer = GpuLayer(cfg, T)
     layer.set_x(to_dev(bi.activations(T, cfg["n_in"], cfg["dtype"], scale=cfg["x_scale"])))
 
+    # timed region: exactly `steps` forward calls, inputs resident, synchronised on both sides.
+    # eager = a Python loop of C calls (host-launch-bound for microsecond kernels);
+    # graph = the same `steps` calls captured once in a HIP graph and replayed (the reported value).
     torch.cuda.synchronize()
-    ms = time_calls(layer.forward, args.steps, args.warmup)
+    ms_eager = time_calls(layer.prepared(), args.steps, args.warmup)
+    torch.cuda.synchronize()
+    ms = ms_eager if args.eager else time_graph(layer.prepared, args.steps, args.warmup)
     torch.cuda.synchronize()
     stages = stage_times(layer, args.steps, args.warmup)
     roof = dominant_roofline(layer, ms, stages)
 
     W = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
     Yd = torch.empty_like(layer.Y)
-    ms_dense = time_calls(lambda: B.dense_reference_forward(layer.X, W, Yd), args.steps, args.warmup)
+    ms_dense = time_graph(lambda: B.prepared(B.dense_reference_forward, layer.X, W, Yd), args.steps, args.warmup)
 
     sa = layer.shape_args()
     out = {
@@ -252,6 +297,7 @@ def main():
         "config": {"workload": f"{args.workload}: {cfg['op']} linear {cfg['n_in']}->{cfg['n_out']}, "
                                f"b={sa['b']}, r={sa['r']}, T={T}, {cfg['dtype']} storage / fp32 accumulate",
                    "factors": "packed once before timing" if getattr(layer, "flags", 0) & B.BLAST_PACKED else "canonical"},
+        "launch": "eager loop" if args.eager else "hip graph of the K steps, replayed", "ms_per_step_eager": ms_eager,
         "roofline": roof,
         "dense_same_shape": {"ms_per_step": ms_dense, "tokens_per_s": T / (ms_dense * 1e-3), "speedup_of_blr": ms_dense / ms},
     }

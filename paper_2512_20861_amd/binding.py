@@ -148,6 +148,38 @@ def blast_pack(S, V, n_in, n_out, b, r, stream=None):
     return Sp, Vp
 
 
+def prepared(fn, *args, **kw):
+    """Marshal the arguments of `fn` (one of the *_forward functions of this module) ONCE and return
+    a zero-argument callable that re-issues exactly that C call. For tight launch loops: the
+    per-call cost is one foreign-function call, no tensor or stream look-ups. The tensors must stay
+    alive and the stream is the one current at preparation time."""
+    captured = []
+
+    class _Recorder:
+        def __getattr__(self, name):
+            def rec(*cargs):
+                captured.append((name, cargs))
+                return OK
+            return rec
+
+    global _lib
+    real = lib()
+    _lib = _Recorder()
+    try:
+        fn(*args, **kw)
+    finally:
+        _lib = real
+    (name, cargs), = captured
+    cfn = getattr(real, name)
+    conv = tuple(t(a) if not isinstance(a, t) else a for t, a in zip(cfn.argtypes, cargs))
+
+    def call():
+        st = cfn(*conv)
+        if st != OK:
+            raise BlrError(st, name)
+    return call
+
+
 def dense_reference_forward(X, W, Y, flags=0, stream=None):
     """Y[T][n_out] <- X[T][n_in] W[n_out][n_in]^T."""
     T, n_in = X.shape

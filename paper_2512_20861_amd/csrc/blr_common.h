@@ -3,7 +3,19 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+
 namespace blr {
+
+// compile-time loop: f(std::integral_constant<int, 0>{}) ... f(std::integral_constant<int, N-1>{})
+template <class F, int... I>
+__host__ __device__ inline void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__host__ __device__ inline void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 typedef unsigned short bf16_t;  // bfloat16 bit pattern
 
@@ -19,6 +31,11 @@ __host__ __device__ inline bf16_t float_to_bf16(float f) {
     uint32_t u = c.u;
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (bf16_t)(u >> 16);
+}
+
+// value select (a ternary on two uint4 lvalues would select an address and force them into memory)
+__device__ inline uint4 keep_if(bool ok, uint4 v) {
+    return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
 }
 
 // A batched "NT" product with index maps, general enough for every contraction of the path:

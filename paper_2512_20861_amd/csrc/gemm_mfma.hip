@@ -30,9 +30,10 @@ struct TileCfg {
     static_assert(NA >= 1 && NB >= 1 && MI >= 1 && NI >= 1, "tile too small");
 };
 
-template <int BM, int BN, int BK>
+template <int BM, int BN, int BK, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d, int tiles_m) {
     using C = TileCfg<BM, BN, BK>;
+    static_assert(D % 2 == 0, "the ring slot parity must equal the LDS stage parity");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -54,30 +55,42 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d, int tiles_m)
     for (int i = 0; i < C::NA; ++i) {
         int64_t m = m0 + lrow + i * C::RPP;
         if (m > d.M - 1) m = d.M - 1;               // rows past the end re-read the last row; never stored
-        ap[i] = Ag + m * d.a_rs + lchunk * 8;
+        ap[i] = Ag + m * d.a_rs;
     }
 #pragma unroll
     for (int i = 0; i < C::NB; ++i) {
         int n = n0 + lrow + i * C::RPP;
         if (n > d.N - 1) n = d.N - 1;
         const int64_t nr = d.b_div ? (int64_t)(n % d.b_div) * d.b_mul + n / d.b_div : n;
-        bp[i] = Bg + nr * d.b_rs + lchunk * 8;
+        bp[i] = Bg + nr * d.b_rs;
     }
 
-    uint4 ra[C::NA], rb[C::NB];
-    auto gload = [&](int k0) {
-        const bool ok = (k0 + lchunk * 8) < d.K;    // K is a multiple of 8: a chunk is all valid or all past the end
+    // Register ring: the global loads of steps s+1 .. s+D are in flight while step s is computed from
+    // LDS, so HBM/L2 latency is covered by D steps of MFMA work. Slots are indexed statically (the
+    // main loop is unrolled by D) and every load is unconditional (addresses are clamped, chunks past
+    // K are zeroed when they are written to LDS), so each wait counts only the loads older than the
+    // slot it needs instead of draining the queue.
+    const int nk = (d.K + BK - 1) / BK;
+    uint4 ra[D][C::NA], rb[D][C::NB];
+    auto gload = [&](auto SLOT, int kt) {
+        constexpr int slot = decltype(SLOT)::value;
+        if (kt > nk - 1) kt = nk - 1;               // steps past the end repeat the last one; never consumed
+        int k = kt * BK + lchunk * 8;
+        if (k > d.K - 8) k = d.K - 8;               // K is a multiple of 8
 #pragma unroll
-        for (int i = 0; i < C::NA; ++i) ra[i] = ok ? *(const uint4*)(ap[i] + k0) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < C::NA; ++i) ra[slot][i] = *(const uint4*)(ap[i] + k);
 #pragma unroll
-        for (int i = 0; i < C::NB; ++i) rb[i] = ok ? *(const uint4*)(bp[i] + k0) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < C::NB; ++i) rb[slot][i] = *(const uint4*)(bp[i] + k);
     };
-    auto sstore = [&](int stage) {
+    auto sstore = [&](auto SLOT, int kt) {
+        constexpr int slot = decltype(SLOT)::value;
+        constexpr int stage = slot & 1;             // D is even: slot parity == step parity
         unsigned char* base = smem + stage * C::STAGE;
+        const bool ok = (kt * BK + lchunk * 8) < d.K;
 #pragma unroll
-        for (int i = 0; i < C::NA; ++i) *(uint4*)(base + (lrow + i * C::RPP) * C::STR + lchunk * 16) = ra[i];
+        for (int i = 0; i < C::NA; ++i) *(uint4*)(base + (lrow + i * C::RPP) * C::STR + lchunk * 16) = keep_if(ok, ra[slot][i]);
 #pragma unroll
-        for (int i = 0; i < C::NB; ++i) *(uint4*)(base + C::A_BYTES + (lrow + i * C::RPP) * C::STR + lchunk * 16) = rb[i];
+        for (int i = 0; i < C::NB; ++i) *(uint4*)(base + C::A_BYTES + (lrow + i * C::RPP) * C::STR + lchunk * 16) = keep_if(ok, rb[slot][i]);
     };
 
     f32x16 acc[C::MI][C::NI];
@@ -88,15 +101,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d, int tiles_m)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int nk = (d.K + BK - 1) / BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
     const int frag_off = (lane & 31) * C::STR + (lane >> 5) * 16;
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload((kt + 1) * BK);
-        const unsigned char* As = smem + (kt & 1) * C::STAGE + (wm * C::WTM) * C::STR + frag_off;
-        const unsigned char* Bs = smem + (kt & 1) * C::STAGE + C::A_BYTES + (wn * C::WTN) * C::STR + frag_off;
+    auto step = [&](auto U, int kt) {               // u = kt % D, a compile-time constant
+        constexpr int u = decltype(U)::value;
+        const unsigned char* As = smem + (u & 1) * C::STAGE + (wm * C::WTM) * C::STR + frag_off;
+        const unsigned char* Bs = smem + (u & 1) * C::STAGE + C::A_BYTES + (wn * C::WTN) * C::STR + frag_off;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 af[C::MI], bfr[C::NI];
@@ -110,9 +119,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d, int tiles_m)
                 for (int j = 0; j < C::NI; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) sstore((kt + 1) & 1);
+        sstore(std::integral_constant<int, (u + 1) % D>{}, kt + 1);   // past the last step this writes the unused stage
+        gload(std::integral_constant<int, (u + 1) % D>{}, kt + 1 + D);
         __syncthreads();
-    }
+    };
+
+    static_for<D>([&](auto U) { gload(U, decltype(U)::value); });
+    sstore(std::integral_constant<int, 0>{}, 0);
+    gload(std::integral_constant<int, 0>{}, D);
+    __syncthreads();
+    int kt0 = 0;
+    for (; kt0 + D <= nk; kt0 += D) static_for<D>([&](auto U) { step(U, kt0 + decltype(U)::value); });
+    static_for<D - 1>([&](auto U) { if (kt0 + decltype(U)::value < nk) step(U, kt0 + decltype(U)::value); });
 
     // epilogue: accumulator element e of a 32x32 tile is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
     bf16_t* Cp = (bf16_t*)d.C;
@@ -132,11 +150,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d, int tiles_m)
     }
 }
 
-template <int BM, int BN, int BK>
+template <int BM, int BN, int BK, int D>
 hipError_t launch_cfg(const GemmDesc& d, hipStream_t s) {
     using C = TileCfg<BM, BN, BK>;
     static bool attr_set = false;   // benign if set twice
-    auto kern = gemm_mfma_kernel<BM, BN, BK>;
+    auto kern = gemm_mfma_kernel<BM, BN, BK, D>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
@@ -161,10 +179,10 @@ bool mfma_gemm_supported(const GemmDesc& d) {
 
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     const bool k64 = (d.K % 64 == 0);
-    if (d.M > 64 && d.N > 64) return k64 ? launch_cfg<128, 128, 64>(d, s) : launch_cfg<128, 128, 32>(d, s);
-    if (d.M > 64)             return k64 ? launch_cfg<128, 64, 64>(d, s) : launch_cfg<128, 64, 32>(d, s);
-    if (d.N > 64)             return k64 ? launch_cfg<64, 128, 64>(d, s) : launch_cfg<64, 128, 32>(d, s);
-    return k64 ? launch_cfg<64, 64, 64>(d, s) : launch_cfg<64, 64, 32>(d, s);
+    if (d.M > 64 && d.N > 64) return k64 ? launch_cfg<128, 128, 64, 2>(d, s) : launch_cfg<128, 128, 32, 4>(d, s);
+    if (d.M > 64)             return k64 ? launch_cfg<128, 64, 64, 2>(d, s) : launch_cfg<128, 64, 32, 4>(d, s);
+    if (d.N > 64)             return k64 ? launch_cfg<64, 128, 64, 2>(d, s) : launch_cfg<64, 128, 32, 4>(d, s);
+    return k64 ? launch_cfg<64, 64, 64, 4>(d, s) : launch_cfg<64, 64, 32, 4>(d, s);
 }
 
 }  // namespace blr
