@@ -26,6 +26,7 @@ EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forw
            "blr_blast_packed_s_bytes", "blr_blast_pack", "blr_dense_reference_forward")
 
 _lib = None
+_last_workspace = None     # the workspace the latest forward call ran with (kept alive for prepared())
 
 
 class BlrError(RuntimeError):
@@ -107,6 +108,8 @@ def monarch_forward(X, R, L, Y, nblocks, r, flags=0, workspace=None, stream=None
     if workspace is None:
         workspace = torch.empty(max(monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt), 16),
                                 dtype=torch.uint8, device=X.device)
+    global _last_workspace
+    _last_workspace = workspace
     _check(lib().blr_monarch_forward(_ptr(X), _ptr(R), _ptr(L), _ptr(Y), T, n_in, n_out, nblocks, r, dt, flags,
                                      _ptr(workspace), workspace.numel(), _stream(stream)), "blr_monarch_forward")
     return Y
@@ -125,6 +128,8 @@ def blast_forward(X, U, S, V, Y, b, r, flags=0, workspace=None, stream=None):
     if workspace is None:
         workspace = torch.empty(max(blast_workspace_bytes(T, n_in, n_out, b, r, dt, flags), 16),
                                 dtype=torch.uint8, device=X.device)
+    global _last_workspace
+    _last_workspace = workspace
     _check(lib().blr_blast_forward(_ptr(X), _ptr(U), _ptr(S), _ptr(V), _ptr(Y), T, n_in, n_out, b, r, dt, flags,
                                    _ptr(workspace), workspace.numel(), _stream(stream)), "blr_blast_forward")
     return Y
@@ -152,18 +157,22 @@ def prepared(fn, *args, **kw):
     """Marshal the arguments of `fn` (one of the *_forward functions of this module) ONCE and return
     a zero-argument callable that re-issues exactly that C call. For tight launch loops: the
     per-call cost is one foreign-function call, no tensor or stream look-ups. The tensors must stay
-    alive and the stream is the one current at preparation time."""
+    alive (pass an explicit workspace, or keep the returned callable's `.keepalive`) and the stream
+    is the one current at preparation time."""
     captured = []
+
+    real = lib()
 
     class _Recorder:
         def __getattr__(self, name):
+            if not name.endswith("_forward"):
+                return getattr(real, name)      # size queries run for real
             def rec(*cargs):
                 captured.append((name, cargs))
                 return OK
             return rec
 
     global _lib
-    real = lib()
     _lib = _Recorder()
     try:
         fn(*args, **kw)
@@ -177,6 +186,7 @@ def prepared(fn, *args, **kw):
         st = cfn(*conv)
         if st != OK:
             raise BlrError(st, name)
+    call.keepalive = (args, kw, _last_workspace)
     return call
 
 

@@ -1,0 +1,115 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes workspaces as documented, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_20861_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "blr.h")
+
+if not os.path.exists(B.LIB_PATH):
+    from paper_2512_20861_amd import build as _build
+    _build.build_library()
+
+FAKE = 0x10000          # a non-null, 16-byte aligned address that is never dereferenced on these paths
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(blr_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_symbols()
+    assert set(B.EXPORTS) == set(names)
+    lib = B.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    assert B.status_string(B.OK) == "ok"
+    for s in (B.ERR_INVALID_ARG, B.ERR_UNSUPPORTED, B.ERR_WORKSPACE, B.ERR_LAUNCH):
+        assert B.status_string(s) not in ("ok", "unknown status")
+    assert B.status_string(77) == "unknown status"
+
+
+def test_workspace_sizes():
+    # Monarch: Z'[T][nblocks][r] in the storage type, rounded up to 256 bytes
+    assert B.monarch_workspace_bytes(8, 256, 256, 4, 64, B.F32) == 8 * 4 * 64 * 4
+    assert B.monarch_workspace_bytes(8192, 4096, 4096, 4, 1024, B.BF16) == 8192 * 4096 * 2
+    assert B.monarch_workspace_bytes(8, 250, 256, 4, 64, B.F32) == 0          # invalid shape -> 0
+    # BLAST: the whole-layer kernel needs no intermediate; packed factors add nothing
+    assert B.blast_workspace_bytes(6304, 768, 768, 16, 96, B.BF16, B.BLAST_PACKED) == 0
+    unpacked = B.blast_workspace_bytes(6304, 768, 768, 16, 96, B.BF16, 0)
+    assert unpacked == B.blast_packed_v_bytes(768, 16, 96) + B.blast_packed_s_bytes(16, 96)
+    # large ranks keep A[T][b][r] in the workspace
+    assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 512 * 16 * 640 * 2
+    # portable path keeps Z and A
+    assert B.blast_workspace_bytes(50, 36, 30, 3, 10, B.F32, 0) == 2 * ((50 * 3 * 10 * 4 + 255) // 256 * 256)
+    assert B.blast_packed_s_bytes(16, 96) == 96 * 256 * 2 and B.blast_packed_s_bytes(17, 96) == 0
+
+
+def _monarch(T=4, n_in=64, n_out=64, nb=4, r=16, dt=B.BF16, flags=0, X=FAKE, R=FAKE, L=FAKE, Y=FAKE, ws=FAKE, wsb=1 << 20):
+    return B.lib().blr_monarch_forward(X, R, L, Y, T, n_in, n_out, nb, r, dt, flags, ws, wsb, None)
+
+
+def _blast(T=4, n_in=64, n_out=64, b=4, r=16, dt=B.BF16, flags=0, X=FAKE, U=FAKE, S=FAKE, V=FAKE, Y=FAKE, ws=FAKE, wsb=1 << 20):
+    return B.lib().blr_blast_forward(X, U, S, V, Y, T, n_in, n_out, b, r, dt, flags, ws, wsb, None)
+
+
+def test_monarch_argument_checks():
+    assert _monarch(T=0) == B.OK                                   # empty batch: nothing launched
+    assert _monarch(T=0, X=None, Y=None) == B.OK
+    assert _monarch(T=-1) == B.ERR_INVALID_ARG
+    assert _monarch(R=None) == B.ERR_INVALID_ARG
+    assert _monarch(X=None) == B.ERR_INVALID_ARG
+    assert _monarch(n_in=66) == B.ERR_INVALID_ARG                  # nblocks does not divide n_in
+    assert _monarch(n_out=62) == B.ERR_INVALID_ARG
+    assert _monarch(r=18) == B.ERR_INVALID_ARG                     # nblocks does not divide r
+    assert _monarch(nb=0) == B.ERR_INVALID_ARG
+    assert _monarch(dt=7) == B.ERR_INVALID_ARG
+    assert _monarch(flags=0x8000) == B.ERR_INVALID_ARG
+    assert _monarch(flags=B.ONLY_FIRST_STAGE | B.ONLY_LAST_STAGE) == B.ERR_INVALID_ARG
+    assert _monarch(X=FAKE + 2) == B.ERR_INVALID_ARG               # misaligned pointer
+    assert _monarch(ws=None) == B.ERR_WORKSPACE
+    assert _monarch(wsb=16) == B.ERR_WORKSPACE
+
+
+def test_blast_argument_checks():
+    assert _blast(T=0) == B.OK
+    assert _blast(T=-3) == B.ERR_INVALID_ARG
+    assert _blast(S=None) == B.ERR_INVALID_ARG
+    assert _blast(Y=None) == B.ERR_INVALID_ARG
+    assert _blast(n_in=66) == B.ERR_INVALID_ARG
+    assert _blast(n_out=30) == B.ERR_INVALID_ARG
+    assert _blast(b=0) == B.ERR_INVALID_ARG
+    assert _blast(r=0) == B.ERR_INVALID_ARG
+    assert _blast(flags=0x1) == B.ERR_INVALID_ARG                  # a Monarch flag
+    assert _blast(dt=B.F32, flags=B.BLAST_PACKED) == B.ERR_INVALID_ARG
+    assert _blast(flags=B.BLAST_PACKED | B.FORCE_GENERIC) == B.ERR_INVALID_ARG
+    assert _blast(T=64, n_in=4096, n_out=4096, b=16, r=640, wsb=1024) == B.ERR_WORKSPACE
+    assert _blast(T=64, n_in=4096, n_out=4096, b=16, r=640, ws=None, wsb=0) == B.ERR_WORKSPACE
+
+
+def test_dense_and_pack_argument_checks():
+    lib = B.lib()
+    assert lib.blr_dense_reference_forward(FAKE, FAKE, FAKE, 0, 8, 8, B.BF16, 0, None) == B.OK
+    assert lib.blr_dense_reference_forward(FAKE, None, FAKE, 4, 8, 8, B.BF16, 0, None) == B.ERR_INVALID_ARG
+    assert lib.blr_dense_reference_forward(FAKE, FAKE, FAKE, 4, 0, 8, B.BF16, 0, None) == B.ERR_INVALID_ARG
+    assert lib.blr_dense_reference_forward(FAKE, FAKE, FAKE, 4, 8, 8, B.BF16, 0x2, None) == B.ERR_INVALID_ARG
+    assert lib.blr_blast_pack(FAKE, FAKE, FAKE, FAKE, 64, 64, 4, 16, B.F32, None) == B.ERR_INVALID_ARG
+    assert lib.blr_blast_pack(FAKE, FAKE, FAKE, FAKE, 64, 64, 32, 16, B.BF16, None) == B.ERR_INVALID_ARG
+    assert lib.blr_blast_pack(None, FAKE, FAKE, FAKE, 64, 64, 4, 16, B.BF16, None) == B.ERR_INVALID_ARG
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        B.lib()
