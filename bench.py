@@ -68,7 +68,7 @@ class GpuLayer:
             self.b, self.r = cfg["b"], cfg["r"]
             self.flags = 0
             if self.dtype == "bf16" and (self.n_in // self.b) % 8 == 0 and self.r % 8 == 0 and self.b <= 16:
-                self.Sp, self.Vp = B.blast_pack(self.S, self.V, self.n_in, self.n_out, self.b, self.r)
+                self.packed = B.blast_pack(self.U, self.S, self.V, self.n_in, self.n_out, self.b, self.r)
                 self.flags = B.BLAST_PACKED
             self.ws = torch.empty(max(B.blast_workspace_bytes(T, self.n_in, self.n_out, self.b, self.r, dt, self.flags), 16),
                                   dtype=torch.uint8, device="cuda")
@@ -81,7 +81,7 @@ class GpuLayer:
         if self.op == "monarch":
             return (B.monarch_forward, self.X, self.R, self.L, self.Y, self.nb, self.r, self.flags | extra_flags, self.ws)
         if self.flags & B.BLAST_PACKED:
-            return (B.blast_forward, self.X, self.U, self.Sp, self.Vp, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
+            return (B.blast_forward, self.X, self.U, None, self.packed, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
         return (B.blast_forward, self.X, self.U, self.S, self.V, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
 
     def forward(self, extra_flags=0):

@@ -49,8 +49,8 @@ typedef void* blr_stream;      /* a hipStream_t */
  * are permuted offline. */
 #define BLR_MONARCH_OUT_INTERLEAVED 0u
 #define BLR_MONARCH_OUT_BLOCKED     1u
-/* flag of blr_blast_forward: S and V are the re-laid-out tensors written by blr_blast_pack (the
- * one-time offline weight re-layout of paper Section 4, optimisations 1 and 5), not the canonical ones. */
+/* flag of blr_blast_forward: the `V` argument is the buffer written by blr_blast_pack (the one-time
+ * offline weight re-layout of paper Section 4, optimisations 1 and 5) and `S` is ignored. */
 #define BLR_BLAST_PACKED            2u
 /* flag of every forward: run the portable scalar-ALU kernels even where an MFMA kernel exists
  * (used by the tests to cross-check the two GPU paths). */
@@ -85,9 +85,10 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
  *   A[t][i][rho]  = sum_j S[i][j][rho] * Z[t][j][rho]
  *   Y[t][i*p+a]   = sum_rho A[t][i][rho] * U[i][a][rho]
  * X[T][n_in]; U[b][p][r]; S[b][b][r] indexed [output block i][input block j]; V[b][q][r]; Y[T][n_out].
- * b must divide n_in and n_out. With BLR_BLAST_PACKED, `S` and `V` point to the tensors produced
- * by blr_blast_pack (bf16 only). workspace: at least blr_blast_workspace_bytes(...) bytes with the
- * same flags (holds A; without BLR_BLAST_PACKED also the per-call re-layout of S and V).
+ * b must divide n_in and n_out. With BLR_BLAST_PACKED, `V` points to the buffer produced by
+ * blr_blast_pack for the same (n_in, n_out, b, r), `S` is ignored (may be NULL), `U` is still the
+ * canonical tensor (bf16 only). workspace: at least blr_blast_workspace_bytes(...) bytes with the
+ * same flags (holds A where a kernel needs it; without BLR_BLAST_PACKED also the per-call re-layout).
  */
 size_t     blr_blast_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags);
 blr_status blr_blast_forward(const void* X, const void* U, const void* S, const void* V, void* Y,
@@ -97,14 +98,17 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
 
 /*
  * One-time re-layout of the static BLAST factors (paper Section 4: weights are static, so their
- * layout is changed once before inference). bf16 only.
- *   V_packed[j][rho][c] = V[j][c][rho]                      (contraction index contiguous)
- *   S_packed[rho][i][j] = S[i][j][rho], i and j padded with zeros to 16   (one 16x16 tile per rho)
- * Sizes in bytes from blr_blast_packed_v_bytes / blr_blast_packed_s_bytes. b <= 16 required.
+ * layout is changed once before inference). bf16 only, b <= 16. `packed` is an opaque buffer of
+ * blr_blast_packed_bytes(...) bytes that holds
+ *   S as one zero-padded 16x16 coupling tile per rank index, Sp[rho][i][j] = S[i][j][rho];
+ *   V with the contraction index contiguous, Vt[j][rho][c] = V[j][c][rho]; or, for layers the
+ *   single-kernel path serves (r <= 128, n_out/b <= 64), V and U in the register order of the
+ *   matrix-core instructions that consume them, so that one load instruction of a wavefront reads
+ *   one contiguous kilobyte.
+ * The canonical tensors are not modified and are not needed afterwards, except U.
  */
-size_t     blr_blast_packed_v_bytes(int n_in, int b, int r, blr_dtype dt);
-size_t     blr_blast_packed_s_bytes(int b, int r, blr_dtype dt);
-blr_status blr_blast_pack(const void* S, const void* V, void* S_packed, void* V_packed,
+size_t     blr_blast_packed_bytes(int n_in, int n_out, int b, int r, blr_dtype dt);
+blr_status blr_blast_pack(const void* U, const void* S, const void* V, void* packed,
                           int n_in, int n_out, int b, int r, blr_dtype dt, blr_stream stream);
 
 /*

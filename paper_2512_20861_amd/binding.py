@@ -22,8 +22,8 @@ MONARCH_OUT_INTERLEAVED, MONARCH_OUT_BLOCKED, BLAST_PACKED, FORCE_GENERIC = 0, 1
 ONLY_FIRST_STAGE, ONLY_LAST_STAGE = 0x200, 0x400
 
 EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forward",
-           "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_v_bytes",
-           "blr_blast_packed_s_bytes", "blr_blast_pack", "blr_dense_reference_forward")
+           "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_bytes",
+           "blr_blast_pack", "blr_dense_reference_forward")
 
 _lib = None
 _last_workspace = None     # the workspace the latest forward call ran with (kept alive for prepared())
@@ -53,10 +53,8 @@ def lib() -> ctypes.CDLL:
         L.blr_blast_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.blr_blast_forward.restype = ci
         L.blr_blast_forward.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, cu, vp, sz, vp]
-        L.blr_blast_packed_v_bytes.restype = sz
-        L.blr_blast_packed_v_bytes.argtypes = [ci, ci, ci, ci]
-        L.blr_blast_packed_s_bytes.restype = sz
-        L.blr_blast_packed_s_bytes.argtypes = [ci, ci, ci]
+        L.blr_blast_packed_bytes.restype = sz
+        L.blr_blast_packed_bytes.argtypes = [ci, ci, ci, ci, ci]
         L.blr_blast_pack.restype = ci
         L.blr_blast_pack.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
         L.blr_dense_reference_forward.restype = ci
@@ -121,7 +119,7 @@ def blast_workspace_bytes(T, n_in, n_out, b, r, dt, flags=0) -> int:
 
 def blast_forward(X, U, S, V, Y, b, r, flags=0, workspace=None, stream=None):
     """Y[T][n_out] <- BLAST(X[T][n_in]; U[b][n_out/b][r], S[b][b][r], V[b][n_in/b][r]);
-    with BLAST_PACKED in flags, S and V are the outputs of blast_pack."""
+    with BLAST_PACKED in flags, V is the buffer returned by blast_pack and S is None."""
     T, n_in = X.shape
     n_out = Y.shape[1]
     dt = _dt(X)
@@ -135,22 +133,18 @@ def blast_forward(X, U, S, V, Y, b, r, flags=0, workspace=None, stream=None):
     return Y
 
 
-def blast_packed_v_bytes(n_in, b, r, dt=BF16) -> int:
-    return lib().blr_blast_packed_v_bytes(n_in, b, r, dt)
+def blast_packed_bytes(n_in, n_out, b, r, dt=BF16) -> int:
+    return lib().blr_blast_packed_bytes(n_in, n_out, b, r, dt)
 
 
-def blast_packed_s_bytes(b, r, dt=BF16) -> int:
-    return lib().blr_blast_packed_s_bytes(b, r, dt)
-
-
-def blast_pack(S, V, n_in, n_out, b, r, stream=None):
-    """One-time re-layout of the BLAST factors; returns (S_packed, V_packed) as byte buffers."""
+def blast_pack(U, S, V, n_in, n_out, b, r, stream=None):
+    """One-time re-layout of the BLAST factors; returns the opaque packed buffer to pass as `V`
+    (with `S=None`) to blast_forward together with the BLAST_PACKED flag."""
     dt = _dt(V)
-    Sp = torch.empty(max(blast_packed_s_bytes(b, r, dt), 16), dtype=torch.uint8, device=V.device)
-    Vp = torch.empty(max(blast_packed_v_bytes(n_in, b, r, dt), 16), dtype=torch.uint8, device=V.device)
-    _check(lib().blr_blast_pack(_ptr(S), _ptr(V), _ptr(Sp), _ptr(Vp), n_in, n_out, b, r, dt, _stream(stream)),
+    packed = torch.empty(max(blast_packed_bytes(n_in, n_out, b, r, dt), 16), dtype=torch.uint8, device=V.device)
+    _check(lib().blr_blast_pack(_ptr(U), _ptr(S), _ptr(V), _ptr(packed), n_in, n_out, b, r, dt, _stream(stream)),
            "blr_blast_pack")
-    return Sp, Vp
+    return packed
 
 
 def prepared(fn, *args, **kw):

@@ -28,9 +28,7 @@ static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 static_assert(D % 2 == 0, "ring slot parity must equal LDS stage parity");
 static_assert(ZS_BYTES % 16 == 0, "Zs is cleared with 16-byte stores");
 
-__device__ inline uint32_t pack2(float lo, float hi) {
-    return (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
-}
+__device__ inline uint32_t pack2(float lo, float hi) { return pack2_bf16(lo, hi); }
 
 // workgroup id -> logical tile id such that each XCD (workgroups are dealt round-robin over 8 XCDs)
 // works on a contiguous range of logical ids, i.e. shares its X tiles in its own L2
@@ -195,229 +193,214 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // Whole BLAST layer in one kernel, for layers whose coupled intermediate fits on chip:
 // a workgroup (8 wavefronts) owns FT = 32 tokens and ALL rank indices and all blocks.
-//   phase 1  Z_j = X_j V_j for every j (wavefronts split j), operands straight from global memory
-//            into MFMA fragments (each element is used by exactly one wavefront), result as bf16
-//            into LDS, Zs[rho][t][j];
+//   phase 0  the X tile (32 rows, contiguous) goes to LDS with fully coalesced 16-byte loads;
+//   phase 1  Z_j = X_j V_j for every j (wavefronts split j) on v_mfma_f32_32x32x16_bf16; the V
+//            fragments come straight from global memory in fragment order (Vf: one load instruction
+//            of a wavefront reads one contiguous KiB, i.e. 8 cache lines instead of ~24), each is
+//            used by exactly one wavefront; result as bf16 into LDS, Zs[rho][t][j];
 //   phase 2  per group of 8 rank indices: A[t][i] = sum_j Z[t][j] S[i][j] on v_mfma_f32_16x16x16_bf16,
 //            written back IN PLACE over the group's own Z rows as As[i][t][8 rho] (the group is read
 //            completely before it is overwritten, and only one wavefront touches it);
 //   phase 3  Y_i = A_i U_i^T (wavefronts split i) on v_mfma_f32_16x16x32_bf16, A fragments from LDS,
-//            U fragments from global memory, result staged in LDS and written to Y with 16-byte stores.
-// Neither Z nor A ever leaves the chip: HBM traffic is X, the factors and Y.
+//            U fragments from global memory in fragment order (Uf), result staged in LDS (over the
+//            dead X tile) and written to Y with 16-byte coalesced stores.
+// Neither Z nor A ever leaves the chip: HBM traffic is X, the factors and Y. The factor fragments
+// of the next phase are fetched while the current one runs.
 // ---------------------------------------------------------------------------------------------
 constexpr int FT = 32;                          // tokens per workgroup
 constexpr int FZSTR = FT * 32 + 8;              // bytes of one rho row of Zs
 constexpr int FCHUNK = 8 * FZSTR;               // 8 rho rows; also holds As[16 i][32 t][8 rho] (8192 B)
 constexpr int FWAVES = 8;
+constexpr int FTHREADS = 64 * FWAVES;
 static_assert(16 * FT * 16 <= FCHUNK, "in-place A must fit in the chunk it replaces");
 
-template <int NT, int KG>                       // r <= 32*NT rank indices; KG k-steps of 16 fetched per round
-__global__ __launch_bounds__(64 * FWAVES) __attribute__((amdgpu_waves_per_eu(1, 2)))
-void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ U, const bf16_t* __restrict__ Sp,
-                       const bf16_t* __restrict__ Vt, bf16_t* __restrict__ Y,
+// r <= 32*NT rank indices; KG k-steps of 16 fetched per round; NPT = (n_out/b)/16 output tiles per block.
+// Every global load is unconditional (indices are clamped, work that does not exist is computed on
+// repeated data and not written) so that each wait counts exactly the loads older than the data it needs.
+template <int NT, int KG, int NPT>
+__global__ __launch_bounds__(FTHREADS) __attribute__((amdgpu_waves_per_eu(1, 2)))
+void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Sp, const bf16_t* __restrict__ Vf,
+                       const bf16_t* __restrict__ Uf, bf16_t* __restrict__ Y,
                        int64_t T, int n_in, int n_out, int b, int r) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int nchunks = r >> 3;                                     // r is a multiple of 8
     unsigned char* Zs = smem;
-    unsigned char* Ys = smem + NT * 4 * FCHUNK;                      // [FT][n_out] bf16, row stride ystr
-    const int ystr = n_out * 2 + 16;
+    unsigned char* XY = smem + NT * 4 * FCHUNK;                      // X tile [FT][n_in], later Y tile [FT][n_out]
+    const int xstr = n_in * 2 + 16, ystr = n_out * 2 + 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t t0 = (int64_t)blockIdx.x * FT;
     const int q = n_in / b, p = n_out / b;
-
-    if (b < 16) {                                                   // unused j slots must read as zero
-        for (int i = tid * 16; i < NT * 4 * FCHUNK; i += 64 * FWAVES * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
-        __syncthreads();
-    }
-
-    // Every global load of a phase is issued before the first dependent MFMA (static register arrays,
-    // uniform guards), and the factor fragments of the next phase are fetched while the current one
-    // runs, so a wavefront pays one memory latency per phase instead of one per k-step.
+    const int nks = (q + 15) >> 4;
     const int ci = lane & 15, cg = lane >> 4;
+    const int l32 = lane & 31, kg = lane >> 5;
+    // this wavefront's input blocks (phase 1), rank groups (phase 2) and output blocks (phase 3)
+    const int jw[2] = {wave < b ? wave : b - 1, wave + FWAVES < b ? wave + FWAVES : b - 1};
+    const int cw[2] = {wave < nchunks ? wave : nchunks - 1, wave + FWAVES < nchunks ? wave + FWAVES : nchunks - 1};
 
-    // ---- phase 1: this wavefront's input blocks j = wave, wave + 8; the fragments of the second
-    // block are in flight while the first is multiplied
-    {
-        const int l32 = lane & 31, kg = lane >> 5;
-        int64_t tx = t0 + l32;
-        if (tx > T - 1) tx = T - 1;
-        const bf16_t* xrow = X + tx * n_in;
-        const int nks = (q + 15) >> 4;
-        uint4 araw[2][KG], braw[2][KG][NT];
-        auto load_j = [&](auto JJ, int ks0) {
-            constexpr int jj = decltype(JJ)::value;
-            const int j = wave + jj * FWAVES;
-            if (j < b) {
-                const bf16_t* vj = Vt + (int64_t)j * r * q;
+    // V fragments (first round of k-steps)
+    uint4 braw[2][KG][NT];
+    auto load_vf = [&](int ks0) {
 #pragma unroll
-                for (int u = 0; u < KG; ++u) {
-                    if (ks0 + u < nks) {
-                        int k = (ks0 + u) * 16 + kg * 8;
-                        if (k > q - 8) k = q - 8;
-                        araw[jj][u] = *(const uint4*)(xrow + j * q + k);
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            int rho = nt * 32 + l32;
-                            if (rho > r - 1) rho = r - 1;
-                            braw[jj][u][nt] = *(const uint4*)(vj + (int64_t)rho * q + k);
-                        }
-                    }
-                }
-            }
-        };
-        f32x16 zacc[NT];
-        auto mul_j = [&](auto JJ, int ks0) {
-            constexpr int jj = decltype(JJ)::value;
+        for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
             for (int u = 0; u < KG; ++u) {
-                if (ks0 + u < nks) {
-                    const bool ok = ((ks0 + u) * 16 + kg * 8) < q;
-                    const uint4 a = keep_if(ok, araw[jj][u]);
+                int ks = ks0 + u;
+                if (ks > nks - 1) ks = nks - 1;
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        zacc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&a, *(const bf16x8*)&braw[jj][u][nt],
-                                                                          zacc[nt], 0, 0, 0);
-                }
+                for (int nt = 0; nt < NT; ++nt)
+                    braw[jj][u][nt] = *(const uint4*)(Vf + (((int64_t)(jw[jj] * NT + nt) * nks + ks) * 64 + lane) * 8);
             }
-        };
-        auto zero_acc = [&]() {
+    };
+    load_vf(0);
+
+    // ---- phase 0: X tile -> LDS with coalesced 16-byte loads (rows past T repeat the last row; the
+    // 16 pad bytes of a row are zeroed because the last k-step of the last block may read them
+    // against zero V fragments)
+    {
+        const int cpr = n_in >> 3;                                   // 16-byte chunks per row
+        const int total = FT * cpr;
+        for (int base = 0; base < total; base += FTHREADS * 4) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int id = base + u * FTHREADS + tid;
+                if (id > total - 1) id = total - 1;
+                const int row = id / cpr, cc = id - row * cpr;
+                int64_t tx = t0 + row;
+                if (tx > T - 1) tx = T - 1;
+                v[u] = *(const uint4*)(X + tx * n_in + cc * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int id = base + u * FTHREADS + tid;
+                if (id > total - 1) id = total - 1;
+                const int row = id / cpr, cc = id - row * cpr;
+                *(uint4*)(XY + row * xstr + cc * 16) = v[u];
+            }
+        }
+        if (tid < FT) *(uint4*)(XY + tid * xstr + n_in * 2) = make_uint4(0, 0, 0, 0);
+        if (b < 16)                                                 // unused j slots must read as zero
+            for (int i = tid * 16; i < NT * 4 * FCHUNK; i += FTHREADS * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+
+    // S tiles of this wavefront's rank groups: in flight during phase 1
+    s16x4 sfr[2][8];
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int ri = 0; ri < 8; ++ri)
+            sfr[cc][ri] = *(const s16x4*)(Sp + (int64_t)(cw[cc] * 8 + ri) * 256 + ci * 16 + cg * 4);
+
+    // ---- phase 1: both blocks of this wavefront, then one 4-byte LDS write per (token, rank index)
+    // holding the pair (slots 2*wave, 2*wave+1 of the permuted block order j' = (j%8)*2 + j/8, which
+    // the packed S tiles follow)
+    uint4 ufr[2][NPT][NT];
+    auto load_u = [&](auto II) {
+        constexpr int ii = decltype(II)::value;
+        const int i = wave + ii * FWAVES < b ? wave + ii * FWAVES : b - 1;
+#pragma unroll
+        for (int nt = 0; nt < NPT; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < NT; ++ks)
+                ufr[ii][nt][ks] = *(const uint4*)(Uf + (((int64_t)(i * NPT + nt) * NT + ks) * 64 + lane) * 8);
+    };
+    {
+        f32x16 zacc[2][NT];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) zacc[nt][e] = 0.f;
+                for (int e = 0; e < 16; ++e) zacc[jj][nt][e] = 0.f;
+        auto mul = [&](int ks0) {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int u = 0; u < KG; ++u) {
+                    if (ks0 + u < nks) {
+                        const bf16x8 a = *(const bf16x8*)(XY + l32 * xstr + (jw[jj] * q + (ks0 + u) * 16 + kg * 8) * 2);
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            zacc[jj][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, *(const bf16x8*)&braw[jj][u][nt], zacc[jj][nt], 0, 0, 0);
+                    }
+                }
         };
-        auto park_j = [&](int j) {
-            // zacc[nt][e]: token 8*(e/4) + 4*kg + e%4, rank index nt*32 + l32
+        mul(0);
+        for (int ks0 = KG; ks0 < nks; ks0 += KG) {                  // further rounds only if q > 16*KG
+            load_vf(ks0);
+            mul(ks0);
+        }
+        load_u(std::integral_constant<int, 0>{});                   // U of the first output block: in flight from here
+        if (wave < b) {
+            const bool has1 = wave + FWAVES < b;
+            // zacc[jj][nt][e]: token 8*(e/4) + 4*kg + e%4, rank index nt*32 + l32
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 const int rho = nt * 32 + l32;
                 if (rho < r) {
-                    unsigned char* zrow = Zs + rho * FZSTR + (4 * kg) * 32 + j * 2;
+                    unsigned char* zrow = Zs + rho * FZSTR + (4 * kg) * 32 + wave * 4;
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
-                        *(bf16_t*)(zrow + (8 * (e / 4) + (e % 4)) * 32) = float_to_bf16(zacc[nt][e]);
-                }
-            }
-        };
-        std::integral_constant<int, 0> J0;
-        std::integral_constant<int, 1> J1;
-        const bool has1 = wave + FWAVES < b;
-        if (nks <= KG) {                                            // common case: one group of k-steps per block
-            load_j(J0, 0);
-            load_j(J1, 0);
-            if (wave < b) { zero_acc(); mul_j(J0, 0); park_j(wave); }
-            if (has1) { zero_acc(); mul_j(J1, 0); park_j(wave + FWAVES); }
-        } else {
-            for (int jj = 0; jj < 2; ++jj) {
-                const int j = wave + jj * FWAVES;
-                if (j < b) {
-                    zero_acc();
-                    for (int ks0 = 0; ks0 < nks; ks0 += KG) {
-                        if (jj == 0) { load_j(J0, ks0); mul_j(J0, ks0); }
-                        else { load_j(J1, ks0); mul_j(J1, ks0); }
-                    }
-                    park_j(j);
+                        *(uint32_t*)(zrow + (8 * (e / 4) + (e % 4)) * 32) = pack2_bf16(zacc[0][nt][e], has1 ? zacc[1][nt][e] : 0.f);
                 }
             }
         }
     }
-
-    // S tiles of this wavefront's rank groups (phase 2)
-    s16x4 sfr[2][8];
-#pragma unroll
-    for (int cc = 0; cc < 2; ++cc) {
-        const int c = wave + cc * FWAVES;
-        if (c < nchunks) {
-#pragma unroll
-            for (int ri = 0; ri < 8; ++ri)
-                sfr[cc][ri] = *(const s16x4*)(Sp + (int64_t)(c * 8 + ri) * 256 + ci * 16 + cg * 4);
-        }
-    }
-
-    // U fragments of this wavefront's first output block (phase 3), in flight during phase 2
-    const int npt = p >> 4;                                         // p is a multiple of 16, at most 64
-    uint4 ufr[2][4][NT];
-    auto load_u = [&](auto II) {
-        constexpr int ii = decltype(II)::value;
-        const int i = wave + ii * FWAVES;
-        if (i < b) {
-            const bf16_t* ui = U + (int64_t)i * p * r;
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                if (nt < npt) {
-#pragma unroll
-                    for (int ks = 0; ks < NT; ++ks) {
-                        int k = ks * 32 + cg * 8;
-                        if (k > r - 8) k = r - 8;
-                        ufr[ii][nt][ks] = *(const uint4*)(ui + (int64_t)(nt * 16 + ci) * r + k);
-                    }
-                }
-            }
-        }
-    };
-    load_u(std::integral_constant<int, 0>{});
     __syncthreads();
 
     // ---- phase 2: one wavefront per group of 8 rank indices
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) {
-        const int c = wave + cc * FWAVES;
-        if (c < nchunks) {
-            unsigned char* chunk = Zs + c * FCHUNK;
-            f32x4 d[2][8];
+        if (wave + cc * FWAVES >= nchunks) continue;                // uniform; no global loads inside
+        unsigned char* chunk = Zs + cw[cc] * FCHUNK;
+        f32x4 d[2][8];
 #pragma unroll
-            for (int ri = 0; ri < 8; ++ri)
+        for (int ri = 0; ri < 8; ++ri)
 #pragma unroll
-                for (int tg = 0; tg < 2; ++tg) {
-                    const s16x4 a = *(const s16x4*)(chunk + ri * FZSTR + (tg * 16 + ci) * 32 + cg * 8);
-                    d[tg][ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, sfr[cc][ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-                }
-            // every read of this chunk has been issued by this wavefront before the writes below, and
-            // LDS operations of one wavefront complete in order; d[tg][ri][e]: token tg*16 + 4*cg + e, block ci
+            for (int tg = 0; tg < 2; ++tg) {
+                const s16x4 a = *(const s16x4*)(chunk + ri * FZSTR + (tg * 16 + ci) * 32 + cg * 8);
+                d[tg][ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, sfr[cc][ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+            }
+        // every read of this chunk has been issued by this wavefront before the writes below, and
+        // LDS operations of one wavefront complete in order; d[tg][ri][e]: token tg*16 + 4*cg + e, block ci
 #pragma unroll
-            for (int tg = 0; tg < 2; ++tg)
+        for (int tg = 0; tg < 2; ++tg)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int tok = tg * 16 + 4 * cg + e;
-                    *(uint4*)(chunk + (ci * FT + (tok ^ (ci & 7))) * 16) =
-                        make_uint4(pack2(d[tg][0][e], d[tg][1][e]), pack2(d[tg][2][e], d[tg][3][e]),
-                                   pack2(d[tg][4][e], d[tg][5][e]), pack2(d[tg][6][e], d[tg][7][e]));
-                }
-        }
+            for (int e = 0; e < 4; ++e) {
+                const int tok = tg * 16 + 4 * cg + e;
+                *(uint4*)(chunk + (ci * FT + (tok ^ (ci & 7))) * 16) =
+                    make_uint4(pack2_bf16(d[tg][0][e], d[tg][1][e]), pack2_bf16(d[tg][2][e], d[tg][3][e]),
+                               pack2_bf16(d[tg][4][e], d[tg][5][e]), pack2_bf16(d[tg][6][e], d[tg][7][e]));
+            }
     }
-    load_u(std::integral_constant<int, 1>{});
+    load_u(std::integral_constant<int, 1>{});                       // U of the second output block
     __syncthreads();
 
     // ---- phase 3: this wavefront's output blocks i = wave, wave + 8
     static_for<2>([&](auto II) {
         constexpr int ii = decltype(II)::value;
         const int i = wave + ii * FWAVES;
-        if (i < b) {
+        if (i >= b) return;                                         // uniform; no global loads inside
+        const int ic = i;
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                if (nt < npt) {
-                    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        for (int nt = 0; nt < NPT; ++nt) {
+            f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int ks = 0; ks < NT; ++ks) {
-                        int k = ks * 32 + cg * 8;
-                        const bool ok = k < r;
-                        if (k > r - 8) k = r - 8;
-                        const uint4 braw = keep_if(ok, ufr[ii][nt][ks]);
-                        const unsigned char* chunk = Zs + (k >> 3) * FCHUNK;
-                        const uint4 a0 = *(const uint4*)(chunk + (i * FT + (ci ^ (i & 7))) * 16);
-                        const uint4 a1 = *(const uint4*)(chunk + (i * FT + ((16 + ci) ^ (i & 7))) * 16);
-                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&a0, *(const bf16x8*)&braw, acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&a1, *(const bf16x8*)&braw, acc1, 0, 0, 0);
-                    }
-                    // acc[e]: token (mt*16) + 4*cg + e, output feature i*p + nt*16 + ci
-                    unsigned char* ycol = Ys + (i * p + nt * 16 + ci) * 2;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        *(bf16_t*)(ycol + (4 * cg + e) * ystr) = float_to_bf16(acc0[e]);
-                        *(bf16_t*)(ycol + (16 + 4 * cg + e) * ystr) = float_to_bf16(acc1[e]);
-                    }
-                }
+            for (int ks = 0; ks < NT; ++ks) {
+                int c = ks * 4 + cg;                                // group of 8 rank indices this lane multiplies
+                if (c > nchunks - 1) c = nchunks - 1;               // past r the U fragment is zero; read a valid group
+                const unsigned char* chunk = Zs + c * FCHUNK;
+                const bf16x8 a0 = *(const bf16x8*)(chunk + (ic * FT + (ci ^ (ic & 7))) * 16);
+                const bf16x8 a1 = *(const bf16x8*)(chunk + (ic * FT + ((16 + ci) ^ (ic & 7))) * 16);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&ufr[ii][nt][ks], a0, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&ufr[ii][nt][ks], a1, acc1, 0, 0, 0);
             }
+            // U is the first operand, so acc[e] is output feature i*p + nt*16 + 4*cg + e of token
+            // (mt*16) + ci: four consecutive features per lane, one 8-byte LDS write each
+            unsigned char* ydst = XY + ci * ystr + (i * p + nt * 16 + 4 * cg) * 2;
+            *(uint2*)ydst = make_uint2(pack2_bf16(acc0[0], acc0[1]), pack2_bf16(acc0[2], acc0[3]));
+            *(uint2*)(ydst + 16 * ystr) = make_uint2(pack2_bf16(acc1[0], acc1[1]), pack2_bf16(acc1[2], acc1[3]));
         }
     });
     __syncthreads();
@@ -425,70 +408,78 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
     // ---- coalesced copy of the staged output tile
     {
         const int cpr = n_out >> 3;                                  // 16-byte chunks per row
-        for (int id = tid; id < FT * cpr; id += 64 * FWAVES) {
+        for (int id = tid; id < FT * cpr; id += FTHREADS) {
             const int row = id / cpr, cc = id - row * cpr;
-            if (t0 + row < T) *(uint4*)(Y + (t0 + row) * n_out + cc * 8) = *(const uint4*)(Ys + row * ystr + cc * 16);
+            if (t0 + row < T) *(uint4*)(Y + (t0 + row) * n_out + cc * 8) = *(const uint4*)(XY + row * ystr + cc * 16);
         }
     }
 }
 
-inline int full_fusion_lds_bytes(int n_out, int r) {
+inline int full_fusion_lds_bytes(int n_in, int n_out, int r) {
     const int nt = (r + 31) / 32;
-    return nt * 4 * FCHUNK + FT * (n_out * 2 + 16);
+    const int wide = n_in > n_out ? n_in : n_out;
+    return nt * 4 * FCHUNK + FT * (wide * 2 + 16);
 }
 
 }  // namespace
 
-bool blast_full_fusion_supported(int64_t T, int n_in, int n_out, int b, int r) {
-    if (T <= 0 || b <= 0 || b > 16 || n_in % b || n_out % b) return false;
+bool blast_full_fusion_shape_ok(int n_in, int n_out, int b, int r) {
+    if (b <= 0 || b > 16 || n_in <= 0 || n_out <= 0 || r <= 0 || n_in % b || n_out % b) return false;
     const int q = n_in / b, p = n_out / b;
     if (q % 8 || r % 8 || p % 16 || p > 64 || r > 128) return false;
-    if ((T + FT - 1) / FT >= (1ll << 30)) return false;
-    return full_fusion_lds_bytes(n_out, r) <= 160 * 1024;
+    return full_fusion_lds_bytes(n_in, n_out, r) <= 160 * 1024;
 }
 
-template <int NT, int KG>
-static hipError_t launch_full_nt(const void* X, const void* U, const void* Sp, const void* Vt, void* Y,
-                                 int64_t T, int n_in, int n_out, int b, int r, hipStream_t s) {
-    static int attr_bytes = 0;
-    const int lds = full_fusion_lds_bytes(n_out, r);
-    auto kern = blast_full_kernel<NT, KG>;
-    if (lds > attr_bytes) {
+bool blast_full_fusion_supported(int64_t T, int n_in, int n_out, int b, int r) {
+    return T > 0 && (T + FT - 1) / FT < (1ll << 30) && blast_full_fusion_shape_ok(n_in, n_out, b, r);
+}
+
+size_t blast_vf_bytes(int n_in, int b, int r) {
+    return (size_t)b * ((r + 31) / 32) * ((n_in / b + 15) / 16) * 1024;
+}
+
+size_t blast_uf_bytes(int n_out, int b, int r) {
+    return (size_t)b * (n_out / b / 16) * ((r + 31) / 32) * 1024;
+}
+
+template <int NT, int KG, int NPT>
+static hipError_t launch_full_inst(const void* X, const void* Sp, const void* Vf, const void* Uf, void* Y,
+                                   int64_t T, int n_in, int n_out, int b, int r, hipStream_t s) {
+    static bool attr_set = false;
+    const int lds = full_fusion_lds_bytes(n_in, n_out, r);
+    auto kern = blast_full_kernel<NT, KG, NPT>;
+    if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_bytes = 160 * 1024;
+        attr_set = true;
     }
     const unsigned nblk = (unsigned)((T + FT - 1) / FT);
-    hipLaunchKernelGGL(kern, dim3(nblk), dim3(64 * FWAVES), lds, s, (const bf16_t*)X, (const bf16_t*)U,
-                       (const bf16_t*)Sp, (const bf16_t*)Vt, (bf16_t*)Y, T, n_in, n_out, b, r);
+    hipLaunchKernelGGL(kern, dim3(nblk), dim3(FTHREADS), lds, s, (const bf16_t*)X, (const bf16_t*)Sp,
+                       (const bf16_t*)Vf, (const bf16_t*)Uf, (bf16_t*)Y, T, n_in, n_out, b, r);
     return hipGetLastError();
 }
 
-// k-steps fetched per round, capped so that the fragment arrays stay in registers
+// KG (k-steps fetched per round) is fixed per NT so that the fragment arrays stay in registers
 template <int NT>
-static hipError_t launch_full_kg(const void* X, const void* U, const void* Sp, const void* Vt, void* Y,
+static hipError_t launch_full_nt(const void* X, const void* Sp, const void* Vf, const void* Uf, void* Y,
                                  int64_t T, int n_in, int n_out, int b, int r, hipStream_t s) {
-    constexpr int KG_MAX = NT <= 2 ? 4 : (NT == 3 ? 3 : 2);
-    const int nks = (n_in / b + 15) / 16;
-    const int kg = nks < KG_MAX ? nks : KG_MAX;
-    if (kg == 1) return launch_full_nt<NT, 1>(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s);
-    if (kg == 2) return launch_full_nt<NT, 2>(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s);
-    if constexpr (KG_MAX >= 3) {
-        if (kg == 3) return launch_full_nt<NT, 3>(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s);
-    }
-    if constexpr (KG_MAX >= 4) {
-        if (kg == 4) return launch_full_nt<NT, 4>(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s);
+    constexpr int KG = NT <= 2 ? 4 : (NT == 3 ? 3 : 1);
+    switch (n_out / b / 16) {
+        case 1: return launch_full_inst<NT, KG, 1>(X, Sp, Vf, Uf, Y, T, n_in, n_out, b, r, s);
+        case 2: return launch_full_inst<NT, KG, 2>(X, Sp, Vf, Uf, Y, T, n_in, n_out, b, r, s);
+        case 3: return launch_full_inst<NT, KG, 3>(X, Sp, Vf, Uf, Y, T, n_in, n_out, b, r, s);
+        case 4: return launch_full_inst<NT, KG, 4>(X, Sp, Vf, Uf, Y, T, n_in, n_out, b, r, s);
     }
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_blast_full(const void* X, const void* U, const void* Sp, const void* Vt, void* Y,
+hipError_t launch_blast_full(const void* X, const void* Sp, const void* Vf, const void* Uf, void* Y,
                              int64_t T, int n_in, int n_out, int b, int r, hipStream_t s) {
     switch ((r + 31) / 32) {
-        case 1: return launch_full_kg<1>(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s);
-        case 2: return launch_full_kg<2>(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s);
-        case 3: return launch_full_kg<3>(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s);
-        case 4: return launch_full_kg<4>(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s);
+        case 1: return launch_full_nt<1>(X, Sp, Vf, Uf, Y, T, n_in, n_out, b, r, s);
+        case 2: return launch_full_nt<2>(X, Sp, Vf, Uf, Y, T, n_in, n_out, b, r, s);
+        case 3: return launch_full_nt<3>(X, Sp, Vf, Uf, Y, T, n_in, n_out, b, r, s);
+        case 4: return launch_full_nt<4>(X, Sp, Vf, Uf, Y, T, n_in, n_out, b, r, s);
     }
     return hipErrorInvalidValue;
 }

@@ -24,12 +24,40 @@ __global__ __launch_bounds__(256) void pack_v_kernel(const bf16_t* V, bf16_t* Vt
     }
 }
 
-__global__ __launch_bounds__(256) void pack_s_kernel(const bf16_t* S, bf16_t* Sp, int b, int r) {
+// perm: the slot order of the single-kernel path, slot j' = (j % 8)*2 + j/8 holds input block j
+__global__ __launch_bounds__(256) void pack_s_kernel(const bf16_t* S, bf16_t* Sp, int b, int r, int perm) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= (int64_t)r * 256) return;
-    const int j = (int)(e & 15), i = (int)((e >> 4) & 15);
+    const int slot = (int)(e & 15), i = (int)((e >> 4) & 15);
+    const int j = perm ? (slot >> 1) + (slot & 1) * 8 : slot;
     const int rho = (int)(e >> 8);
     Sp[e] = (i < b && j < b) ? S[((int64_t)i * b + j) * r + rho] : (bf16_t)0;
+}
+
+// V in the fragment order of v_mfma_f32_32x32x16_bf16 (see blr_common.h), zero-filled past q and r
+__global__ __launch_bounds__(256) void pack_vf_kernel(const bf16_t* V, bf16_t* Vf, int q, int r, int ntl, int nks, int64_t total) {
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= total) return;
+    const int e = (int)(id & 7), lane = (int)((id >> 3) & 63);
+    int64_t t = id >> 9;
+    const int ks = (int)(t % nks); t /= nks;
+    const int nt = (int)(t % ntl);
+    const int j = (int)(t / ntl);
+    const int rho = nt * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8 + e;
+    Vf[id] = (rho < r && k < q) ? V[((int64_t)j * q + k) * r + rho] : (bf16_t)0;
+}
+
+// U in the fragment order of v_mfma_f32_16x16x32_bf16, zero-filled past r
+__global__ __launch_bounds__(256) void pack_uf_kernel(const bf16_t* U, bf16_t* Uf, int p, int r, int npt, int nks, int64_t total) {
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= total) return;
+    const int e = (int)(id & 7), lane = (int)((id >> 3) & 63);
+    int64_t t = id >> 9;
+    const int ks = (int)(t % nks); t /= nks;
+    const int nt = (int)(t % npt);
+    const int i = (int)(t / npt);
+    const int a = nt * 16 + (lane & 15), rho = ks * 32 + (lane >> 4) * 8 + e;
+    Uf[id] = (rho < r) ? U[((int64_t)i * p + a) * r + rho] : (bf16_t)0;
 }
 
 // stand-alone coupling from the packed tiles: A[t][i][rho] = sum_j Sp[rho][i][j] * Z[t][j][rho]
@@ -58,14 +86,32 @@ hipError_t launch_coupling_packed(const void* Z, const void* Sp, void* A, int64_
     return hipGetLastError();
 }
 
-hipError_t launch_blast_pack(const void* S, const void* V, void* Sp, void* Vt, int n_in, int b, int r, hipStream_t s) {
-    const int q = n_in / b;
-    dim3 gv((unsigned)((r + 31) / 32), (unsigned)((q + 31) / 32), (unsigned)b);
-    hipLaunchKernelGGL(pack_v_kernel, gv, dim3(256), 0, s, (const bf16_t*)V, (bf16_t*)Vt, q, r);
+hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Vt, void* Vf, void* Uf,
+                             int n_in, int n_out, int b, int r, hipStream_t s) {
+    const int q = n_in / b, p = n_out / b;
+    hipLaunchKernelGGL(pack_s_kernel, dim3((unsigned)r), dim3(256), 0, s, (const bf16_t*)S, (bf16_t*)Sp, b, r, Vf ? 1 : 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(pack_s_kernel, dim3((unsigned)r), dim3(256), 0, s, (const bf16_t*)S, (bf16_t*)Sp, b, r);
-    return hipGetLastError();
+    if (Vt) {
+        dim3 gv((unsigned)((r + 31) / 32), (unsigned)((q + 31) / 32), (unsigned)b);
+        hipLaunchKernelGGL(pack_v_kernel, gv, dim3(256), 0, s, (const bf16_t*)V, (bf16_t*)Vt, q, r);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (Vf) {
+        const int ntl = (r + 31) / 32, nks = (q + 15) / 16;
+        const int64_t total = (int64_t)b * ntl * nks * 512;
+        hipLaunchKernelGGL(pack_vf_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const bf16_t*)V, (bf16_t*)Vf, q, r, ntl, nks, total);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (Uf) {
+        const int npt = p / 16, nks = (r + 31) / 32;
+        const int64_t total = (int64_t)b * npt * nks * 512;
+        hipLaunchKernelGGL(pack_uf_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const bf16_t*)U, (bf16_t*)Uf, p, r, npt, nks, total);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace blr

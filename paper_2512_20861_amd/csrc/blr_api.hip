@@ -26,10 +26,31 @@ bool blast_shape_ok(int64_t T, int n_in, int n_out, int b, int r) {
     return T >= 0 && n_in > 0 && n_out > 0 && b > 0 && r > 0 && n_in % b == 0 && n_out % b == 0;
 }
 
+// Where the re-laid-out BLAST factors live inside the packed buffer.
+struct PackLayout {
+    bool full;                       // served by the single-kernel path: fragment-ordered V and U
+    size_t off_Sp, off_Vt, off_Vf, off_Uf, total;
+};
+
+PackLayout pack_layout(int n_in, int n_out, int b, int r) {
+    PackLayout pk{};
+    size_t off = 0;
+    pk.off_Sp = off; off += align_up((size_t)r * 256 * 2);
+    pk.full = blast_full_fusion_shape_ok(n_in, n_out, b, r);
+    if (pk.full) {
+        pk.off_Vf = off; off += align_up(blast_vf_bytes(n_in, b, r));
+        pk.off_Uf = off; off += align_up(blast_uf_bytes(n_out, b, r));
+    } else {
+        pk.off_Vt = off; off += align_up((size_t)n_in * r * 2);
+    }
+    pk.total = off;
+    return pk;
+}
+
 // How a BLAST call is executed and where its temporaries live in the workspace.
 struct BlastPlan {
     enum Path { GENERIC, MFMA_UNFUSED, MFMA_STAGE12, MFMA_FULL } path;
-    size_t off_A, off_Z, off_Vt, off_Sp, total;
+    size_t off_A, off_Z, off_pack, total;
 };
 
 BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
@@ -49,13 +70,18 @@ BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt,
         else pl.path = BlastPlan::MFMA_UNFUSED;
         if (pl.path != BlastPlan::MFMA_FULL) { pl.off_A = off; off += align_up(inter); }
         if (pl.path == BlastPlan::MFMA_UNFUSED) { pl.off_Z = off; off += align_up(inter); }
-        if (!packed) {
-            pl.off_Vt = off; off += align_up((size_t)b * q * r * 2);
-            pl.off_Sp = off; off += align_up((size_t)r * 256 * 2);
-        }
+        if (!packed) { pl.off_pack = off; off += pack_layout(n_in, n_out, b, r).total; }
     }
     pl.total = off;
     return pl;
+}
+
+blr_status run_pack(const void* U, const void* S, const void* V, void* packed, int n_in, int n_out, int b, int r, hipStream_t s) {
+    const PackLayout pk = pack_layout(n_in, n_out, b, r);
+    unsigned char* base = (unsigned char*)packed;
+    return from_hip(launch_blast_pack(U, S, V, base + pk.off_Sp, pk.full ? nullptr : base + pk.off_Vt,
+                                      pk.full ? base + pk.off_Vf : nullptr, pk.full ? base + pk.off_Uf : nullptr,
+                                      n_in, n_out, b, r, s));
 }
 
 }  // namespace
@@ -122,29 +148,25 @@ size_t blr_blast_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, b
     return blast_plan(T, n_in, n_out, b, r, dt, flags).total;
 }
 
-size_t blr_blast_packed_v_bytes(int n_in, int b, int r, blr_dtype dt) {
-    if (dt != BLR_BF16 || n_in <= 0 || b <= 0 || r <= 0 || n_in % b) return 0;
-    return align_up((size_t)n_in * r * 2);
+size_t blr_blast_packed_bytes(int n_in, int n_out, int b, int r, blr_dtype dt) {
+    if (dt != BLR_BF16 || !blast_shape_ok(0, n_in, n_out, b, r) || b > 16 || (n_in / b) % 8 || r % 8) return 0;
+    return pack_layout(n_in, n_out, b, r).total;
 }
 
-size_t blr_blast_packed_s_bytes(int b, int r, blr_dtype dt) {
-    if (dt != BLR_BF16 || b <= 0 || b > 16 || r <= 0) return 0;
-    return align_up((size_t)r * 256 * 2);
-}
-
-blr_status blr_blast_pack(const void* S, const void* V, void* S_packed, void* V_packed,
+blr_status blr_blast_pack(const void* U, const void* S, const void* V, void* packed,
                           int n_in, int n_out, int b, int r, blr_dtype dt, blr_stream stream) {
-    if (!S || !V || !S_packed || !V_packed) return BLR_ERR_INVALID_ARG;
+    if (!U || !S || !V || !packed) return BLR_ERR_INVALID_ARG;
     if (!blast_shape_ok(0, n_in, n_out, b, r) || dt != BLR_BF16 || b > 16) return BLR_ERR_INVALID_ARG;
-    if (!aligned16(S) || !aligned16(V) || !aligned16(S_packed) || !aligned16(V_packed)) return BLR_ERR_INVALID_ARG;
-    return from_hip(launch_blast_pack(S, V, S_packed, V_packed, n_in, b, r, (hipStream_t)stream));
+    if ((n_in / b) % 8 || r % 8) return BLR_ERR_UNSUPPORTED;          // such layers run on the portable kernels, unpacked
+    if (!aligned16(U) || !aligned16(S) || !aligned16(V) || !aligned16(packed)) return BLR_ERR_INVALID_ARG;
+    return run_pack(U, S, V, packed, n_in, n_out, b, r, (hipStream_t)stream);
 }
 
 blr_status blr_blast_forward(const void* X, const void* U, const void* S, const void* V, void* Y,
                              int64_t T, int n_in, int n_out, int b, int r,
                              blr_dtype dt, unsigned flags,
                              void* workspace, size_t workspace_bytes, blr_stream stream) {
-    if (!U || !S || !V) return BLR_ERR_INVALID_ARG;
+    if (!U || !V || (!S && !(flags & BLR_BLAST_PACKED))) return BLR_ERR_INVALID_ARG;
     if (!blast_shape_ok(T, n_in, n_out, b, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
     if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
@@ -186,17 +208,20 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
         return last ? run_gemm(s3, dt, false, s) : BLR_OK;
     }
 
-    const void* Vt = V;
-    const void* Sp = S;
-    if (!(flags & BLR_BLAST_PACKED) && first) {
-        blr_status st = from_hip(launch_blast_pack(S, V, ws + pl.off_Sp, ws + pl.off_Vt, n_in, b, r, s));
-        if (st != BLR_OK) return st;
-        Vt = ws + pl.off_Vt;
-        Sp = ws + pl.off_Sp;
+    const unsigned char* pack = (const unsigned char*)V;
+    if (!(flags & BLR_BLAST_PACKED)) {
+        pack = ws + pl.off_pack;
+        if (first) {
+            blr_status st = run_pack(U, S, V, ws + pl.off_pack, n_in, n_out, b, r, s);
+            if (st != BLR_OK) return st;
+        }
     }
+    const PackLayout pk = pack_layout(n_in, n_out, b, r);
+    const void* Sp = pack + pk.off_Sp;
+    const void* Vt = pack + pk.off_Vt;
     if (pl.path == BlastPlan::MFMA_FULL) {
         if (!first || !last) return BLR_ERR_UNSUPPORTED;   // one kernel: there are no stages to select
-        return from_hip(launch_blast_full(X, U, Sp, Vt, Y, T, n_in, n_out, b, r, s));
+        return from_hip(launch_blast_full(X, Sp, pack + pk.off_Vf, pack + pk.off_Uf, Y, T, n_in, n_out, b, r, s));
     }
     if (first) {
         if (pl.path == BlastPlan::MFMA_STAGE12) {

@@ -24,13 +24,26 @@ __host__ __device__ inline float bf16_to_float(bf16_t v) {
     c.u = (uint32_t)v << 16;
     return c.f;
 }
-// round to nearest even (inputs are finite)
+// round to nearest even (inputs are finite); on the device this is the hardware conversion
 __host__ __device__ inline bf16_t float_to_bf16(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(bf16_t, h);
+#else
     union { uint32_t u; float f; } c;
     c.f = f;
     uint32_t u = c.u;
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (bf16_t)(u >> 16);
+#endif
+}
+// two floats -> two bf16 in one 32-bit word (lo in the low half): one v_cvt_pk_bf16_f32
+__device__ inline uint32_t pack2_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t h = __builtin_convertvector(v, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, h);
 }
 
 // value select (a ternary on two uint4 lvalues would select an address and force them into memory)
@@ -67,15 +80,21 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s);
 bool blast_fused_supported(int64_t T, int n_in, int b, int r);
 hipError_t launch_blast_stage12(const void* X, const void* Vt, const void* Sp, void* A,
                                 int64_t T, int n_in, int b, int r, hipStream_t s);
-// BLAST: whole layer in one kernel for small b*r. U[b][p][r]
+// BLAST: whole layer in one kernel for small ranks. Vf / Uf are V and U in MFMA-fragment order:
+//   Vf[j][nt][ks][lane][e] = V[j][ks*16 + (lane/32)*8 + e][nt*32 + lane%32]      (zero past q, r)
+//   Uf[i][nt][ks][lane][e] = U[i][nt*16 + lane%16][ks*32 + (lane/16)*8 + e]      (zero past r)
+bool blast_full_fusion_shape_ok(int n_in, int n_out, int b, int r);
 bool blast_full_fusion_supported(int64_t T, int n_in, int n_out, int b, int r);
-hipError_t launch_blast_full(const void* X, const void* U, const void* Sp, const void* Vt, void* Y,
+size_t blast_vf_bytes(int n_in, int b, int r);
+size_t blast_uf_bytes(int n_out, int b, int r);
+hipError_t launch_blast_full(const void* X, const void* Sp, const void* Vf, const void* Uf, void* Y,
                              int64_t T, int n_in, int n_out, int b, int r, hipStream_t s);
 
 // stand-alone coupling reading the packed tiles Sp[r][16][16] (bf16)
 hipError_t launch_coupling_packed(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s);
 
-// BLAST weight re-layout (bf16)
-hipError_t launch_blast_pack(const void* S, const void* V, void* Sp, void* Vt, int n_in, int b, int r, hipStream_t s);
+// BLAST weight re-layout (bf16): Sp always; Vt (row-major transpose) if non-null; Vf and Uf if non-null
+hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Vt, void* Vf, void* Uf,
+                             int n_in, int n_out, int b, int r, hipStream_t s);
 
 }  // namespace blr

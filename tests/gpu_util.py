@@ -46,8 +46,8 @@ def run_blast(X, lay, flags=0, packed=False):
     Xd, Ud, Sd, Vd = to_dev(X), to_dev(lay.U), to_dev(lay.S), to_dev(lay.V)
     Y = empty_out(X.shape[0], lay.n_out, lay.dtype)
     if packed:
-        Sp, Vp = B.blast_pack(Sd, Vd, lay.n_in, lay.n_out, lay.b, lay.r)
-        B.blast_forward(Xd, Ud, Sp, Vp, Y, lay.b, lay.r, flags | B.BLAST_PACKED)
+        packed = B.blast_pack(Ud, Sd, Vd, lay.n_in, lay.n_out, lay.b, lay.r)
+        B.blast_forward(Xd, Ud, None, packed, Y, lay.b, lay.r, flags | B.BLAST_PACKED)
     else:
         B.blast_forward(Xd, Ud, Sd, Vd, Y, lay.b, lay.r, flags)
     torch.cuda.synchronize()

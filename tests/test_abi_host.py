@@ -47,12 +47,16 @@ def test_workspace_sizes():
     # BLAST: the whole-layer kernel needs no intermediate; packed factors add nothing
     assert B.blast_workspace_bytes(6304, 768, 768, 16, 96, B.BF16, B.BLAST_PACKED) == 0
     unpacked = B.blast_workspace_bytes(6304, 768, 768, 16, 96, B.BF16, 0)
-    assert unpacked == B.blast_packed_v_bytes(768, 16, 96) + B.blast_packed_s_bytes(16, 96)
+    assert unpacked == B.blast_packed_bytes(768, 768, 16, 96)
+    # Sp (one 16x16 tile per rank index) + V and U in fragment order (1 KiB per block x tile x k-step)
+    assert B.blast_packed_bytes(768, 768, 16, 96) == 96 * 512 + 16 * 3 * 3 * 1024 + 16 * 3 * 3 * 1024
+    # larger ranks: Sp + the row-major transpose of V
+    assert B.blast_packed_bytes(4096, 4096, 16, 640) == 640 * 512 + 4096 * 640 * 2
     # large ranks keep A[T][b][r] in the workspace
     assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 512 * 16 * 640 * 2
     # portable path keeps Z and A
     assert B.blast_workspace_bytes(50, 36, 30, 3, 10, B.F32, 0) == 2 * ((50 * 3 * 10 * 4 + 255) // 256 * 256)
-    assert B.blast_packed_s_bytes(16, 96) == 96 * 256 * 2 and B.blast_packed_s_bytes(17, 96) == 0
+    assert B.blast_packed_bytes(768, 768, 32, 96) == 0 and B.blast_packed_bytes(768, 768, 16, 96, B.F32) == 0
 
 
 def _monarch(T=4, n_in=64, n_out=64, nb=4, r=16, dt=B.BF16, flags=0, X=FAKE, R=FAKE, L=FAKE, Y=FAKE, ws=FAKE, wsb=1 << 20):
@@ -85,6 +89,8 @@ def test_blast_argument_checks():
     assert _blast(T=0) == B.OK
     assert _blast(T=-3) == B.ERR_INVALID_ARG
     assert _blast(S=None) == B.ERR_INVALID_ARG
+    # with packed factors S may be null: the call gets as far as the workspace check
+    assert _blast(S=None, flags=B.BLAST_PACKED, T=64, n_in=4096, n_out=4096, b=16, r=640, wsb=1024) == B.ERR_WORKSPACE
     assert _blast(Y=None) == B.ERR_INVALID_ARG
     assert _blast(n_in=66) == B.ERR_INVALID_ARG
     assert _blast(n_out=30) == B.ERR_INVALID_ARG
@@ -106,6 +112,7 @@ def test_dense_and_pack_argument_checks():
     assert lib.blr_blast_pack(FAKE, FAKE, FAKE, FAKE, 64, 64, 4, 16, B.F32, None) == B.ERR_INVALID_ARG
     assert lib.blr_blast_pack(FAKE, FAKE, FAKE, FAKE, 64, 64, 32, 16, B.BF16, None) == B.ERR_INVALID_ARG
     assert lib.blr_blast_pack(None, FAKE, FAKE, FAKE, 64, 64, 4, 16, B.BF16, None) == B.ERR_INVALID_ARG
+    assert lib.blr_blast_pack(FAKE, FAKE, FAKE, FAKE, 36, 30, 3, 10, B.BF16, None) == B.ERR_UNSUPPORTED
 
 
 def test_missing_library_fails_loudly(tmp_path, monkeypatch):

@@ -102,10 +102,10 @@ def test_graph_replay_and_prepared_calls_match_eager():
     Xb, Xm = gu.to_dev(bi.activations(333, 768, "bf16")), gu.to_dev(bi.activations(333, 512, "bf16"))
     Ud, Sd, Vd = gu.to_dev(lay.U), gu.to_dev(lay.S), gu.to_dev(lay.V)
     Rd, Ld = gu.to_dev(mon.R), gu.to_dev(mon.L)
-    Sp, Vp = B.blast_pack(Sd, Vd, 768, 768, 16, 96)
+    packed = B.blast_pack(Ud, Sd, Vd, 768, 768, 16, 96)
     wsm = torch.empty(B.monarch_workspace_bytes(333, 512, 768, 4, 256, B.BF16), dtype=torch.uint8, device="cuda")
     Yb_e, Ym_e = gu.empty_out(333, 768, "bf16"), gu.empty_out(333, 768, "bf16")
-    B.blast_forward(Xb, Ud, Sp, Vp, Yb_e, 16, 96, B.BLAST_PACKED)
+    B.blast_forward(Xb, Ud, None, packed, Yb_e, 16, 96, B.BLAST_PACKED)
     B.monarch_forward(Xm, Rd, Ld, Ym_e, 4, 256, 0, wsm)
     torch.cuda.synchronize()
 
@@ -114,7 +114,7 @@ def test_graph_replay_and_prepared_calls_match_eager():
     side.wait_stream(torch.cuda.current_stream())
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=side):
-        cb = B.prepared(B.blast_forward, Xb, Ud, Sp, Vp, Yb, 16, 96, B.BLAST_PACKED)
+        cb = B.prepared(B.blast_forward, Xb, Ud, None, packed, Yb, 16, 96, B.BLAST_PACKED)
         cm = B.prepared(B.monarch_forward, Xm, Rd, Ld, Ym, 4, 256, 0, wsm)
         cb()
         cm()
@@ -127,6 +127,6 @@ def test_graph_replay_and_prepared_calls_match_eager():
         assert torch.equal(Ym.view(torch.int16), Ym_e.view(torch.int16)), f"Monarch replay {rep}"
     # prepared call outside a graph
     Yb.fill_(float("nan"))
-    B.prepared(B.blast_forward, Xb, Ud, Sp, Vp, Yb, 16, 96, B.BLAST_PACKED)()
+    B.prepared(B.blast_forward, Xb, Ud, None, packed, Yb, 16, 96, B.BLAST_PACKED)()
     torch.cuda.synchronize()
     assert torch.equal(Yb.view(torch.int16), Yb_e.view(torch.int16))
