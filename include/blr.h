@@ -58,9 +58,15 @@ typedef void* blr_stream;      /* a hipStream_t */
 /* measurement aids of the two BLR forwards: enqueue only the kernels up to and including the one
  * that writes the workspace intermediate (FIRST), or only the kernel that consumes it (LAST; the
  * workspace must hold the intermediate of an earlier call with identical arguments). Mutually
- * exclusive; BLR_ERR_UNSUPPORTED where the call is a single kernel. */
+ * exclusive; BLR_ERR_UNSUPPORTED where the call is a single kernel. Where BLAST walks the tokens in
+ * several chunks the workspace holds one chunk only, so LAST is then good for timing, not for values. */
 #define BLR_ONLY_FIRST_STAGE        0x200u
 #define BLR_ONLY_LAST_STAGE         0x400u
+/* flag of blr_blast_forward: where the layer is too large for the single-kernel path, fuse stage 1
+ * and the coupling in one kernel (Z stays in LDS; the paper's optimisation 4 with the coupling on
+ * the matrix cores) instead of the default three kernels over cache-resident token chunks (the
+ * paper's optimisation 5). Both are kept so that the benchmark can show which wins per shape. */
+#define BLR_BLAST_FUSED_STAGE12     0x800u
 
 /*
  * Monarch forward (paper Section 2.1 "Monarch"; Section 4 "Monarch", optimisations 1-3).

@@ -28,8 +28,6 @@ static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 static_assert(D % 2 == 0, "ring slot parity must equal LDS stage parity");
 static_assert(ZS_BYTES % 16 == 0, "Zs is cleared with 16-byte stores");
 
-__device__ inline uint32_t pack2(float lo, float hi) { return pack2_bf16(lo, hi); }
-
 // workgroup id -> logical tile id such that each XCD (workgroups are dealt round-robin over 8 XCDs)
 // works on a contiguous range of logical ids, i.e. shares its X tiles in its own L2
 __device__ inline int xcd_contiguous(int bid, int nblk) {
@@ -38,9 +36,130 @@ __device__ inline int xcd_contiguous(int bid, int nblk) {
     return xcd * q8 + (xcd < rem ? xcd : rem) + slot;
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Vt,
-                                                            const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
-                                                            int64_t T, int n_in, int b, int r, int tiles_r, int nblk) {
+// Coupling of one 64-token x 64-rank tile whose Z values sit in LDS as Zs[rho][t][j] (bf16):
+// A[t][i][rho] = sum_j S[i][j][rho] Z[t][j][rho] on v_mfma_f32_16x16x16_bf16, one MFMA per rank index
+// and 16 tokens, S tiles from the packed Sp[rho][i][j]. Each wavefront takes two groups of 8 rank
+// indices; a group's result replaces the group's own Z rows IN PLACE as As[i][t][8 rho] (the group is
+// read completely first and only this wavefront touches it), so that A leaves with full-line stores.
+// Must be entered after a barrier that follows the last write to Zs.
+__device__ __forceinline__ void couple_tile_and_store(unsigned char* Zs, const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
+                                             int64_t T, int64_t t0, int rho0, int b, int r) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ci = lane & 15, cg = lane >> 4;
+    constexpr int GROUP = 8 * ZSTR;
+    static_assert(16 * TN * 16 <= GROUP, "in-place A must fit in the rows it replaces");
+#pragma unroll 1
+    for (int cc = 0; cc < 2; ++cc) {
+        const int c = wave * 2 + cc;
+        unsigned char* grp = Zs + c * GROUP;
+        s16x4 sfrag[8];
+#pragma unroll
+        for (int ri = 0; ri < 8; ++ri) {
+            int rg = rho0 + c * 8 + ri;
+            if (rg > r - 1) rg = r - 1;                 // groups past r are computed on repeated tiles and not stored
+            sfrag[ri] = *(const s16x4*)(Sp + (int64_t)rg * 256 + ci * 16 + cg * 4);
+        }
+        f32x4 d[TN / 16][8];
+#pragma unroll
+        for (int ri = 0; ri < 8; ++ri)
+#pragma unroll
+            for (int tg = 0; tg < TN / 16; ++tg) {
+                const s16x4 a = *(const s16x4*)(grp + ri * ZSTR + (tg * 16 + ci) * 32 + cg * 8);
+                d[tg][ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, sfrag[ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+            }
+        // d[tg][ri][e]: token tg*16 + 4*(lane/16) + e, output block i = lane%16
+#pragma unroll
+        for (int tg = 0; tg < TN / 16; ++tg)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int tok = tg * 16 + 4 * cg + e;
+                *(uint4*)(grp + (ci * TN + (tok ^ (ci & 7))) * 16) =
+                    make_uint4(pack2_bf16(d[tg][0][e], d[tg][1][e]), pack2_bf16(d[tg][2][e], d[tg][3][e]),
+                               pack2_bf16(d[tg][4][e], d[tg][5][e]), pack2_bf16(d[tg][6][e], d[tg][7][e]));
+            }
+    }
+    __syncthreads();
+    // A[t][i][rho0 .. rho0+63]: 8 lanes write the 128 contiguous bytes of one (token, block)
+    for (int id = tid; id < TN * b * 8; id += 256) {
+        const int c8 = id & 7;
+        const int i = (id >> 3) % b;
+        const int t = (id >> 3) / b;
+        if (t0 + t < T && rho0 + c8 * 8 < r)
+            *(uint4*)(A + ((t0 + t) * b + i) * r + rho0 + c8 * 8) = *(const uint4*)(Zs + c8 * GROUP + (i * TN + (t ^ (i & 7))) * 16);
+    }
+}
+
+// Stand-alone coupling (the middle kernel of the three-kernel path): Z[T][b][r] -> A[T][b][r].
+// The Z tile is read with full-line loads (8 lanes per 128-byte row segment) and transposed on its
+// way into LDS; blocks j and j+1 travel together so that every LDS write is a bf16 pair.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
+                           int64_t T, int b, int r, int tiles_r, int nblk) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* Zs = smem;
+    const int tid = threadIdx.x;
+    const int logical = xcd_contiguous(blockIdx.x, nblk);
+    const int tile_t = logical / tiles_r, tile_r = logical % tiles_r;
+    const int64_t t0 = (int64_t)tile_t * TN;
+    const int rho0 = tile_r * TR;
+    const int c8 = tid & 7;                              // which 8 rank indices of the 64
+    int rho = rho0 + c8 * 8;
+    if (rho > r - 8) rho = r - 8;                        // past r: repeat valid data, never stored (r is a multiple of 8)
+    const int npair = (b + 1) >> 1;
+    if (b < 16)
+        for (int i = tid * 16; i < ZS_BYTES; i += 256 * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
+    if (b < 16) __syncthreads();
+    // work item = (token, block pair): 8 lanes cover its 128-byte segment; 4 items in flight per thread
+    const int items = TN * npair;
+    for (int base = 0; base < items; base += 32 * 4) {
+        uint4 v0[4], v1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int it = base + u * 32 + (tid >> 3);
+            if (it > items - 1) it = items - 1;
+            const int t = it / npair, jp = it - t * npair;
+            int64_t tok = t0 + t;
+            if (tok > T - 1) tok = T - 1;
+            const int j1 = 2 * jp + 1 < b ? 2 * jp + 1 : 2 * jp;
+            v0[u] = *(const uint4*)(Z + (tok * b + 2 * jp) * r + rho);
+            v1[u] = *(const uint4*)(Z + (tok * b + j1) * r + rho);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int it = base + u * 32 + (tid >> 3);
+            if (it < items) {
+                const int t = it / npair, jp = it - t * npair;
+                const bool has1 = 2 * jp + 1 < b;
+                const uint32_t w0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w};
+                const uint32_t w1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
+                unsigned char* dst = Zs + (c8 * 8) * ZSTR + t * 32 + jp * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t hi = has1 ? w1[e] : 0u;
+                    *(uint32_t*)(dst + (2 * e) * ZSTR) = (w0[e] & 0xFFFFu) | (hi << 16);
+                    *(uint32_t*)(dst + (2 * e + 1) * ZSTR) = (w0[e] >> 16) | (hi & 0xFFFF0000u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    couple_tile_and_store(Zs, Sp, A, T, t0, rho0, b, r);
+}
+
+// Round a finished Z_j accumulator tile to bf16 and park it in LDS (column j of Zs[rho][t][j]).
+// Deliberately not inlined: inlined, the compiler hoists the accumulator reads and conversions out of
+// the once-per-block branch into every step of the main loop.
+__device__ __noinline__ void park_z_tile(unsigned char* zcol, f32x16 acc) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) *(bf16_t*)(zcol + (8 * (e / 4) + (e % 4)) * 32) = float_to_bf16(acc[e]);
+}
+
+// TAIL: q is not a multiple of BK, i.e. the last k-chunk of every input block is partial.
+template <bool TAIL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Vt,
+                          const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
+                          int64_t T, int n_in, int b, int r, int tiles_r, int nblk) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* Zs = smem;
     unsigned char* stg = smem + ZS_BYTES;
@@ -51,41 +170,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int64_t t0 = (int64_t)tile_t * TN;
     const int rho0 = tile_r * TR;
     const int q = n_in / b;
+    const int nkc = (q + BK - 1) / BK;
+    const int nsteps = b * nkc;
 
+    // Addresses = a uniform running base (advanced with scalar arithmetic once per step) plus a
+    // per-thread byte offset that never changes: the main loop spends almost nothing on indexing.
     const int lrow = tid >> 2, lchunk = tid & 3;
-    int64_t tx = t0 + lrow;
-    if (tx > T - 1) tx = T - 1;                         // rows past the end re-read the last row; never stored
-    int rr = rho0 + lrow;
-    if (rr > r - 1) rr = r - 1;
-    const bf16_t* xp = X + tx * n_in;
-    const bf16_t* vp = Vt + (int64_t)rr * q;
-    const int64_t v_jstride = (int64_t)r * q;
+    int xr = lrow;
+    if (t0 + xr > T - 1) xr = (int)(T - 1 - t0);        // rows past the end re-read the last row; never stored
+    int vr = rho0 + lrow;
+    if (vr > r - 1) vr = r - 1;
+    const int xoff = (xr * n_in + lchunk * 8) * 2;      // bytes from the tile's first X row
+    const int voff = (vr * q + lchunk * 8) * 2;         // bytes from Vt[j]
+    const unsigned char* xs = (const unsigned char*)(X + t0 * n_in);
+    const unsigned char* vs = (const unsigned char*)Vt;
+    // in the last chunk of a block, 16-byte pieces at or past q re-read the last valid piece and are zeroed in LDS
+    const int last_k = (nkc - 1) * BK + lchunk * 8;
+    const bool tail_bad = TAIL && last_k >= q;
+    const int tail_fix = tail_bad ? (q - 8 - last_k) * 2 : 0;
+    const int x_wrap = (q - (nkc - 1) * BK) * 2;                        // last chunk of block j -> first chunk of j+1
+    const int64_t v_wrap = ((int64_t)r * q - (int64_t)(nkc - 1) * BK) * 2;
 
     if (b < 16)                                         // unused j slots must read as zero in the coupling
         for (int i = tid * 16; i < ZS_BYTES; i += 256 * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
 
-    const int nkc = (q + BK - 1) / BK;
-    const int nsteps = b * nkc;
-    // Register ring of D steps of global loads in flight (as in the GEMM kernel); a step is (j, kc).
-    // Loads are unconditional: the fetch cursor stops at the last step, chunks past q are zeroed on
-    // their way to LDS.
+    // register ring of D steps of global loads in flight (as in the GEMM kernel); a step is (j, kc)
     uint4 ra[D], rb[D];
-    int pj = 0, pk = 0;                                 // cursor of the next step to fetch
+    int pk = 0, fetched = 0;                            // fetch cursor (uniform)
     auto gload = [&](auto SLOT) {
         constexpr int slot = decltype(SLOT)::value;
-        int k = pk * BK + lchunk * 8;
-        if (k > q - 8) k = q - 8;                       // q is a multiple of 8
-        ra[slot] = *(const uint4*)(xp + pj * q + k);
-        rb[slot] = *(const uint4*)(vp + pj * v_jstride + k);
-        if (pj * nkc + pk < nsteps - 1) { if (++pk == nkc) { pk = 0; ++pj; } }
+        const int fix = (TAIL && pk == nkc - 1) ? tail_fix : 0;
+        ra[slot] = *(const uint4*)(xs + (xoff + fix));
+        rb[slot] = *(const uint4*)(vs + (voff + fix));
+        if (fetched < nsteps - 1) {                     // the cursor stops at the last step; later fetches repeat it
+            ++fetched;
+            if (pk == nkc - 1) { pk = 0; xs += x_wrap; vs += v_wrap; }
+            else { ++pk; xs += BK * 2; vs += BK * 2; }
+        }
     };
-    auto sstore = [&](auto SLOT, int kc_of_slot) {
+    auto sstore = [&](auto SLOT, bool last_chunk) {
         constexpr int slot = decltype(SLOT)::value;
-        constexpr int stage = slot & 1;              // D is even: slot parity == step parity
+        constexpr int stage = slot & 1;                 // D is even: slot parity == step parity
         unsigned char* base = stg + stage * STAGE;
-        const bool ok = (kc_of_slot * BK + lchunk * 8) < q;
-        *(uint4*)(base + lrow * STR + lchunk * 16) = keep_if(ok, ra[slot]);
-        *(uint4*)(base + TN * STR + lrow * STR + lchunk * 16) = keep_if(ok, rb[slot]);
+        const bool ok = !(TAIL && last_chunk && tail_bad);
+        *(uint4*)(base + lrow * STR + lchunk * 16) = TAIL ? keep_if(ok, ra[slot]) : ra[slot];
+        *(uint4*)(base + TN * STR + lrow * STR + lchunk * 16) = TAIL ? keep_if(ok, rb[slot]) : rb[slot];
     };
 
     f32x16 acc;
@@ -93,75 +222,42 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
 
     const int frag_off = (lane & 31) * STR + (lane >> 5) * 16;
+    // accumulator element e is token 8*(e/4) + 4*(lane/32) + e%4, rank index lane%32 of this wavefront's quadrant
+    unsigned char* zbase = Zs + (wn * 32 + (lane & 31)) * ZSTR + (wm * 32 + 4 * (lane >> 5)) * 32;
     int j = 0, kc = 0;                                  // cursor of the step being computed
     auto step = [&](auto U) {                           // u = step % D, a compile-time constant
         constexpr int u = decltype(U)::value;
         const unsigned char* As = stg + (u & 1) * STAGE + (wm * 32) * STR + frag_off;
         const unsigned char* Bs = stg + (u & 1) * STAGE + TN * STR + (wn * 32) * STR + frag_off;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            const bf16x8 af = *(const bf16x8*)(As + ks * 32);
-            const bf16x8 bfr = *(const bf16x8*)(Bs + ks * 32);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc, 0, 0, 0);
-        }
+        const bf16x8 a0 = *(const bf16x8*)As, a1 = *(const bf16x8*)(As + 32);
+        const bf16x8 b0 = *(const bf16x8*)Bs, b1 = *(const bf16x8*)(Bs + 32);
+        // the next step's operands go to the other LDS stage and the ring is refilled while the
+        // fragment reads above are in flight; the MFMAs below then run into the next step's reads
         const bool last_kc = (kc == nkc - 1);
-        if (last_kc) {
-            // Z_j tile done: element e is token 8*(e/4) + 4*(lane/32) + e%4, rank index lane%32 of this wave's quadrant
-            unsigned char* zrow = Zs + (wn * 32 + (lane & 31)) * ZSTR + (wm * 32 + 4 * (lane >> 5)) * 32 + j * 2;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                *(bf16_t*)(zrow + (8 * (e / 4) + (e % 4)) * 32) = float_to_bf16(acc[e]);
-                acc[e] = 0.f;
-            }
-        }
         const int kc_next = last_kc ? 0 : kc + 1;
-        sstore(std::integral_constant<int, (u + 1) % D>{}, kc_next);   // past the last step this writes the unused stage
+        sstore(std::integral_constant<int, (u + 1) % D>{}, kc_next == nkc - 1);   // past the last step this writes the unused stage
         gload(std::integral_constant<int, (u + 1) % D>{});
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc, 0, 0, 0);
+        if (__builtin_expect(last_kc, 0)) {             // out of line: nothing of it runs in the other steps
+            park_z_tile(zbase + j * 2, acc);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        }
         __syncthreads();
         kc = kc_next;
         if (last_kc) ++j;
     };
 
     static_for<D>([&](auto U) { gload(U); });
-    sstore(std::integral_constant<int, 0>{}, 0);
+    sstore(std::integral_constant<int, 0>{}, nkc == 1);
     gload(std::integral_constant<int, 0>{});
     __syncthreads();
     int s0 = 0;
     for (; s0 + D <= nsteps; s0 += D) static_for<D>([&](auto U) { step(U); });
     static_for<D - 1>([&](auto U) { if (s0 + decltype(U)::value < nsteps) step(U); });
 
-    // coupling: this wave takes 16 consecutive rank indices of the tile
-    const int rl0 = wave * 16;
-    const int ci = lane & 15, cg = lane >> 4;
-    s16x4 sfrag[16];
-#pragma unroll
-    for (int ri = 0; ri < 16; ++ri) {
-        const int rg = rho0 + rl0 + ri;
-        if (rg < r) sfrag[ri] = *(const s16x4*)(Sp + (int64_t)rg * 256 + ci * 16 + cg * 4);
-        else sfrag[ri] = s16x4{0, 0, 0, 0};
-    }
-    const bool lo_ok = rho0 + rl0 < r, hi_ok = rho0 + rl0 + 8 < r;   // r is a multiple of 8
-#pragma unroll 1
-    for (int tg = 0; tg < TN / 16; ++tg) {
-        f32x4 d[16];
-#pragma unroll
-        for (int ri = 0; ri < 16; ++ri) {
-            const s16x4 a = *(const s16x4*)(Zs + (rl0 + ri) * ZSTR + (tg * 16 + ci) * 32 + cg * 8);
-            d[ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, sfrag[ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-        }
-        // d[ri][e]: token tg*16 + 4*(lane/16) + e, output block i = lane%16
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int64_t tok = t0 + tg * 16 + 4 * cg + e;
-            if (tok < T && ci < b) {
-                bf16_t* dst = A + (tok * b + ci) * r + rho0 + rl0;
-                if (lo_ok) *(uint4*)dst = make_uint4(pack2(d[0][e], d[1][e]), pack2(d[2][e], d[3][e]),
-                                                     pack2(d[4][e], d[5][e]), pack2(d[6][e], d[7][e]));
-                if (hi_ok) *(uint4*)(dst + 8) = make_uint4(pack2(d[8][e], d[9][e]), pack2(d[10][e], d[11][e]),
-                                                           pack2(d[12][e], d[13][e]), pack2(d[14][e], d[15][e]));
-            }
-        }
-    }
+    couple_tile_and_store(Zs, Sp, A, T, t0, rho0, b, r);
 }
 
 }  // namespace
@@ -177,14 +273,34 @@ hipError_t launch_blast_stage12(const void* X, const void* Vt, const void* Sp, v
                                 int64_t T, int n_in, int b, int r, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void*)blast_stage12_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles_t = (int)((T + TN - 1) / TN), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
-    hipLaunchKernelGGL(blast_stage12_kernel, dim3((unsigned)nblk), dim3(256), LDS_BYTES, s,
-                       (const bf16_t*)X, (const bf16_t*)Vt, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r, tiles_r, nblk);
+    if ((n_in / b) % BK)
+        hipLaunchKernelGGL(blast_stage12_kernel<true>, dim3((unsigned)nblk), dim3(256), LDS_BYTES, s,
+                           (const bf16_t*)X, (const bf16_t*)Vt, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r, tiles_r, nblk);
+    else
+        hipLaunchKernelGGL(blast_stage12_kernel<false>, dim3((unsigned)nblk), dim3(256), LDS_BYTES, s,
+                           (const bf16_t*)X, (const bf16_t*)Vt, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r, tiles_r, nblk);
+    return hipGetLastError();
+}
+
+hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)blast_coupling_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ZS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_t = (int)((T + TN - 1) / TN), tiles_r = (r + TR - 1) / TR;
+    const int nblk = tiles_t * tiles_r;
+    hipLaunchKernelGGL(blast_coupling_kernel, dim3((unsigned)nblk), dim3(256), ZS_BYTES, s,
+                       (const bf16_t*)Z, (const bf16_t*)Sp, (bf16_t*)A, T, b, r, tiles_r, nblk);
     return hipGetLastError();
 }
 

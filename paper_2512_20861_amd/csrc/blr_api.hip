@@ -49,27 +49,40 @@ PackLayout pack_layout(int n_in, int n_out, int b, int r) {
 
 // How a BLAST call is executed and where its temporaries live in the workspace.
 struct BlastPlan {
-    enum Path { GENERIC, MFMA_UNFUSED, MFMA_STAGE12, MFMA_FULL } path;
+    enum Path { GENERIC, MFMA_THREE, MFMA_STAGE12, MFMA_FULL } path;
+    int64_t chunk;                   // tokens per pass of the three-kernel path (its Z and A chunks stay cache-resident)
     size_t off_A, off_Z, off_pack, total;
 };
+
+// The three-kernel path (stage-1 GEMM, MFMA coupling, stage-3 GEMM) walks the tokens in chunks whose
+// two intermediates (Z and A, b*r bf16 per token each) together stay well inside the 256 MB
+// memory-side cache, so that they are produced and consumed without a round trip to HBM.
+constexpr size_t kChunkBytes = 48u << 20;
 
 BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
     BlastPlan pl{};
     const int q = n_in / b;
     const bool packed = flags & BLR_BLAST_PACKED;
     const bool mfma = dt == BLR_BF16 && !(flags & BLR_FORCE_GENERIC) && b <= 16 && q % 8 == 0 && r % 8 == 0;
-    const size_t inter = (size_t)T * b * r * elem_size(dt);
+    const size_t per_token = (size_t)b * r * elem_size(dt);
     size_t off = 0;
+    pl.chunk = T;
     if (!mfma) {
         pl.path = BlastPlan::GENERIC;
-        pl.off_A = off; off += align_up(inter);
-        pl.off_Z = off; off += align_up(inter);
+        pl.off_A = off; off += align_up((size_t)T * per_token);
+        pl.off_Z = off; off += align_up((size_t)T * per_token);
     } else {
         if (blast_full_fusion_supported(T, n_in, n_out, b, r)) pl.path = BlastPlan::MFMA_FULL;
-        else if (blast_fused_supported(T, n_in, b, r)) pl.path = BlastPlan::MFMA_STAGE12;
-        else pl.path = BlastPlan::MFMA_UNFUSED;
-        if (pl.path != BlastPlan::MFMA_FULL) { pl.off_A = off; off += align_up(inter); }
-        if (pl.path == BlastPlan::MFMA_UNFUSED) { pl.off_Z = off; off += align_up(inter); }
+        else if ((flags & BLR_BLAST_FUSED_STAGE12) && blast_fused_supported(T, n_in, b, r)) pl.path = BlastPlan::MFMA_STAGE12;
+        else pl.path = BlastPlan::MFMA_THREE;
+        if (pl.path == BlastPlan::MFMA_STAGE12) { pl.off_A = off; off += align_up((size_t)T * per_token); }
+        if (pl.path == BlastPlan::MFMA_THREE) {
+            int64_t c = (int64_t)(kChunkBytes / per_token) / 256 * 256;
+            if (c < 256) c = 256;
+            if (c < T) pl.chunk = c;
+            pl.off_A = off; off += align_up((size_t)pl.chunk * per_token);
+            pl.off_Z = off; off += align_up((size_t)pl.chunk * per_token);
+        }
         if (!packed) { pl.off_pack = off; off += pack_layout(n_in, n_out, b, r).total; }
     }
     pl.total = off;
@@ -168,7 +181,7 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
                              void* workspace, size_t workspace_bytes, blr_stream stream) {
     if (!U || !V || (!S && !(flags & BLR_BLAST_PACKED))) return BLR_ERR_INVALID_ARG;
     if (!blast_shape_ok(T, n_in, n_out, b, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
-    if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_BLAST_FUSED_STAGE12)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_BLAST_PACKED) && (dt != BLR_BF16 || b > 16 || (flags & BLR_FORCE_GENERIC))) return BLR_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(U) || !aligned16(S) || !aligned16(V) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
@@ -223,20 +236,33 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
         if (!first || !last) return BLR_ERR_UNSUPPORTED;   // one kernel: there are no stages to select
         return from_hip(launch_blast_full(X, Sp, pack + pk.off_Vf, pack + pk.off_Uf, Y, T, n_in, n_out, b, r, s));
     }
-    if (first) {
-        if (pl.path == BlastPlan::MFMA_STAGE12) {
+    if (pl.path == BlastPlan::MFMA_STAGE12) {
+        if (first) {
             blr_status st = from_hip(launch_blast_stage12(X, Vt, Sp, Aws, T, n_in, b, r, s));
             if (st != BLR_OK) return st;
-        } else {
-            // unfused: both intermediates go through the workspace
-            s1.B = Vt; s1.b_gs = (int64_t)q * r; s1.b_rs = q; s1.b_ks = 1; s1.b_div = 0;
+        }
+        return last ? run_gemm(s3, dt, true, s) : BLR_OK;
+    }
+    // three kernels per chunk of tokens: stage-1 GEMM -> Z, MFMA coupling Z -> A, stage-3 GEMM
+    s1.B = Vt; s1.b_gs = (int64_t)q * r; s1.b_rs = q; s1.b_ks = 1; s1.b_div = 0;
+    for (int64_t c0 = 0; c0 < T; c0 += pl.chunk) {
+        const int64_t tc = T - c0 < pl.chunk ? T - c0 : pl.chunk;
+        if (first) {
+            s1.A = (const unsigned char*)X + (size_t)c0 * n_in * 2;
+            s1.M = tc;
             blr_status st = run_gemm(s1, dt, true, s);
             if (st != BLR_OK) return st;
-            st = from_hip(launch_coupling_packed(Zws, Sp, Aws, T, b, r, s));
+            st = from_hip(launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
+            if (st != BLR_OK) return st;
+        }
+        if (last) {
+            s3.C = (unsigned char*)Y + (size_t)c0 * n_out * 2;
+            s3.M = tc;
+            blr_status st = run_gemm(s3, dt, true, s);
             if (st != BLR_OK) return st;
         }
     }
-    return last ? run_gemm(s3, dt, true, s) : BLR_OK;
+    return BLR_OK;
 }
 
 blr_status blr_dense_reference_forward(const void* X, const void* W, void* Y,

@@ -80,6 +80,9 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s);
 bool blast_fused_supported(int64_t T, int n_in, int b, int r);
 hipError_t launch_blast_stage12(const void* X, const void* Vt, const void* Sp, void* A,
                                 int64_t T, int n_in, int b, int r, hipStream_t s);
+// BLAST: stand-alone coupling on MFMA, Z[T][b][r] -> A[T][b][r] (bf16), S tiles from Sp[r][16][16]; needs r % 8 == 0, b <= 16
+hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s);
+
 // BLAST: whole layer in one kernel for small ranks. Vf / Uf are V and U in MFMA-fragment order:
 //   Vf[j][nt][ks][lane][e] = V[j][ks*16 + (lane/32)*8 + e][nt*32 + lane%32]      (zero past q, r)
 //   Uf[i][nt][ks][lane][e] = U[i][nt*16 + lane%16][ks*32 + (lane/16)*8 + e]      (zero past r)

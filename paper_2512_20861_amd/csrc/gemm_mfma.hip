@@ -247,9 +247,10 @@ bool mfma_gemm_supported(const GemmDesc& d) {
 }
 
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
+    constexpr int kSmallK = 256;     // short contractions: 128 x 128 tiles, two workgroups per CU overlap prologue and epilogue
     const bool k64 = (d.K % 64 == 0);
     // large problems: 256 x 256 tiles on 8 wavefronts (half the LDS and L2 traffic per FLOP of 128 x 128)
-    if (d.M > 128 && d.N > 128 && (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.G >= 256)
+    if (d.M > 128 && d.N > 128 && d.K > kSmallK && (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.G >= 256)
         return k64 ? launch_cfg<256, 256, 64, 2, 4, 2>(d, s) : launch_cfg<256, 256, 32, 2, 4, 2>(d, s);
     if (d.M > 64 && d.N > 64) return k64 ? launch_cfg<128, 128, 64, 2, 2, 2>(d, s) : launch_cfg<128, 128, 32, 2, 2, 4>(d, s);
     if (d.M > 64)             return k64 ? launch_cfg<128, 64, 64, 2, 2, 2>(d, s) : launch_cfg<128, 64, 32, 2, 2, 4>(d, s);

@@ -52,8 +52,12 @@ def test_workspace_sizes():
     assert B.blast_packed_bytes(768, 768, 16, 96) == 96 * 512 + 16 * 3 * 3 * 1024 + 16 * 3 * 3 * 1024
     # larger ranks: Sp + the row-major transpose of V
     assert B.blast_packed_bytes(4096, 4096, 16, 640) == 640 * 512 + 4096 * 640 * 2
-    # large ranks keep A[T][b][r] in the workspace
-    assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 512 * 16 * 640 * 2
+    # large ranks: Z and A of one chunk of tokens (three-kernel path), or A alone (fused stage 1 + coupling)
+    assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 2 * 512 * 16 * 640 * 2
+    assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED | B.BLAST_FUSED_STAGE12) == 512 * 16 * 640 * 2
+    # many tokens: the chunk (a multiple of 256 tokens whose Z and A are 48 MiB each at most) bounds the workspace
+    chunk = (48 << 20) // (16 * 640 * 2) // 256 * 256
+    assert B.blast_workspace_bytes(100000, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 2 * chunk * 16 * 640 * 2
     # portable path keeps Z and A
     assert B.blast_workspace_bytes(50, 36, 30, 3, 10, B.F32, 0) == 2 * ((50 * 3 * 10 * 4 + 255) // 256 * 256)
     assert B.blast_packed_bytes(768, 768, 32, 96) == 0 and B.blast_packed_bytes(768, 768, 16, 96, B.F32) == 0

@@ -67,18 +67,21 @@ BLAST_CASES = [
     (9, 256, 256, 4, 64, "f32"),
     (1, 768, 768, 16, 96, "bf16"),
     (200, 1152, 1152, 9, 128, "bf16"),   # b = 9 (DiT-XL/2 rows of the paper's layer table)
+    (300, 2752, 1024, 16, 328, "bf16"),  # q = 172: partial last k-chunk; r = 328: partial last rank tile
+    (150, 2560, 2560, 5, 200, "bf16"),   # odd number of blocks
 ]
 
 
 @pytest.mark.parametrize("T,n_in,n_out,b,r,dtype", BLAST_CASES)
-@pytest.mark.parametrize("mode", ["canonical", "packed", "generic"])
+@pytest.mark.parametrize("mode", ["canonical", "packed", "generic", "fused12"])
 def test_blast_parity(T, n_in, n_out, b, r, dtype, mode):
     gu = _gu()
-    if mode == "packed" and (dtype != "bf16" or (n_in // b) % 8 or r % 8):
+    if mode in ("packed", "fused12") and (dtype != "bf16" or (n_in // b) % 8 or r % 8):
         pytest.skip("packed factors exist only for the bf16 MFMA path")
     lay = bi.blast_layer(n_in, n_out, b, r, dtype)
     X = bi.activations(T, n_in, dtype)
-    Y = gu.to_f64(gu.run_blast(X, lay, gu.B.FORCE_GENERIC if mode == "generic" else 0, packed=(mode == "packed")))
+    flags = {"generic": gu.B.FORCE_GENERIC, "fused12": gu.B.BLAST_FUSED_STAGE12}.get(mode, 0)
+    Y = gu.to_f64(gu.run_blast(X, lay, flags, packed=(mode in ("packed", "fused12"))))
     Yref = oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64)
     err = gu.rel_err(Y, Yref)
     print(f"blast {T}x{n_in}->{n_out} b={b} r={r} {dtype} {mode}: rel err {err:.3e}")
