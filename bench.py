@@ -233,14 +233,15 @@ def run_sweep(steps, warmup):
             sa = layer.shape_args()
             mem, mfma = rf.floors(cfg["op"], T, **sa)
             dmem, dmfma = rf.floors("dense", T, cfg["n_in"], cfg["n_out"])
-            ms_alt = None
-            if cfg["op"] == "blast" and st is not None:     # the other BLAST variant: stage 1 + coupling fused in one kernel
-                ws_alt = torch.empty(max(B.blast_workspace_bytes(T, cfg["n_in"], cfg["n_out"], cfg["b"], cfg["r"], B.BF16,
-                                                                 layer.flags | B.BLAST_FUSED_STAGE12), 16), dtype=torch.uint8, device="cuda")
-                mk = lambda: B.prepared(B.blast_forward, layer.X, layer.U, None, layer.packed, layer.Y, layer.b, layer.r,
-                                        layer.flags | B.BLAST_FUSED_STAGE12, ws_alt)
-                ms_alt = time_graph(mk, steps, warmup)
-            row = {"config": name, "op": cfg["op"], "T": T, "ms": ms, "ms_fused_stage12": ms_alt, "tokens_per_s": T / (ms * 1e-3),
+            ms_alt = {}
+            if cfg["op"] == "blast" and st is not None:     # both executions for large ranks, forced
+                for key, fl in (("fused_stage12", B.BLAST_FUSED_STAGE12), ("three_kernels", B.BLAST_THREE_KERNELS)):
+                    ws_alt = torch.empty(max(B.blast_workspace_bytes(T, cfg["n_in"], cfg["n_out"], cfg["b"], cfg["r"], B.BF16,
+                                                                     layer.flags | fl), 16), dtype=torch.uint8, device="cuda")
+                    mk = lambda: B.prepared(B.blast_forward, layer.X, layer.U, None, layer.packed, layer.Y, layer.b, layer.r,
+                                            layer.flags | fl, ws_alt)
+                    ms_alt[key] = time_graph(mk, steps, warmup)
+            row = {"config": name, "op": cfg["op"], "T": T, "ms": ms, "ms_variants": ms_alt, "tokens_per_s": T / (ms * 1e-3),
                    "stage_ms": st, "floor_hbm_us": mem * 1e6, "floor_mfma_us": mfma * 1e6,
                    "bound": "hbm" if mem >= mfma else "mfma", "frac_of_floor": max(mem, mfma) / (ms * 1e-3),
                    "dense_ms": ms_dense, "dense_frac_of_floor": max(dmem, dmfma) / (ms_dense * 1e-3),
@@ -249,7 +250,7 @@ def run_sweep(steps, warmup):
             log(f"{name:4s} {cfg['op']:7s} T={T:5d}  {ms*1e3:9.1f} us  stages={None if st is None else [round(x*1e3,1) for x in st]}  "
                 f"floor {max(mem, mfma)*1e6:7.1f} us ({row['bound']}) frac {row['frac_of_floor']:.3f} | "
                 f"dense {ms_dense*1e3:9.1f} us frac {row['dense_frac_of_floor']:.3f} | speedup {row['speedup_vs_dense']:.2f}x"
-                + (f" | fused12 {ms_alt*1e3:.1f} us" if ms_alt else ""))
+                + "".join(f" | {k} {v*1e3:.1f} us" for k, v in ms_alt.items()))
             del layer, Yd
         del W
         torch.cuda.empty_cache()

@@ -62,11 +62,14 @@ typedef void* blr_stream;      /* a hipStream_t */
  * several chunks the workspace holds one chunk only, so LAST is then good for timing, not for values. */
 #define BLR_ONLY_FIRST_STAGE        0x200u
 #define BLR_ONLY_LAST_STAGE         0x400u
-/* flag of blr_blast_forward: where the layer is too large for the single-kernel path, fuse stage 1
- * and the coupling in one kernel (Z stays in LDS; the paper's optimisation 4 with the coupling on
- * the matrix cores) instead of the default three kernels over cache-resident token chunks (the
- * paper's optimisation 5). Both are kept so that the benchmark can show which wins per shape. */
+/* flags of blr_blast_forward for layers too large for the single-kernel path. Two executions exist:
+ * (a) stage 1 and the coupling fused in one kernel (Z stays on chip; the paper's optimisation 4 with
+ * the coupling on the matrix cores) followed by the stage-3 GEMM, and (b) three kernels over
+ * cache-resident token chunks (the paper's optimisation 5). By default the library picks (a) when
+ * the call has enough 128-token x 64-rank tiles to fill the chip and (b) otherwise; these flags
+ * force one of them (mutually exclusive) so that tests and the benchmark can run both. */
 #define BLR_BLAST_FUSED_STAGE12     0x800u
+#define BLR_BLAST_THREE_KERNELS     0x1000u
 
 /*
  * Monarch forward (paper Section 2.1 "Monarch"; Section 4 "Monarch", optimisations 1-3).

@@ -21,6 +21,7 @@ F32, BF16 = 0, 1
 MONARCH_OUT_INTERLEAVED, MONARCH_OUT_BLOCKED, BLAST_PACKED, FORCE_GENERIC = 0, 1, 2, 0x100
 ONLY_FIRST_STAGE, ONLY_LAST_STAGE = 0x200, 0x400
 BLAST_FUSED_STAGE12 = 0x800
+BLAST_THREE_KERNELS = 0x1000
 
 EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forward",
            "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_bytes",

@@ -1,11 +1,13 @@
 // BLAST stage 1 + coupling fused in one kernel (bf16 MFMA, gfx950).
 //
-// A workgroup owns a tile of TN tokens x TR rank indices. It loops over the input blocks j inside
+// A workgroup owns a tile of 128 tokens x 64 rank indices. It loops over the input blocks j inside
 // the workgroup (the reduction over j cannot be split across workgroups): for each j the tile
-// Z_j = X_j V_j is a small GEMM on v_mfma_f32_32x32x16_bf16, whose result is rounded to bf16 and
-// parked in LDS as Zs[rho][t][j]. When all j are done, the coupling A[t][i][rho] = sum_j S[i][j][rho]
-// Z[t][j][rho] is, for every rho, a (tokens x 16) . (16 x 16) product: one v_mfma_f32_16x16x16_bf16
-// per 16 tokens, with the per-rho 16x16 tile of S read from the packed tensor Sp[rho][i][j].
+// Z_j = X_j V_j is a small GEMM on v_mfma_f32_32x32x16_bf16 whose operands stream from global memory
+// straight into LDS (global_load_lds, no staging registers), and whose result is rounded to bf16 and
+// kept in registers. When all j are done the tile goes through LDS as Zs[rho][t][j], 64 tokens at a
+// time, and the coupling A[t][i][rho] = sum_j S[i][j][rho] Z[t][j][rho] is, for every rho, a
+// (tokens x 16) . (16 x 16) product: one v_mfma_f32_16x16x16_bf16 per 16 tokens, with the per-rho
+// 16x16 tile of S read from the packed tensor Sp[rho][i][j].
 // Z never leaves the chip and the coupling runs on the matrix cores; only A goes to HBM.
 #include "blr_common.h"
 
@@ -17,16 +19,29 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
-constexpr int TN = 64, TR = 64, BK = 32;
-constexpr int D = 8;                         // steps of global loads kept in flight (even)
+constexpr int TN = 64, TR = 64;              // the coupling works on 64 tokens x 64 rank indices at a time
 constexpr int ZSTR = TN * 32 + 8;            // bytes of one rho row of Zs: TN tokens x 16 j x 2 B, + 8 B pad
 constexpr int ZS_BYTES = TR * ZSTR;
-constexpr int STR = BK * 2 + 16;             // staged operand row stride (bytes)
-constexpr int STAGE = (TN + TR) * STR;
-constexpr int LDS_BYTES = ZS_BYTES + 2 * STAGE;
-static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
-static_assert(D % 2 == 0, "ring slot parity must equal LDS stage parity");
 static_assert(ZS_BYTES % 16 == 0, "Zs is cleared with 16-byte stores");
+
+// stage 1 of the fused kernel: 128 tokens x 64 ranks per workgroup, 8 wavefronts of 32 x 32
+constexpr int ST_TT = 128;                   // tokens per workgroup
+constexpr int ST_BK = 64;                    // k elements per step: operand rows of 128 bytes = 8 pieces of 16 bytes
+constexpr int ST_ROWS = ST_TT + TR;          // operand rows of one stage: X rows, then Vt rows
+constexpr int ST_STAGE = ST_ROWS * ST_BK * 2;
+constexpr int ST_NS = 6;                     // stages in LDS
+constexpr int ST_PD = ST_NS - 1;             // steps of loads in flight
+constexpr int ST_LDS = ST_NS * ST_STAGE > ZS_BYTES ? ST_NS * ST_STAGE : ZS_BYTES;
+static_assert(ST_LDS <= 160 * 1024, "LDS budget");
+static_assert(ST_ROWS % 64 == 0, "every wavefront issues the same number of loads per stage");
+constexpr int ST_LPW = ST_ROWS / 64;         // direct-to-LDS loads per wavefront and stage (8 rows each)
+static_assert(ST_LPW * (ST_PD - 1) < 64, "vmcnt range");
+
+#define BLR_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define BLR_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+// 16 zero bytes in global memory: the source of operand pieces that lie past the end of a block
+__device__ __attribute__((aligned(16))) const unsigned char zero_piece[16] = {0};
 
 // workgroup id -> logical tile id such that each XCD (workgroups are dealt round-robin over 8 XCDs)
 // works on a contiguous range of logical ids, i.e. shares its X tiles in its own L2
@@ -38,54 +53,64 @@ __device__ inline int xcd_contiguous(int bid, int nblk) {
 
 // Coupling of one 64-token x 64-rank tile whose Z values sit in LDS as Zs[rho][t][j] (bf16):
 // A[t][i][rho] = sum_j S[i][j][rho] Z[t][j][rho] on v_mfma_f32_16x16x16_bf16, one MFMA per rank index
-// and 16 tokens, S tiles from the packed Sp[rho][i][j]. Each wavefront takes two groups of 8 rank
-// indices; a group's result replaces the group's own Z rows IN PLACE as As[i][t][8 rho] (the group is
-// read completely first and only this wavefront touches it), so that A leaves with full-line stores.
-// Must be entered after a barrier that follows the last write to Zs.
-__device__ __forceinline__ void couple_tile_and_store(unsigned char* Zs, const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
-                                             int64_t T, int64_t t0, int rho0, int b, int r) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ci = lane & 15, cg = lane >> 4;
-    constexpr int GROUP = 8 * ZSTR;
-    static_assert(16 * TN * 16 <= GROUP, "in-place A must fit in the rows it replaces");
-#pragma unroll 1
-    for (int cc = 0; cc < 2; ++cc) {
-        const int c = wave * 2 + cc;
-        unsigned char* grp = Zs + c * GROUP;
-        s16x4 sfrag[8];
+// and 16 tokens, S tiles from the packed Sp[rho][i][j]. The 64 rank indices form 8 groups of 8; a
+// group's result replaces the group's own Z rows IN PLACE as As[i][t][8 rho] (the group is read
+// completely first and only one wavefront touches it), so that A leaves with full-line stores.
+constexpr int GROUP = 8 * ZSTR;
+static_assert(16 * TN * 16 <= GROUP, "in-place A must fit in the rows it replaces");
+
+// the S tiles of group c as MFMA B operands (lane: output block i = lane % 16, input blocks 4 (lane / 16) ..)
+__device__ __forceinline__ void load_s_group(const bf16_t* __restrict__ Sp, int rho0, int c, int r, s16x4 (&sfrag)[8]) {
+    const int lane = threadIdx.x & 63, ci = lane & 15, cg = lane >> 4;
 #pragma unroll
-        for (int ri = 0; ri < 8; ++ri) {
-            int rg = rho0 + c * 8 + ri;
-            if (rg > r - 1) rg = r - 1;                 // groups past r are computed on repeated tiles and not stored
-            sfrag[ri] = *(const s16x4*)(Sp + (int64_t)rg * 256 + ci * 16 + cg * 4);
-        }
-        f32x4 d[TN / 16][8];
-#pragma unroll
-        for (int ri = 0; ri < 8; ++ri)
-#pragma unroll
-            for (int tg = 0; tg < TN / 16; ++tg) {
-                const s16x4 a = *(const s16x4*)(grp + ri * ZSTR + (tg * 16 + ci) * 32 + cg * 8);
-                d[tg][ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, sfrag[ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-            }
-        // d[tg][ri][e]: token tg*16 + 4*(lane/16) + e, output block i = lane%16
-#pragma unroll
-        for (int tg = 0; tg < TN / 16; ++tg)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int tok = tg * 16 + 4 * cg + e;
-                *(uint4*)(grp + (ci * TN + (tok ^ (ci & 7))) * 16) =
-                    make_uint4(pack2_bf16(d[tg][0][e], d[tg][1][e]), pack2_bf16(d[tg][2][e], d[tg][3][e]),
-                               pack2_bf16(d[tg][4][e], d[tg][5][e]), pack2_bf16(d[tg][6][e], d[tg][7][e]));
-            }
+    for (int ri = 0; ri < 8; ++ri) {
+        int rg = rho0 + c * 8 + ri;
+        if (rg > r - 1) rg = r - 1;                     // groups past r are computed on repeated tiles and not stored
+        sfrag[ri] = *(const s16x4*)(Sp + (int64_t)rg * 256 + ci * 16 + cg * 4);
     }
-    __syncthreads();
-    // A[t][i][rho0 .. rho0+63]: 8 lanes write the 128 contiguous bytes of one (token, block)
-    for (int id = tid; id < TN * b * 8; id += 256) {
-        const int c8 = id & 7;
-        const int i = (id >> 3) % b;
-        const int t = (id >> 3) / b;
-        if (t0 + t < T && rho0 + c8 * 8 < r)
-            *(uint4*)(A + ((t0 + t) * b + i) * r + rho0 + c8 * 8) = *(const uint4*)(Zs + c8 * GROUP + (i * TN + (t ^ (i & 7))) * 16);
+}
+
+// Must be entered after a barrier that follows the last write to Zs.
+__device__ __forceinline__ void couple_group(unsigned char* grp, const s16x4 (&sfrag)[8]) {
+    const int lane = threadIdx.x & 63, ci = lane & 15, cg = lane >> 4;
+    f32x4 d[TN / 16][8];
+#pragma unroll
+    for (int ri = 0; ri < 8; ++ri)
+#pragma unroll
+        for (int tg = 0; tg < TN / 16; ++tg) {
+            const s16x4 a = *(const s16x4*)(grp + ri * ZSTR + (tg * 16 + ci) * 32 + cg * 8);
+            d[tg][ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, sfrag[ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        }
+    // d[tg][ri][e]: token tg*16 + 4*(lane/16) + e, output block i = lane%16
+#pragma unroll
+    for (int tg = 0; tg < TN / 16; ++tg)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int tok = tg * 16 + 4 * cg + e;
+            *(uint4*)(grp + (ci * TN + (tok ^ (ci & 7))) * 16) =
+                make_uint4(pack2_bf16(d[tg][0][e], d[tg][1][e]), pack2_bf16(d[tg][2][e], d[tg][3][e]),
+                           pack2_bf16(d[tg][4][e], d[tg][5][e]), pack2_bf16(d[tg][6][e], d[tg][7][e]));
+        }
+}
+
+// A[t][i][rho0 .. rho0+63] from the in-place groups: 8 lanes write the 128 contiguous bytes of one
+// (token, block). tok(t) is the token (relative to t0) that row t of the tile stands for.
+// Must be entered after a barrier that follows couple_group.
+template <int NW, class TokMap>                        // NW wavefronts in the workgroup
+__device__ __forceinline__ void store_a_tile(const unsigned char* Zs, bf16_t* __restrict__ A,
+                                             int64_t T, int64_t t0, int rho0, int b, int r, TokMap tok) {
+    const int tid = threadIdx.x, c8 = tid & 7;
+    constexpr int PER = NW * 8;                         // (token, block) items per sweep of the workgroup
+    const int di = PER % b, dt = PER / b;
+    int v = tid >> 3, i = v % b, t = v / b;
+    const bool rho_ok = rho0 + c8 * 8 < r;
+    const unsigned char* src = Zs + c8 * GROUP;
+    for (; v < TN * b; v += PER) {
+        const int64_t tg = t0 + tok(t);
+        if (tg < T && rho_ok)
+            *(uint4*)(A + (tg * b + i) * r + rho0 + c8 * 8) = *(const uint4*)(src + (i * TN + (t ^ (i & 7))) * 16);
+        i += di; t += dt;
+        if (i >= b) { i -= b; ++t; }
     }
 }
 
@@ -143,121 +168,170 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
         }
     }
     __syncthreads();
-    couple_tile_and_store(Zs, Sp, A, T, t0, rho0, b, r);
+#pragma unroll 1
+    for (int cc = 0; cc < 2; ++cc) {                    // 4 wavefronts, 2 groups each
+        const int c = (tid >> 6) * 2 + cc;
+        s16x4 sfrag[8];
+        load_s_group(Sp, rho0, c, r, sfrag);
+        couple_group(Zs + c * GROUP, sfrag);
+    }
+    __syncthreads();
+    store_a_tile<4>(Zs, A, T, t0, rho0, b, r, [](int t) { return t; });
 }
 
-// Round a finished Z_j accumulator tile to bf16 and park it in LDS (column j of Zs[rho][t][j]).
-// Deliberately not inlined: inlined, the compiler hoists the accumulator reads and conversions out of
-// the once-per-block branch into every step of the main loop.
-__device__ __noinline__ void park_z_tile(unsigned char* zcol, f32x16 acc) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) *(bf16_t*)(zcol + (8 * (e / 4) + (e % 4)) * 32) = float_to_bf16(acc[e]);
-}
-
-// TAIL: q is not a multiple of BK, i.e. the last k-chunk of every input block is partial.
+// Stage 1 + coupling. Per step (one 64-wide k chunk of one input block j) a stage of LDS holds 128
+// X rows and 64 Vt rows of 128 bytes; its 16-byte pieces are XOR-swizzled by (row / 2) & 7 so that the
+// 16 lanes a ds_read_b128 serves per clock (16 consecutive rows) hit 16 different 16-byte columns of
+// the 64 banks, without the row padding that a direct-to-LDS load cannot produce (lane l of such a
+// load always lands at base + 16 l). Loads for step s + ST_PD are issued while
+// step s computes; vmcnt counts them, so one wait + one barrier per step is all the synchronisation.
+// The fragment reads are inline assembly with their own lgkmcnt waits: reads that the compiler can
+// see make it wait for ALL outstanding direct-to-LDS loads first.
+// TAIL: q is not a multiple of 64, i.e. the last k chunk of every input block is partial.
 template <bool TAIL>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(512)
 void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Vt,
                           const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
                           int64_t T, int n_in, int b, int r, int tiles_r, int nblk) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* Zs = smem;
-    unsigned char* stg = smem + ZS_BYTES;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;            // token quarter, rank half of this wavefront's 32 x 32
     const int logical = xcd_contiguous(blockIdx.x, nblk);
     const int tile_t = logical / tiles_r, tile_r = logical % tiles_r;
-    const int64_t t0 = (int64_t)tile_t * TN;
+    const int64_t t0 = (int64_t)tile_t * ST_TT;
     const int rho0 = tile_r * TR;
     const int q = n_in / b;
-    const int nkc = (q + BK - 1) / BK;
+    const int nkc = (q + ST_BK - 1) / ST_BK;
     const int nsteps = b * nkc;
 
-    // Addresses = a uniform running base (advanced with scalar arithmetic once per step) plus a
-    // per-thread byte offset that never changes: the main loop spends almost nothing on indexing.
-    const int lrow = tid >> 2, lchunk = tid & 3;
-    int xr = lrow;
-    if (t0 + xr > T - 1) xr = (int)(T - 1 - t0);        // rows past the end re-read the last row; never stored
-    int vr = rho0 + lrow;
-    if (vr > r - 1) vr = r - 1;
-    const int xoff = (xr * n_in + lchunk * 8) * 2;      // bytes from the tile's first X row
-    const int voff = (vr * q + lchunk * 8) * 2;         // bytes from Vt[j]
+    // Load h of this wavefront fills operand rows 8 (ST_LPW wave + h) .. + 7 of a stage: lane l brings
+    // the piece that belongs at row l / 8 of those, slot l % 8.
+    int off[ST_LPW];
+    bool bad[ST_LPW];
+#pragma unroll
+    for (int h = 0; h < ST_LPW; ++h) {
+        const int row = 8 * (ST_LPW * wave + h) + (lane >> 3);
+        const int piece = (lane & 7) ^ ((row >> 1) & 7);
+        if (row < ST_TT) {
+            int xr = row;
+            if (t0 + xr > T - 1) xr = (int)(T - 1 - t0);    // rows past the end re-read the last row; never stored
+            off[h] = (xr * n_in + piece * 8) * 2;           // bytes from the tile's first X row
+        } else {
+            int vr = rho0 + row - ST_TT;
+            if (vr > r - 1) vr = r - 1;
+            off[h] = (vr * q + piece * 8) * 2;              // bytes from Vt[j]
+        }
+        bad[h] = TAIL && (nkc - 1) * ST_BK + piece * 8 >= q;   // in a block's last chunk this piece lies past q
+    }
     const unsigned char* xs = (const unsigned char*)(X + t0 * n_in);
     const unsigned char* vs = (const unsigned char*)Vt;
-    // in the last chunk of a block, 16-byte pieces at or past q re-read the last valid piece and are zeroed in LDS
-    const int last_k = (nkc - 1) * BK + lchunk * 8;
-    const bool tail_bad = TAIL && last_k >= q;
-    const int tail_fix = tail_bad ? (q - 8 - last_k) * 2 : 0;
-    const int x_wrap = (q - (nkc - 1) * BK) * 2;                        // last chunk of block j -> first chunk of j+1
-    const int64_t v_wrap = ((int64_t)r * q - (int64_t)(nkc - 1) * BK) * 2;
+    const int x_wrap = (q - (nkc - 1) * ST_BK) * 2;                        // last chunk of block j -> first chunk of j+1
+    const int64_t v_wrap = ((int64_t)r * q - (int64_t)(nkc - 1) * ST_BK) * 2;
 
-    if (b < 16)                                         // unused j slots must read as zero in the coupling
-        for (int i = tid * 16; i < ZS_BYTES; i += 256 * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
-
-    // register ring of D steps of global loads in flight (as in the GEMM kernel); a step is (j, kc)
-    uint4 ra[D], rb[D];
     int pk = 0, fetched = 0;                            // fetch cursor (uniform)
-    auto gload = [&](auto SLOT) {
-        constexpr int slot = decltype(SLOT)::value;
-        const int fix = (TAIL && pk == nkc - 1) ? tail_fix : 0;
-        ra[slot] = *(const uint4*)(xs + (xoff + fix));
-        rb[slot] = *(const uint4*)(vs + (voff + fix));
-        if (fetched < nsteps - 1) {                     // the cursor stops at the last step; later fetches repeat it
+    auto issue = [&](int stage_off) {
+        const bool lastc = TAIL && pk == nkc - 1;
+#pragma unroll
+        for (int h = 0; h < ST_LPW; ++h) {
+            const bool isx = 8 * (ST_LPW * wave + h) < ST_TT;              // uniform
+            const unsigned char* p = (isx ? xs : vs) + off[h];
+            if (TAIL) p = (lastc && bad[h]) ? zero_piece : p;
+            __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (ST_LPW * wave + h) * 1024), 16, 0, 0);
+        }
+        if (fetched < nsteps - 1) {                     // the cursor stops at the last step; later issues repeat it
             ++fetched;
             if (pk == nkc - 1) { pk = 0; xs += x_wrap; vs += v_wrap; }
-            else { ++pk; xs += BK * 2; vs += BK * 2; }
+            else { ++pk; xs += ST_BK * 2; vs += ST_BK * 2; }
         }
     };
-    auto sstore = [&](auto SLOT, bool last_chunk) {
-        constexpr int slot = decltype(SLOT)::value;
-        constexpr int stage = slot & 1;                 // D is even: slot parity == step parity
-        unsigned char* base = stg + stage * STAGE;
-        const bool ok = !(TAIL && last_chunk && tail_bad);
-        *(uint4*)(base + lrow * STR + lchunk * 16) = TAIL ? keep_if(ok, ra[slot]) : ra[slot];
-        *(uint4*)(base + TN * STR + lrow * STR + lchunk * 16) = TAIL ? keep_if(ok, rb[slot]) : rb[slot];
+
+    // fragment addresses inside a stage: row m of this wavefront's 32 tokens (resp. ranks), k group kg
+    const int m = lane & 31, kg = lane >> 5;
+    const unsigned lds0 = (unsigned)(uintptr_t)BLR_LPTR(smem);
+    unsigned fa[ST_BK / 16], fb[ST_BK / 16];
+#pragma unroll
+    for (int ks = 0; ks < ST_BK / 16; ++ks) {
+        const unsigned sw = (unsigned)(((2 * ks + kg) ^ ((m >> 1) & 7)) * 16);
+        fa[ks] = lds0 + (wm * 32 + m) * (ST_BK * 2) + sw;
+        fb[ks] = lds0 + (ST_TT + wn * 32 + m) * (ST_BK * 2) + sw;
+    }
+
+    int cstage = 0, istage = ST_PD * ST_STAGE;          // byte offsets of the stage to compute on / to refill
+    auto step = [&](f32x16& acc) {
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(ST_LPW * (ST_PD - 1)) : "memory");
+        issue(istage);                                  // the stage every wavefront finished reading one step ago
+        bf16x8 af[ST_BK / 16], bfr[ST_BK / 16];
+#pragma unroll
+        for (int ks = 0; ks < ST_BK / 16; ++ks) {
+            asm volatile("ds_read_b128 %0, %1" : "=v"(af[ks]) : "v"(fa[ks] + cstage) : "memory");
+            asm volatile("ds_read_b128 %0, %1" : "=v"(bfr[ks]) : "v"(fb[ks] + cstage) : "memory");
+        }
+        static_assert(ST_BK / 16 == 4, "the waits below are written for four fragment pairs");
+        asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(af[0]), "+v"(bfr[0]) :: "memory");
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0], bfr[0], acc, 0, 0, 0);
+        asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(af[1]), "+v"(bfr[1]) :: "memory");
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1], bfr[1], acc, 0, 0, 0);
+        asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(af[2]), "+v"(bfr[2]) :: "memory");
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[2], bfr[2], acc, 0, 0, 0);
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[3]), "+v"(bfr[3]) :: "memory");
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[3], bfr[3], acc, 0, 0, 0);
+        cstage = cstage + ST_STAGE == ST_NS * ST_STAGE ? 0 : cstage + ST_STAGE;
+        istage = istage + ST_STAGE == ST_NS * ST_STAGE ? 0 : istage + ST_STAGE;
     };
 
-    f32x16 acc;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    for (int s = 0; s < ST_PD; ++s) issue(s * ST_STAGE);
 
-    const int frag_off = (lane & 31) * STR + (lane >> 5) * 16;
-    // accumulator element e is token 8*(e/4) + 4*(lane/32) + e%4, rank index lane%32 of this wavefront's quadrant
-    unsigned char* zbase = Zs + (wn * 32 + (lane & 31)) * ZSTR + (wm * 32 + 4 * (lane >> 5)) * 32;
-    int j = 0, kc = 0;                                  // cursor of the step being computed
-    auto step = [&](auto U) {                           // u = step % D, a compile-time constant
-        constexpr int u = decltype(U)::value;
-        const unsigned char* As = stg + (u & 1) * STAGE + (wm * 32) * STR + frag_off;
-        const unsigned char* Bs = stg + (u & 1) * STAGE + TN * STR + (wn * 32) * STR + frag_off;
-        const bf16x8 a0 = *(const bf16x8*)As, a1 = *(const bf16x8*)(As + 32);
-        const bf16x8 b0 = *(const bf16x8*)Bs, b1 = *(const bf16x8*)(Bs + 32);
-        // the next step's operands go to the other LDS stage and the ring is refilled while the
-        // fragment reads above are in flight; the MFMAs below then run into the next step's reads
-        const bool last_kc = (kc == nkc - 1);
-        const int kc_next = last_kc ? 0 : kc + 1;
-        sstore(std::integral_constant<int, (u + 1) % D>{}, kc_next == nkc - 1);   // past the last step this writes the unused stage
-        gload(std::integral_constant<int, (u + 1) % D>{});
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc, 0, 0, 0);
-        if (__builtin_expect(last_kc, 0)) {             // out of line: nothing of it runs in the other steps
-            park_z_tile(zbase + j * 2, acc);
+    // Z of the whole tile, bf16, in registers: zq[e][jp] = (Z_{2jp}, Z_{2jp+1}) of accumulator element e,
+    // i.e. token 8 (e/4) + 4 (lane/32) + e%4 and rank lane%32 of this wavefront's 32 x 32
+    uint32_t zq[16][8];
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+#pragma unroll
+        for (int jp = 0; jp < 8; ++jp) zq[e][jp] = 0u;  // blocks past b stay zero
+    static_for<8>([&](auto JP) {
+        constexpr int jp = decltype(JP)::value;
+        if (2 * jp < b) {
+            f32x16 acc;
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll 1
+            for (int kc = 0; kc < nkc; ++kc) step(acc);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { zq[e][jp] = pack2_bf16(acc[e], 0.f); acc[e] = 0.f; }
+            if (2 * jp + 1 < b) {
+#pragma unroll 1
+                for (int kc = 0; kc < nkc; ++kc) step(acc);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) zq[e][jp] |= pack2_bf16(0.f, acc[e]);
+            }
         }
-        __syncthreads();
-        kc = kc_next;
-        if (last_kc) ++j;
-    };
+    });
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the repeated loads of the last steps have landed too
 
-    static_for<D>([&](auto U) { gload(U); });
-    sstore(std::integral_constant<int, 0>{}, nkc == 1);
-    gload(std::integral_constant<int, 0>{});
-    __syncthreads();
-    int s0 = 0;
-    for (; s0 + D <= nsteps; s0 += D) static_for<D>([&](auto U) { step(U); });
-    static_for<D - 1>([&](auto U) { if (s0 + decltype(U)::value < nsteps) step(U); });
-
-    couple_tile_and_store(Zs, Sp, A, T, t0, rho0, b, r);
+    // coupling, 64 tokens at a time: pass hf takes tokens 16 hf .. 16 hf + 15 of every wavefront's 32 (so
+    // that each wavefront hands over half of its registers per pass) and lays them out as Zs[rho][t][j];
+    // wavefront w then couples the 8 rank indices of group w
+    unsigned char* Zs = smem;
+    s16x4 sfrag[8];
+    load_s_group(Sp, rho0, wave, r, sfrag);             // in flight across the barrier and the Zs writes
+    static_for<2>([&](auto HF) {
+        constexpr int hf = decltype(HF)::value;
+        if (hf == 0 || T - t0 > 16) {                   // uniform
+            __syncthreads();                            // stages / the previous pass's A are no longer read
+            unsigned char* zrow = Zs + (wn * 32 + m) * ZSTR + (wm * 16 + 4 * kg) * 32;
+#pragma unroll
+            for (int e2 = 0; e2 < 8; ++e2) {
+                unsigned char* dst = zrow + (8 * (e2 / 4) + (e2 % 4)) * 32;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) *(uint2*)(dst + v * 8) = make_uint2(zq[8 * hf + e2][2 * v], zq[8 * hf + e2][2 * v + 1]);
+            }
+            __syncthreads();
+            couple_group(Zs + wave * GROUP, sfrag);
+            __syncthreads();
+            store_a_tile<8>(Zs, A, T, t0, rho0, b, r, [](int t) { return (t >> 4) * 32 + hf * 16 + (t & 15); });
+        }
+    });
 }
 
 }  // namespace
@@ -265,27 +339,29 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
 bool blast_fused_supported(int64_t T, int n_in, int b, int r) {
     if (T <= 0 || b <= 0 || b > 16 || n_in % b) return false;
     const int q = n_in / b;
-    const int64_t nblk = ((T + TN - 1) / TN) * ((r + TR - 1) / TR);
+    const int64_t nblk = blast_fused_tiles(T, r);
     return q % 8 == 0 && r % 8 == 0 && nblk < (1ll << 30);
 }
+
+int64_t blast_fused_tiles(int64_t T, int r) { return ((T + ST_TT - 1) / ST_TT) * ((r + TR - 1) / TR); }
 
 hipError_t launch_blast_stage12(const void* X, const void* Vt, const void* Sp, void* A,
                                 int64_t T, int n_in, int b, int r, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)blast_stage12_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        e = hipFuncSetAttribute((const void*)blast_stage12_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles_t = (int)((T + TN - 1) / TN), tiles_r = (r + TR - 1) / TR;
+    const int tiles_t = (int)((T + ST_TT - 1) / ST_TT), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
-    if ((n_in / b) % BK)
-        hipLaunchKernelGGL(blast_stage12_kernel<true>, dim3((unsigned)nblk), dim3(256), LDS_BYTES, s,
+    if ((n_in / b) % ST_BK)
+        hipLaunchKernelGGL(blast_stage12_kernel<true>, dim3((unsigned)nblk), dim3(512), ST_LDS, s,
                            (const bf16_t*)X, (const bf16_t*)Vt, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r, tiles_r, nblk);
     else
-        hipLaunchKernelGGL(blast_stage12_kernel<false>, dim3((unsigned)nblk), dim3(256), LDS_BYTES, s,
+        hipLaunchKernelGGL(blast_stage12_kernel<false>, dim3((unsigned)nblk), dim3(512), ST_LDS, s,
                            (const bf16_t*)X, (const bf16_t*)Vt, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r, tiles_r, nblk);
     return hipGetLastError();
 }

@@ -58,6 +58,9 @@ struct BlastPlan {
 // two intermediates (Z and A, b*r bf16 per token each) together stay well inside the 256 MB
 // memory-side cache, so that they are produced and consumed without a round trip to HBM.
 constexpr size_t kChunkBytes = 48u << 20;
+// The fused stage 1 + coupling kernel runs one workgroup per compute unit; below this many tiles it
+// leaves too much of the chip idle and the three-kernel path (finer tiles) is faster.
+constexpr int64_t kFusedMinTiles = 128;
 
 BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
     BlastPlan pl{};
@@ -73,7 +76,8 @@ BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt,
         pl.off_Z = off; off += align_up((size_t)T * per_token);
     } else {
         if (blast_full_fusion_supported(T, n_in, n_out, b, r)) pl.path = BlastPlan::MFMA_FULL;
-        else if ((flags & BLR_BLAST_FUSED_STAGE12) && blast_fused_supported(T, n_in, b, r)) pl.path = BlastPlan::MFMA_STAGE12;
+        else if (!(flags & BLR_BLAST_THREE_KERNELS) && blast_fused_supported(T, n_in, b, r) &&
+                 ((flags & BLR_BLAST_FUSED_STAGE12) || blast_fused_tiles(T, r) >= kFusedMinTiles)) pl.path = BlastPlan::MFMA_STAGE12;
         else pl.path = BlastPlan::MFMA_THREE;
         if (pl.path == BlastPlan::MFMA_STAGE12) { pl.off_A = off; off += align_up((size_t)T * per_token); }
         if (pl.path == BlastPlan::MFMA_THREE) {
@@ -181,8 +185,9 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
                              void* workspace, size_t workspace_bytes, blr_stream stream) {
     if (!U || !V || (!S && !(flags & BLR_BLAST_PACKED))) return BLR_ERR_INVALID_ARG;
     if (!blast_shape_ok(T, n_in, n_out, b, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
-    if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_BLAST_FUSED_STAGE12)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_BLAST_FUSED_STAGE12 | BLR_BLAST_THREE_KERNELS)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_BLAST_FUSED_STAGE12) && (flags & BLR_BLAST_THREE_KERNELS)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_BLAST_PACKED) && (dt != BLR_BF16 || b > 16 || (flags & BLR_FORCE_GENERIC))) return BLR_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(U) || !aligned16(S) || !aligned16(V) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
     if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null

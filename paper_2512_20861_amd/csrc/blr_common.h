@@ -78,6 +78,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s);
 
 // BLAST: fused stage 1 + coupling on MFMA. X[T][n_in], Vt[b][r][q], Sp[r][16][16] -> A[T][b][r] (bf16)
 bool blast_fused_supported(int64_t T, int n_in, int b, int r);
+int64_t blast_fused_tiles(int64_t T, int r);                 // workgroups the fused stage 1 + coupling kernel would launch
 hipError_t launch_blast_stage12(const void* X, const void* Vt, const void* Sp, void* A,
                                 int64_t T, int n_in, int b, int r, hipStream_t s);
 // BLAST: stand-alone coupling on MFMA, Z[T][b][r] -> A[T][b][r] (bf16), S tiles from Sp[r][16][16]; needs r % 8 == 0, b <= 16

@@ -55,9 +55,12 @@ def test_workspace_sizes():
     # large ranks: Z and A of one chunk of tokens (three-kernel path), or A alone (fused stage 1 + coupling)
     assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 2 * 512 * 16 * 640 * 2
     assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED | B.BLAST_FUSED_STAGE12) == 512 * 16 * 640 * 2
+    # enough 128-token x 64-rank tiles (16 x 10 >= 128): the fused kernel is the default, A for all tokens
+    assert B.blast_workspace_bytes(2048, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 2048 * 16 * 640 * 2
+    assert B.blast_workspace_bytes(2048, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED | B.BLAST_THREE_KERNELS) == 2 * 2048 * 16 * 640 * 2
     # many tokens: the chunk (a multiple of 256 tokens whose Z and A are 48 MiB each at most) bounds the workspace
     chunk = (48 << 20) // (16 * 640 * 2) // 256 * 256
-    assert B.blast_workspace_bytes(100000, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 2 * chunk * 16 * 640 * 2
+    assert B.blast_workspace_bytes(100000, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED | B.BLAST_THREE_KERNELS) == 2 * chunk * 16 * 640 * 2
     # portable path keeps Z and A
     assert B.blast_workspace_bytes(50, 36, 30, 3, 10, B.F32, 0) == 2 * ((50 * 3 * 10 * 4 + 255) // 256 * 256)
     assert B.blast_packed_bytes(768, 768, 32, 96) == 0 and B.blast_packed_bytes(768, 768, 16, 96, B.F32) == 0
@@ -84,6 +87,8 @@ def test_monarch_argument_checks():
     assert _monarch(dt=7) == B.ERR_INVALID_ARG
     assert _monarch(flags=0x8000) == B.ERR_INVALID_ARG
     assert _monarch(flags=B.ONLY_FIRST_STAGE | B.ONLY_LAST_STAGE) == B.ERR_INVALID_ARG
+    assert _blast(flags=B.BLAST_FUSED_STAGE12 | B.BLAST_THREE_KERNELS) == B.ERR_INVALID_ARG
+    assert _monarch(flags=B.BLAST_THREE_KERNELS) == B.ERR_INVALID_ARG
     assert _monarch(X=FAKE + 2) == B.ERR_INVALID_ARG               # misaligned pointer
     assert _monarch(ws=None) == B.ERR_WORKSPACE
     assert _monarch(wsb=16) == B.ERR_WORKSPACE

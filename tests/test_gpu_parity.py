@@ -73,15 +73,15 @@ BLAST_CASES = [
 
 
 @pytest.mark.parametrize("T,n_in,n_out,b,r,dtype", BLAST_CASES)
-@pytest.mark.parametrize("mode", ["canonical", "packed", "generic", "fused12"])
+@pytest.mark.parametrize("mode", ["canonical", "packed", "generic", "fused12", "three"])
 def test_blast_parity(T, n_in, n_out, b, r, dtype, mode):
     gu = _gu()
-    if mode in ("packed", "fused12") and (dtype != "bf16" or (n_in // b) % 8 or r % 8):
+    if mode in ("packed", "fused12", "three") and (dtype != "bf16" or (n_in // b) % 8 or r % 8):
         pytest.skip("packed factors exist only for the bf16 MFMA path")
     lay = bi.blast_layer(n_in, n_out, b, r, dtype)
     X = bi.activations(T, n_in, dtype)
-    flags = {"generic": gu.B.FORCE_GENERIC, "fused12": gu.B.BLAST_FUSED_STAGE12}.get(mode, 0)
-    Y = gu.to_f64(gu.run_blast(X, lay, flags, packed=(mode in ("packed", "fused12"))))
+    flags = {"generic": gu.B.FORCE_GENERIC, "fused12": gu.B.BLAST_FUSED_STAGE12, "three": gu.B.BLAST_THREE_KERNELS}.get(mode, 0)
+    Y = gu.to_f64(gu.run_blast(X, lay, flags, packed=(mode in ("packed", "fused12", "three"))))
     Yref = oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64)
     err = gu.rel_err(Y, Yref)
     print(f"blast {T}x{n_in}->{n_out} b={b} r={r} {dtype} {mode}: rel err {err:.3e}")
