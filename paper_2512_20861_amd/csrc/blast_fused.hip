@@ -37,9 +37,6 @@ static_assert(ST_ROWS % 64 == 0, "every wavefront issues the same number of load
 constexpr int ST_LPW = ST_ROWS / 64;         // direct-to-LDS loads per wavefront and stage (8 rows each)
 static_assert(ST_LPW * (ST_PD - 1) < 64, "vmcnt range");
 
-#define BLR_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
-#define BLR_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
-
 // 16 zero bytes in global memory: the source of operand pieces that lie past the end of a block
 __device__ __attribute__((aligned(16))) const unsigned char zero_piece[16] = {0};
 

@@ -46,6 +46,11 @@ __device__ inline uint32_t pack2_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
+// pointer casts for __builtin_amdgcn_global_load_lds (global -> LDS without staging registers:
+// lane l of the wavefront deposits its 16 bytes at the wavefront-uniform LDS address + 16 l)
+#define BLR_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define BLR_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
+
 // value select (a ternary on two uint4 lvalues would select an address and force them into memory)
 __device__ inline uint4 keep_if(bool ok, uint4 v) {
     return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);

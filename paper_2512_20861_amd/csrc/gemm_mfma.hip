@@ -2,10 +2,8 @@
 //
 // A workgroup of WGM x WGN wavefronts owns a BM x BN output tile; each wavefront owns
 // (BM/WGM) x (BN/WGN) as a grid of 32x32 v_mfma_f32_32x32x16_bf16 tiles with fp32 accumulators.
-// Operand tiles (BM x BK of A, BN x BK of B, both with the contraction index contiguous) go
-// global -> registers -> LDS with 16-byte accesses, LDS double-buffered, one barrier per BK step,
-// with a register ring of D steps of global loads in flight. LDS rows are padded by 16 bytes so
-// that the 16-byte fragment reads of a wavefront fall into distinct banks.
+// Operand tiles (BM x 32 of A, BN x 32 of B, both with the contraction index contiguous) stream
+// global -> LDS directly (global_load_lds), four stages deep, one barrier per step.
 // The weight tile is the FIRST MFMA operand: an accumulator lane then holds four consecutive
 // output columns of one token, which go to an LDS copy of the C tile as 8-byte writes and from
 // there to global memory as 16-byte row-contiguous stores (or element-wise through the column map
@@ -21,47 +19,20 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-template <int BM, int BN, int BK, int WGM, int WGN>
-struct TileCfg {
-    static constexpr int THREADS = 64 * WGM * WGN;
-    static constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
-    static constexpr int RPP = THREADS / CPR;       // tile rows covered by one pass of the workgroup
-    static constexpr int NA = BM / RPP;             // passes for the A tile
-    static constexpr int NB = BN / RPP;             // passes for the B tile
-    static constexpr int STR = BK * 2 + 16;         // LDS row stride in bytes
-    static constexpr int A_BYTES = BM * STR;
-    static constexpr int B_BYTES = BN * STR;
-    static constexpr int STAGE = A_BYTES + B_BYTES;
-    static constexpr int CSTR = BN * 2 + 16;        // row stride of the staged C tile
-    static constexpr int C_BYTES = BM * CSTR;
-    static constexpr int LDS_BYTES = 2 * STAGE > C_BYTES ? 2 * STAGE : C_BYTES;
-    static constexpr int WTM = BM / WGM, WTN = BN / WGN;
-    static constexpr int MI = WTM / 32, NI = WTN / 32;
-    static_assert(NA >= 1 && NB >= 1 && MI >= 1 && NI >= 1, "tile too small");
-    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must be a multiple of one load pass");
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
-};
-
 __device__ inline int xcd_contiguous(int bid, int nblk) {
     const int q8 = nblk >> 3, rem = nblk & 7;
     const int xcd = bid & 7, slot = bid >> 3;
     return xcd * q8 + (xcd < rem ? xcd : rem) + slot;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int D>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int gfast) {
-    using C = TileCfg<BM, BN, BK, WGM, WGN>;
-    static_assert(D % 2 == 0, "the ring slot parity must equal the LDS stage parity");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-    // tile and batch index of this workgroup. With a scattering column map (gfast) the batch index
-    // varies fastest, so the G workgroups that interleave their columns into the same cache lines
-    // run side by side on one XCD and their partial-line writes merge in its L2.
+// Tile and batch index of this workgroup. Workgroup ids are remapped so that each XCD owns a
+// contiguous range of tiles, walked in groups of 8 row-tiles per column-tile. With a scattering
+// column map (gfast) the batch index varies fastest, so the G workgroups that interleave their
+// columns into the same cache lines run side by side on one XCD and their partial-line writes
+// merge in its L2.
+__device__ inline void workgroup_tile(const GemmDesc& d, int tiles_m, int tiles_n, int gfast, int& g, int& tile_m, int& tile_n) {
     constexpr int GM = 8;
-    int g, logical;
+    int logical;
     if (gfast) {
         const int lg = xcd_contiguous(blockIdx.x, tiles_m * tiles_n * d.G);
         g = lg % d.G;
@@ -74,58 +45,163 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmDesc d, i
     const int first_m = (logical / group_size) * GM;
     const int gm = tiles_m - first_m < GM ? tiles_m - first_m : GM;
     const int in_group = logical % group_size;
-    const int tile_m = first_m + in_group % gm;
-    const int tile_n = in_group / gm;
+    tile_m = first_m + in_group % gm;
+    tile_n = in_group / gm;
+}
+
+// Epilogue: accumulators -> bf16 C tile in LDS -> global memory. With the weight fragment as first
+// MFMA operand, accumulator element e of tile (i, j) is output column j*32 + 8*(e/4) + 4*(lane/32) + e%4
+// of token i*32 + lane%32: 8-byte LDS writes, then 16-byte row-contiguous stores (or element-wise
+// through the column map when the map scatters). Must be entered after a barrier that follows the
+// last read of the operand stages, which the C tile overwrites.
+template <int BM, int BN, int WTM, int WTN, int MI, int NI, int CSTR, int THREADS>
+__device__ __forceinline__ void store_c_tile(const GemmDesc& d, const f32x16 (&acc)[MI][NI], unsigned char* Cs,
+                                             int64_t m0, int n0, int g, int wm, int wn, int cvec) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    {
+        const int mrow = wm * WTM + (lane & 31);
+        const int ncol = wn * WTN + 4 * (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *(uint2*)(Cs + (mrow + i * 32) * CSTR + (ncol + j * 32 + 8 * q4) * 2) =
+                        make_uint2(pack2_bf16(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1]),
+                                   pack2_bf16(acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]));
+    }
+    __syncthreads();
+    bf16_t* Cp = (bf16_t*)d.C;
+    if (cvec) {
+        // groups of 8 consecutive columns map to 8 consecutive, 16-byte aligned elements of C
+        constexpr int CPRC = BN / 8;
+        for (int id = tid; id < BM * CPRC; id += THREADS) {
+            const int row = id / CPRC, cc = id % CPRC;
+            const int64_t m = m0 + row;
+            const int n = n0 + cc * 8;
+            if (m < d.M && n < d.N) {
+                const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
+                *(uint4*)(Cp + m * d.c_rs + col) = *(const uint4*)(Cs + row * CSTR + cc * 16);
+            }
+        }
+    } else {
+        for (int id = tid; id < BM * BN; id += THREADS) {
+            const int row = id / BN, nn = id % BN;
+            const int64_t m = m0 + row;
+            const int n = n0 + nn;
+            if (m < d.M && n < d.N) {
+                const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
+                Cp[m * d.c_rs + col] = *(const bf16_t*)(Cs + row * CSTR + nn * 2);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Operand tiles stream global -> LDS directly (global_load_lds): no staging registers and no LDS
+// store instructions, so the prefetch depth is set by LDS capacity (NS stages of BK = 32) instead of
+// by the register file. A stage holds BM A rows and BN B rows of 64 bytes = four
+// 16-byte pieces; a direct load lands lane l at base + 16 l, so rows cannot be padded and the pieces
+// are XOR-swizzled instead: piece c of row w sits in slot c ^ ((w >> 2) & 3), which puts the 16
+// rows that a ds_read_b128 serves per clock into 16 different 16-byte columns of the 64 banks.
+// Loads for step s + PD are issued when step s has been consumed and vmcnt counts them, so one wait
+// and one barrier per step is all the synchronisation. The fragment reads are inline assembly with their own
+// lgkmcnt waits: LDS reads that the compiler can see make it wait for ALL outstanding direct loads.
+// 16 zero bytes in global memory: the source of operand pieces that lie past K
+__device__ __attribute__((aligned(16))) const unsigned char zero_piece[16] = {0};
+
+// asynchronous 16-byte LDS read the compiler does not see as a memory access; the caller waits on
+// lgkmcnt itself and ties the result to that wait before using it
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
+
+template <int BM, int BN, int WGM, int WGN>
+struct DmaCfg {
+    static constexpr int BK = 32, NS = 4, PD = NS;   // stages in LDS = steps of loads in flight
+    static constexpr int WAVES = WGM * WGN, THREADS = 64 * WAVES;
+    static constexpr int ROWS = BM + BN;
+    static constexpr int STAGE = ROWS * BK * 2;
+    static constexpr int LPW = ROWS / 16 / WAVES;    // direct loads (16 rows each) per wavefront and stage
+    static constexpr int CSTR = BN * 2 + 16;
+    static constexpr int C_BYTES = BM * CSTR;
+    static constexpr int LDS_BYTES = NS * STAGE > C_BYTES ? NS * STAGE : C_BYTES;
+    static constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    static constexpr int MI = WTM / 32, NI = WTN / 32;
+    static_assert(ROWS % (16 * WAVES) == 0 && BM % 16 == 0, "whole direct loads per wavefront, none straddling A and B");
+    static_assert(PD >= 2 && MI >= 1 && NI >= 1 && LPW * (PD - 1) < 64, "tile / vmcnt range");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert((MI * 32 - 32) * 64 < 65536 && (NI * 32 - 32) * 64 < 65536, "fragment offsets are ds_read immediates");
+};
+
+// TAIL: K is not a multiple of 32, the last step is partial
+template <int BM, int BN, int WGM, int WGN, bool TAIL>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int gfast) {
+    using C = DmaCfg<BM, BN, WGM, WGN>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    int g, tile_m, tile_n;
+    workgroup_tile(d, tiles_m, tiles_n, gfast, g, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     const int n0 = tile_n * BN;
+    const unsigned char* Abase = (const unsigned char*)((const bf16_t*)d.A + (int64_t)g * d.a_gs + m0 * d.a_rs);
+    const unsigned char* Bbase = (const unsigned char*)((const bf16_t*)d.B + (int64_t)g * d.b_gs);
 
-    const bf16_t* Ag = (const bf16_t*)d.A + (int64_t)g * d.a_gs;
-    const bf16_t* Bg = (const bf16_t*)d.B + (int64_t)g * d.b_gs;
-
-    const int lrow = tid / C::CPR, lchunk = tid % C::CPR;
-    const bf16_t* ap[C::NA];
-    const bf16_t* bp[C::NB];
+    // Direct load h of this wavefront fills stage rows 16 (LPW wave + h) .. + 15 (A rows first, then B
+    // rows): lane l brings the piece that belongs at row l / 4 of those, slot l % 4. Offsets are bytes
+    // from Abase / Bbase (the launcher checks that they fit 32 bits).
+    unsigned off[C::LPW];
+    bool bad[C::LPW];
+    const int nk = (d.K + C::BK - 1) / C::BK;
 #pragma unroll
-    for (int i = 0; i < C::NA; ++i) {
-        int64_t m = m0 + lrow + i * C::RPP;
-        if (m > d.M - 1) m = d.M - 1;               // rows past the end re-read the last row; never stored
-        ap[i] = Ag + m * d.a_rs;
+    for (int h = 0; h < C::LPW; ++h) {
+        const int row = 16 * (C::LPW * wave + h) + (lane >> 2);
+        const int piece = (lane & 3) ^ ((row >> 2) & 3);
+        if (row < BM) {
+            int64_t m = row;
+            if (m0 + m > d.M - 1) m = d.M - 1 - m0;     // rows past the end re-read the last row; never stored
+            off[h] = (unsigned)((m * d.a_rs + piece * 8) * 2);
+        } else {
+            int n = n0 + row - BM;
+            if (n > d.N - 1) n = d.N - 1;
+            const int64_t nr = d.b_div ? (int64_t)(n % d.b_div) * d.b_mul + n / d.b_div : n;
+            off[h] = (unsigned)((nr * d.b_rs + piece * 8) * 2);
+        }
+        bad[h] = TAIL && (nk - 1) * C::BK + piece * 8 >= d.K;    // in the last step this piece lies past K
     }
+    int kf = 0;                                         // fetch cursor (uniform); stops at the last step
+    // loads H0 .. H1-1 of the step under the cursor; advance = this completes the step's loads
+    auto issue = [&](int stage_off, auto H0, auto H1, bool advance) {
+        const bool lastk = TAIL && kf == nk - 1;
 #pragma unroll
-    for (int i = 0; i < C::NB; ++i) {
-        int n = n0 + lrow + i * C::RPP;
-        if (n > d.N - 1) n = d.N - 1;
-        const int64_t nr = d.b_div ? (int64_t)(n % d.b_div) * d.b_mul + n / d.b_div : n;
-        bp[i] = Bg + nr * d.b_rs;
-    }
+        for (int h = decltype(H0)::value; h < decltype(H1)::value; ++h) {
+            const bool isa = 16 * (C::LPW * wave + h) < BM;                 // uniform
+            const unsigned char* p = (isa ? Abase : Bbase) + (size_t)kf * (C::BK * 2) + off[h];
+            if (TAIL) p = (lastk && bad[h]) ? zero_piece : p;
+            __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 0);
+        }
+        if (advance && kf < nk - 1) ++kf;
+    };
+    constexpr std::integral_constant<int, 0> L0{};
+    constexpr std::integral_constant<int, (C::LPW + 1) / 2> LH{};
+    constexpr std::integral_constant<int, C::LPW> LN{};
 
-    // Register ring: the global loads of steps s+1 .. s+D are in flight while step s is computed from
-    // LDS, so HBM/L2 latency is covered by D steps of MFMA work. Slots are indexed statically (the
-    // main loop is unrolled by D) and every load is unconditional (addresses are clamped, chunks past
-    // K are zeroed when they are written to LDS), so each wait counts only the loads older than the
-    // slot it needs instead of draining the queue.
-    const int nk = (d.K + BK - 1) / BK;
-    uint4 ra[D][C::NA], rb[D][C::NB];
-    auto gload = [&](auto SLOT, int kt) {
-        constexpr int slot = decltype(SLOT)::value;
-        if (kt > nk - 1) kt = nk - 1;               // steps past the end repeat the last one; never consumed
-        int k = kt * BK + lchunk * 8;
-        if (k > d.K - 8) k = d.K - 8;               // K is a multiple of 8
+    // fragment addresses inside a stage: row m of a 32-row MFMA operand, k group kg, k16 step ks
+    const int m = lane & 31, kg = lane >> 5;
+    const unsigned lds0 = (unsigned)(uintptr_t)BLR_LPTR(smem);
+    unsigned fa[2], fb[2];
 #pragma unroll
-        for (int i = 0; i < C::NA; ++i) ra[slot][i] = *(const uint4*)(ap[i] + k);
-#pragma unroll
-        for (int i = 0; i < C::NB; ++i) rb[slot][i] = *(const uint4*)(bp[i] + k);
-    };
-    auto sstore = [&](auto SLOT, int kt) {
-        constexpr int slot = decltype(SLOT)::value;
-        constexpr int stage = slot & 1;             // D is even: slot parity == step parity
-        unsigned char* base = smem + stage * C::STAGE;
-        const bool ok = (kt * BK + lchunk * 8) < d.K;
-#pragma unroll
-        for (int i = 0; i < C::NA; ++i) *(uint4*)(base + (lrow + i * C::RPP) * C::STR + lchunk * 16) = keep_if(ok, ra[slot][i]);
-#pragma unroll
-        for (int i = 0; i < C::NB; ++i) *(uint4*)(base + C::A_BYTES + (lrow + i * C::RPP) * C::STR + lchunk * 16) = keep_if(ok, rb[slot][i]);
-    };
+    for (int ks = 0; ks < 2; ++ks) {
+        const unsigned sw = (unsigned)(((2 * ks + kg) ^ ((m >> 2) & 3)) * 16);
+        fa[ks] = lds0 + (wm * C::WTM + m) * (C::BK * 2) + sw;
+        fb[ks] = lds0 + (BM + wn * C::WTN + m) * (C::BK * 2) + sw;
+    }
 
     f32x16 acc[C::MI][C::NI];
 #pragma unroll
@@ -135,79 +211,65 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmDesc d, i
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int frag_off = (lane & 31) * C::STR + (lane >> 5) * 16;
-    auto step = [&](auto U, int kt) {               // u = kt % D, a compile-time constant
-        constexpr int u = decltype(U)::value;
-        const unsigned char* As = smem + (u & 1) * C::STAGE + (wm * C::WTM) * C::STR + frag_off;
-        const unsigned char* Bs = smem + (u & 1) * C::STAGE + C::A_BYTES + (wn * C::WTN) * C::STR + frag_off;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[C::MI], bfr[C::NI];
-#pragma unroll
-            for (int i = 0; i < C::MI; ++i) af[i] = *(const bf16x8*)(As + i * 32 * C::STR + ks * 32);
-#pragma unroll
-            for (int j = 0; j < C::NI; ++j) bfr[j] = *(const bf16x8*)(Bs + j * 32 * C::STR + ks * 32);
-#pragma unroll
-            for (int i = 0; i < C::MI; ++i)
-#pragma unroll
-                for (int j = 0; j < C::NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-        }
-        sstore(std::integral_constant<int, (u + 1) % D>{}, kt + 1);   // past the last step this writes the unused stage
-        gload(std::integral_constant<int, (u + 1) % D>{}, kt + 1 + D);
-        __syncthreads();
+    // Software pipeline inside every wavefront: the fragment reads of one half step (k16 step) are in
+    // flight while the MFMAs of the previous half step run, so the LDS and the matrix cores overlap even
+    // though the barrier keeps all wavefronts of the workgroup in phase.
+    bf16x8 af[2][C::MI], bfr[2][C::NI];
+    auto read_frags = [&](auto KS, int stage_off) {
+        constexpr int ks = decltype(KS)::value;
+        const unsigned aa = fa[ks] + stage_off, ab = fb[ks] + stage_off;
+        static_for<C::MI>([&](auto I) { af[ks][decltype(I)::value] = lds_read_b128<decltype(I)::value * 32 * C::BK * 2>(aa); });
+        static_for<C::NI>([&](auto J) { bfr[ks][decltype(J)::value] = lds_read_b128<decltype(J)::value * 32 * C::BK * 2>(ab); });
     };
-
-    static_for<D>([&](auto U) { gload(U, decltype(U)::value); });
-    sstore(std::integral_constant<int, 0>{}, 0);
-    gload(std::integral_constant<int, 0>{}, D);
-    __syncthreads();
-    int kt0 = 0;
-    for (; kt0 + D <= nk; kt0 += D) static_for<D>([&](auto U) { step(U, kt0 + decltype(U)::value); });
-    static_for<D - 1>([&](auto U) { if (kt0 + decltype(U)::value < nk) step(U, kt0 + decltype(U)::value); });
-
-    // epilogue. Every step ends with a barrier, so the operand stages are dead here and the C tile may
-    // overwrite them. With the weight fragment as first operand, accumulator element e of tile (i, j)
-    // is output column j*32 + 8*(e/4) + 4*(lane/32) + e%4 of token i*32 + lane%32.
-    unsigned char* Cs = smem;
-    {
-        const int mrow = wm * C::WTM + (lane & 31);
-        const int ncol = wn * C::WTN + 4 * (lane >> 5);
+    auto mfma_half = [&](auto KS) {
+        constexpr int ks = decltype(KS)::value;
+        // tie the fragments to the preceding wait, so that no MFMA is scheduled above it
+#pragma unroll
+        for (int i = 0; i < C::MI; ++i) asm volatile("" : "+v"(af[ks][i]));
+#pragma unroll
+        for (int j = 0; j < C::NI; ++j) asm volatile("" : "+v"(bfr[ks][j]));
 #pragma unroll
         for (int i = 0; i < C::MI; ++i)
 #pragma unroll
             for (int j = 0; j < C::NI; ++j)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4)
-                    *(uint2*)(Cs + (mrow + i * 32) * C::CSTR + (ncol + j * 32 + 8 * q4) * 2) =
-                        make_uint2(pack2_bf16(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1]),
-                                   pack2_bf16(acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]));
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+    };
+    constexpr std::integral_constant<int, 0> K0{};
+    constexpr std::integral_constant<int, 1> K1{};
+
+    for (int s = 0; s < C::PD; ++s) issue(s * C::STAGE, L0, LN, true);
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(C::LPW * (C::PD - 1)) : "memory");
+    int cstage = 0, fstage = 0;                         // stage being computed on / stage freed at the last barrier
+    read_frags(K0, cstage);
+#pragma unroll 1
+    for (int kt = 0; kt < nk; ++kt) {
+        read_frags(K1, cstage);
+        asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(C::MI + C::NI) : "memory");    // in-order: half step 0 has arrived
+        __builtin_amdgcn_sched_barrier(0);              // keep the schedule as written: MFMAs between the waits
+        __builtin_amdgcn_s_setprio(1);
+        mfma_half(K0);
+        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // The loads of step kt + PD - 1 go out in two halves, each behind a burst of MFMAs, so that their
+        // issue (which can stall on a full queue) never delays the matrix pipe: second half here.
+        if (kt > 0) issue(fstage, LH, LN, true);
+        // all reads of this stage are done and the next stage has landed (own loads: vmcnt; others': barrier)
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(C::LPW * (C::PD - 2)) : "memory");
+        fstage = cstage;                                // step kt + PD refills the stage just consumed
+        cstage = cstage + C::STAGE == C::NS * C::STAGE ? 0 : cstage + C::STAGE;
+        // Never leave a read without a consumer: the compiler sees its destination registers as dead and
+        // reuses them, and the late LDS return would overwrite their new contents.
+        if (kt + 1 < nk) read_frags(K0, cstage);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(1);
+        mfma_half(K1);
+        __builtin_amdgcn_s_setprio(0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(fstage, L0, LH, false);                   // first half of the loads of step kt + PD
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the repeated loads of the last steps have landed too
     __syncthreads();
-    bf16_t* Cp = (bf16_t*)d.C;
-    if (cvec) {
-        // groups of 8 consecutive columns map to 8 consecutive, 16-byte aligned elements of C
-        constexpr int CPRC = BN / 8;
-        for (int id = tid; id < BM * CPRC; id += C::THREADS) {
-            const int row = id / CPRC, cc = id % CPRC;
-            const int64_t m = m0 + row;
-            const int n = n0 + cc * 8;
-            if (m < d.M && n < d.N) {
-                const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
-                *(uint4*)(Cp + m * d.c_rs + col) = *(const uint4*)(Cs + row * C::CSTR + cc * 16);
-            }
-        }
-    } else {
-        for (int id = tid; id < BM * BN; id += C::THREADS) {
-            const int row = id / BN, nn = id % BN;
-            const int64_t m = m0 + row;
-            const int n = n0 + nn;
-            if (m < d.M && n < d.N) {
-                const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
-                Cp[m * d.c_rs + col] = *(const bf16_t*)(Cs + row * C::CSTR + nn * 2);
-            }
-        }
-    }
+    store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
 }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
@@ -219,13 +281,20 @@ inline bool c_map_vectorizes(const GemmDesc& d) {
     return d.c_div % 8 == 0 && d.c_lo == 1 && d.c_hi % 8 == 0;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int D>
-hipError_t launch_cfg(const GemmDesc& d, hipStream_t s) {
-    using C = TileCfg<BM, BN, BK, WGM, WGN>;
+// per-lane source offsets are 32-bit; operands further apart than that take the portable kernel
+inline bool dma_offsets_fit(const GemmDesc& d, int bm) {
+    const int64_t max_brow = d.b_div ? (int64_t)(d.b_div - 1) * d.b_mul + (d.N - 1) / d.b_div : d.N - 1;
+    return ((int64_t)bm * d.a_rs + 64) * 2 < (1ll << 32) && (max_brow * d.b_rs + 64) * 2 < (1ll << 32);
+}
+
+template <int BM, int BN, int WGM, int WGN>
+hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
+    using C = DmaCfg<BM, BN, WGM, WGN>;
     static bool attr_set = false;   // benign if set twice
-    auto kern = gemm_mfma_kernel<BM, BN, BK, WGM, WGN, D>;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_dma_kernel<BM, BN, WGM, WGN, false>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void*)gemm_dma_kernel<BM, BN, WGM, WGN, true>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -234,7 +303,10 @@ hipError_t launch_cfg(const GemmDesc& d, hipStream_t s) {
     const bool vec = c_map_vectorizes(d);
     const bool gfast = !vec && d.G > 1 && (int64_t)tiles_m * tiles_n * d.G < (1ll << 31);
     dim3 grid(gfast ? (unsigned)(tiles_m * tiles_n * d.G) : (unsigned)(tiles_m * tiles_n), gfast ? 1u : (unsigned)d.G);
-    hipLaunchKernelGGL(kern, grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+    if (d.K % C::BK)
+        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+    else
+        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -243,19 +315,18 @@ hipError_t launch_cfg(const GemmDesc& d, hipStream_t s) {
 bool mfma_gemm_supported(const GemmDesc& d) {
     return d.b_ks == 1 && d.K % 8 == 0 && d.a_rs % 8 == 0 && d.a_gs % 8 == 0 && d.b_rs % 8 == 0 &&
            d.b_gs % 8 == 0 && aligned16(d.A) && aligned16(d.B) && d.M > 0 && d.N > 0 && d.K > 0 &&
-           (int64_t)((d.M + 63) / 64) * ((d.N + 63) / 64) < (1ll << 30) && d.G <= 65535;
+           (int64_t)((d.M + 63) / 64) * ((d.N + 63) / 64) < (1ll << 30) && d.G <= 65535 && dma_offsets_fit(d, 256);
 }
 
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     constexpr int kSmallK = 256;     // short contractions: 128 x 128 tiles, two workgroups per CU overlap prologue and epilogue
-    const bool k64 = (d.K % 64 == 0);
     // large problems: 256 x 256 tiles on 8 wavefronts (half the LDS and L2 traffic per FLOP of 128 x 128)
     if (d.M > 128 && d.N > 128 && d.K > kSmallK && (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.G >= 256)
-        return k64 ? launch_cfg<256, 256, 64, 2, 4, 2>(d, s) : launch_cfg<256, 256, 32, 2, 4, 2>(d, s);
-    if (d.M > 64 && d.N > 64) return k64 ? launch_cfg<128, 128, 64, 2, 2, 2>(d, s) : launch_cfg<128, 128, 32, 2, 2, 4>(d, s);
-    if (d.M > 64)             return k64 ? launch_cfg<128, 64, 64, 2, 2, 2>(d, s) : launch_cfg<128, 64, 32, 2, 2, 4>(d, s);
-    if (d.N > 64)             return k64 ? launch_cfg<64, 128, 64, 2, 2, 2>(d, s) : launch_cfg<64, 128, 32, 2, 2, 4>(d, s);
-    return k64 ? launch_cfg<64, 64, 64, 2, 2, 4>(d, s) : launch_cfg<64, 64, 32, 2, 2, 4>(d, s);
+        return launch_dma<256, 256, 2, 4>(d, s);
+    if (d.M > 64 && d.N > 64) return launch_dma<128, 128, 2, 2>(d, s);
+    if (d.M > 64) return launch_dma<128, 64, 2, 2>(d, s);
+    if (d.N > 64) return launch_dma<64, 128, 2, 2>(d, s);
+    return launch_dma<64, 64, 2, 2>(d, s);
 }
 
 }  // namespace blr
