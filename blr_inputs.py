@@ -193,3 +193,44 @@ def make_layer(cfg: dict, seed=BASE_SEED, layer_id=0):
     if cfg["op"] == "monarch":
         return monarch_layer(cfg["n_in"], cfg["n_out"], cfg["nblocks"], cfg["r"], cfg["dtype"], seed, layer_id=layer_id)
     return blast_layer(cfg["n_in"], cfg["n_out"], cfg["b"], cfg["r"], cfg["dtype"], seed, layer_id=layer_id)
+
+
+# Decoder-layer linear chain at Llama-1B width: seven BLR linears per layer (q, k, v, o square;
+# gate, up hidden -> mlp; down mlp -> hidden), no attention.
+CHAIN = dict(hidden=2048, mlp=8192, n_layers=16, T=2048, dtype="bf16",
+             monarch=dict(nblocks=4, r_square=512, r_mlp=512),
+             blast=dict(b=16, r_square=256, r_mlp=512))
+CHAIN_LINEARS = ("q", "k", "v", "o", "gate", "up", "down")
+
+
+def chain_linear_shape(name: str, hidden: int, mlp: int):
+    """(n_in, n_out) of one of the seven linears of a layer."""
+    if name in ("gate", "up"):
+        return hidden, mlp
+    if name == "down":
+        return mlp, hidden
+    return hidden, hidden
+
+
+def chain_layers(op: str, n_layers=None, hidden=None, mlp=None, seed=BASE_SEED, params=None, dtype=None):
+    """Factors of every linear of the chain: a list (one entry per layer) of dicts name -> layer.
+    Every linear draws from its own random streams (layer_id = 1 + 7 * layer + position)."""
+    c = CHAIN
+    n_layers = c["n_layers"] if n_layers is None else n_layers
+    hidden = c["hidden"] if hidden is None else hidden
+    mlp = c["mlp"] if mlp is None else mlp
+    dtype = c["dtype"] if dtype is None else dtype
+    prm = dict(c[op]) if params is None else dict(params)
+    out = []
+    for l in range(n_layers):
+        layer = {}
+        for pos, name in enumerate(CHAIN_LINEARS):
+            n_in, n_out = chain_linear_shape(name, hidden, mlp)
+            r = prm["r_square"] if n_in == n_out else prm["r_mlp"]
+            lid = 1 + 7 * l + pos
+            if op == "monarch":
+                layer[name] = monarch_layer(n_in, n_out, prm["nblocks"], r, dtype, seed, layer_id=lid)
+            else:
+                layer[name] = blast_layer(n_in, n_out, prm["b"], r, dtype, seed, layer_id=lid)
+        out.append(layer)
+    return out
