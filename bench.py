@@ -260,12 +260,110 @@ def run_sweep(steps, warmup):
     return rows
 
 
+def chain_linear_cfg(op, name):
+    """Benchmark-style configuration of one linear of the chain."""
+    c = bi.CHAIN
+    n_in, n_out = bi.chain_linear_shape(name, c["hidden"], c["mlp"])
+    prm = c[op]
+    r = prm["r_square"] if n_in == n_out else prm["r_mlp"]
+    cfg = dict(op=op, n_in=n_in, n_out=n_out, r=r, dtype=c["dtype"], T=(c["T"],), x_scale=1.0)
+    cfg["nblocks" if op == "monarch" else "b"] = prm["nblocks"] if op == "monarch" else prm["b"]
+    return cfg
+
+
+def run_chain(args, op):
+    """One step = one forward pass of the 16-layer chain (x0 copied into the residual stream, then
+    7 BLR linears + 4 glue kernels per layer), all steps captured in one HIP graph."""
+    import torch
+    from paper_2512_20861_amd import binding as B
+    from paper_2512_20861_amd.chain import DeviceChain
+    c = bi.CHAIN
+    T = args.tokens or c["T"]
+    layers = bi.chain_layers(op)
+    chain = DeviceChain(layers, T)
+    x0 = to_dev(bi.activations(T, c["hidden"], c["dtype"]))
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+
+    def make_call():
+        calls = chain.prepared()
+        def step():
+            chain.h.copy_(x0)
+            for f in calls:
+                f()
+        return step
+
+    torch.cuda.synchronize()
+    ms_eager = time_calls(make_call(), steps, warmup)
+    ms = ms_eager if args.eager else time_graph(make_call, steps, warmup)
+
+    # per-shape break-down, each linear timed alone in the chain's launch configuration
+    parts, blr_ms, dense_ms, flops = [], 0.0, 0.0, 0.0
+    dominant = None
+    for name, count in (("q", 4), ("gate", 2), ("down", 1)):
+        cfg = chain_linear_cfg(op, name)
+        layer = GpuLayer(cfg, T)
+        t = time_graph(layer.prepared, 50, 5)
+        st = stage_times(layer, 50, 5)
+        W = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
+        Yd = torch.empty_like(layer.Y)
+        td = time_graph(lambda: B.prepared(B.dense_reference_forward, layer.X, W, Yd), 50, 5)
+        sa = layer.shape_args()
+        fl = rf.flops(op, T, sa["n_in"], sa["n_out"], sa["r"], sa["b"])
+        n_calls = count * c["n_layers"]
+        parts.append({"linear": f"{cfg['n_in']}->{cfg['n_out']} r={cfg['r']}", "calls_per_step": n_calls, "ms": t,
+                      "stage_ms": st, "dense_ms": td, "frac_mfma": fl / (t * 1e-3) / rf.MFMA_BF16_PEAK})
+        blr_ms += n_calls * t
+        dense_ms += n_calls * td
+        flops += n_calls * fl
+        worst = n_calls * (max(st) if st else t)
+        if dominant is None or worst > dominant[0]:
+            dominant = (worst, layer, t, st)
+        del W, Yd
+    roof = dominant_roofline(dominant[1], dominant[2], dominant[3])
+    roof["kernel"] += f" of the {dominant[1].n_in}->{dominant[1].n_out} linear"
+    sa = c[op]
+    out = {
+        "metric": "BLR linear tokens/s", "value": T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": c["dtype"], "data": "synthetic",
+        "config": {"workload": f"C4: {c['n_layers']}-layer decoder linear chain, all-{op} "
+                               f"({', '.join(f'{k}={v}' for k, v in sa.items())}), hidden {c['hidden']}, mlp {c['mlp']}, "
+                               f"T={T}, 7 linears + glue per layer, no attention",
+                   "factors": "packed once before timing" if op == "blast" else "canonical"},
+        "launch": "eager loop" if args.eager else "hip graph of the K steps, replayed", "ms_per_step_eager": ms_eager,
+        "roofline": roof,
+        "chain": {"linears": parts, "linears_ms_sum": blr_ms, "glue_and_gaps_ms": ms - blr_ms,
+                  "frac_mfma_whole_chain": flops / (ms * 1e-3) / rf.MFMA_BF16_PEAK},
+        "dense_same_shape": {"ms_per_step": dense_ms, "note": "the 112 linears as dense GEMMs, glue excluded",
+                             "speedup_of_blr_linears": dense_ms / blr_ms},
+    }
+    if not args.no_cpu:
+        import oracle
+        from oracle import chain as oc
+        T_cpu = 16
+        xs = bi.activations(T, c["hidden"], c["dtype"], rows=np.arange(T_cpu))
+        nthreads = oracle.binding.default_threads()
+        if op == "monarch":
+            lin = lambda x, f: oracle.monarch_forward(x, f.R.f64, f.L.f64, nthreads=nthreads)
+        else:
+            lin = lambda x, f: oracle.blast_forward(x, f.U.f64, f.S.f64, f.V.f64, nthreads=nthreads)
+        t0 = time.perf_counter()
+        passes = 0
+        while passes < 1 or time.perf_counter() - t0 < 10.0:
+            oc.chain_forward(xs.f64, layers, lin)
+            passes += 1
+        el = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": T_cpu * passes / el, "unit": "tokens/s", "cores": min(nthreads, T_cpu), "kind": "oracle",
+                               "sample": f"{passes} passes of the whole chain over the first {T_cpu} tokens ({el:.1f} s of fp64 oracle time)"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C1", choices=sorted(bi.CONFIGS))
+    ap.add_argument("--workload", default="C1", choices=sorted(bi.CONFIGS) + ["C4-monarch", "C4-blast"])
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -283,6 +381,9 @@ def main():
     B.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.manual_seed(0)
+    if args.workload.startswith("C4-"):
+        print(json.dumps(run_chain(args, args.workload[3:])), flush=True)
+        return
     cfg = bi.CONFIGS[args.workload]
     T = args.tokens or cfg["T"][-1]
     layer = GpuLayer(cfg, T)

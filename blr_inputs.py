@@ -23,6 +23,7 @@ depend on values.
 from __future__ import annotations
 
 import math
+import os
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -221,16 +222,22 @@ def chain_layers(op: str, n_layers=None, hidden=None, mlp=None, seed=BASE_SEED, 
     mlp = c["mlp"] if mlp is None else mlp
     dtype = c["dtype"] if dtype is None else dtype
     prm = dict(c[op]) if params is None else dict(params)
-    out = []
-    for l in range(n_layers):
-        layer = {}
-        for pos, name in enumerate(CHAIN_LINEARS):
-            n_in, n_out = chain_linear_shape(name, hidden, mlp)
-            r = prm["r_square"] if n_in == n_out else prm["r_mlp"]
-            lid = 1 + 7 * l + pos
-            if op == "monarch":
-                layer[name] = monarch_layer(n_in, n_out, prm["nblocks"], r, dtype, seed, layer_id=lid)
-            else:
-                layer[name] = blast_layer(n_in, n_out, prm["b"], r, dtype, seed, layer_id=lid)
-        out.append(layer)
+    def make(item):
+        l, pos, name = item
+        n_in, n_out = chain_linear_shape(name, hidden, mlp)
+        r = prm["r_square"] if n_in == n_out else prm["r_mlp"]
+        lid = 1 + 7 * l + pos
+        if op == "monarch":
+            return monarch_layer(n_in, n_out, prm["nblocks"], r, dtype, seed, layer_id=lid)
+        return blast_layer(n_in, n_out, prm["b"], r, dtype, seed, layer_id=lid)
+
+    items = [(l, pos, name) for l in range(n_layers) for pos, name in enumerate(CHAIN_LINEARS)]
+    # every tensor is a pure function of (seed, stream id, element index): generation order is free,
+    # and numpy releases the interpreter lock inside its array kernels
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        made = list(ex.map(make, items))
+    out = [dict() for _ in range(n_layers)]
+    for (l, _, name), lay in zip(items, made):
+        out[l][name] = lay
     return out

@@ -128,6 +128,29 @@ blr_status blr_dense_reference_forward(const void* X, const void* W, void* Y,
                                        int64_t T, int n_in, int n_out, blr_dtype dt,
                                        unsigned flags, blr_stream stream);
 
+/*
+ * Glue between the BLR linears of a decoder-layer chain. The paper replaces the projections and the
+ * MLP of Llama decoder layers with BLR linears (Section 5, Llama experiments) and leaves the rest of
+ * the layer as it is; the chain benchmark of this library keeps, of that rest, a weightless RMS
+ * normalisation, the residual additions and the SiLU gate, and puts the scaled sum of the q/k/v
+ * branches where attention would be. All tensors are row-major [T][d] device memory in the storage
+ * type dt (arithmetic in fp32), caller-owned; each call enqueues one kernel on `stream` and returns.
+ * T == 0 returns BLR_OK without a launch; null pointers, d <= 0, T < 0, negative eps and the aliasings
+ * named below return BLR_ERR_INVALID_ARG.
+ *
+ *   blr_rmsnorm:               N[t][:] = H[t][:] / sqrt(mean_c H[t][c]^2 + eps)          (N must not alias H)
+ *   blr_residual_add_rmsnorm:  H += Y (stored back in dt), then N = rmsnorm(H) of the stored values;
+ *                              N may be NULL, which leaves the plain residual addition (H, Y, N distinct)
+ *   blr_sum3_scaled:           A = (Q + K + V) * scale                                   (A may alias an input)
+ *   blr_silu_mul:              M = silu(G) * U, silu(x) = x / (1 + exp(-x))               (M may alias an input)
+ */
+blr_status blr_rmsnorm(const void* H, void* N, int64_t T, int d, float eps, blr_dtype dt, blr_stream stream);
+blr_status blr_residual_add_rmsnorm(void* H, const void* Y, void* N, int64_t T, int d, float eps,
+                                    blr_dtype dt, blr_stream stream);
+blr_status blr_sum3_scaled(const void* Q, const void* K, const void* V, void* A, int64_t T, int d, float scale,
+                           blr_dtype dt, blr_stream stream);
+blr_status blr_silu_mul(const void* G, const void* U, void* M, int64_t T, int d, blr_dtype dt, blr_stream stream);
+
 const char* blr_status_string(blr_status s);
 
 #ifdef __cplusplus

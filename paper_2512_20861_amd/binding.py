@@ -25,7 +25,11 @@ BLAST_THREE_KERNELS = 0x1000
 
 EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forward",
            "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_bytes",
-           "blr_blast_pack", "blr_dense_reference_forward")
+           "blr_blast_pack", "blr_dense_reference_forward",
+           "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul")
+# entry points that enqueue work and return a status: the ones prepared() can record
+_LAUNCHERS = ("blr_monarch_forward", "blr_blast_forward", "blr_dense_reference_forward",
+              "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul")
 
 _lib = None
 _last_workspace = None     # the workspace the latest forward call ran with (kept alive for prepared())
@@ -61,6 +65,15 @@ def lib() -> ctypes.CDLL:
         L.blr_blast_pack.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
         L.blr_dense_reference_forward.restype = ci
         L.blr_dense_reference_forward.argtypes = [vp, vp, vp, i64, ci, ci, ci, cu, vp]
+        cf = ctypes.c_float
+        L.blr_rmsnorm.restype = ci
+        L.blr_rmsnorm.argtypes = [vp, vp, i64, ci, cf, ci, vp]
+        L.blr_residual_add_rmsnorm.restype = ci
+        L.blr_residual_add_rmsnorm.argtypes = [vp, vp, vp, i64, ci, cf, ci, vp]
+        L.blr_sum3_scaled.restype = ci
+        L.blr_sum3_scaled.argtypes = [vp, vp, vp, vp, i64, ci, cf, ci, vp]
+        L.blr_silu_mul.restype = ci
+        L.blr_silu_mul.argtypes = [vp, vp, vp, i64, ci, ci, vp]
         _lib = L
     return _lib
 
@@ -150,7 +163,7 @@ def blast_pack(U, S, V, n_in, n_out, b, r, stream=None):
 
 
 def prepared(fn, *args, **kw):
-    """Marshal the arguments of `fn` (one of the *_forward functions of this module) ONCE and return
+    """Marshal the arguments of `fn` (one of the launching functions of this module) ONCE and return
     a zero-argument callable that re-issues exactly that C call. For tight launch loops: the
     per-call cost is one foreign-function call, no tensor or stream look-ups. The tensors must stay
     alive (pass an explicit workspace, or keep the returned callable's `.keepalive`) and the stream
@@ -161,7 +174,7 @@ def prepared(fn, *args, **kw):
 
     class _Recorder:
         def __getattr__(self, name):
-            if not name.endswith("_forward"):
+            if name not in _LAUNCHERS:
                 return getattr(real, name)      # size queries run for real
             def rec(*cargs):
                 captured.append((name, cargs))
@@ -193,3 +206,32 @@ def dense_reference_forward(X, W, Y, flags=0, stream=None):
     _check(lib().blr_dense_reference_forward(_ptr(X), _ptr(W), _ptr(Y), T, n_in, n_out, _dt(X), flags,
                                              _stream(stream)), "blr_dense_reference_forward")
     return Y
+
+
+def rmsnorm(H, N, eps=1e-6, stream=None):
+    """N[t] <- H[t] / sqrt(mean(H[t]^2) + eps)."""
+    T, d = H.shape
+    _check(lib().blr_rmsnorm(_ptr(H), _ptr(N), T, d, eps, _dt(H), _stream(stream)), "blr_rmsnorm")
+    return N
+
+
+def residual_add_rmsnorm(H, Y, N=None, eps=1e-6, stream=None):
+    """H <- H + Y in place; if N is given, N <- rmsnorm(H) of the updated H."""
+    T, d = H.shape
+    _check(lib().blr_residual_add_rmsnorm(_ptr(H), _ptr(Y), _ptr(N), T, d, eps, _dt(H), _stream(stream)),
+           "blr_residual_add_rmsnorm")
+    return H
+
+
+def sum3_scaled(Q, K, V, A, scale, stream=None):
+    """A <- (Q + K + V) * scale."""
+    T, d = Q.shape
+    _check(lib().blr_sum3_scaled(_ptr(Q), _ptr(K), _ptr(V), _ptr(A), T, d, scale, _dt(Q), _stream(stream)), "blr_sum3_scaled")
+    return A
+
+
+def silu_mul(G, U, M, stream=None):
+    """M <- silu(G) * U."""
+    T, d = G.shape
+    _check(lib().blr_silu_mul(_ptr(G), _ptr(U), _ptr(M), T, d, _dt(G), _stream(stream)), "blr_silu_mul")
+    return M

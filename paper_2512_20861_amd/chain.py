@@ -1,0 +1,111 @@
+"""Decoder-layer linear chain on the GPU: seven BLR linears per layer with the glue kernels between
+them, every step one call into the C-ABI library (this module only owns buffers and the call list).
+
+Wiring per layer (h is the residual stream, all tensors [T][hidden] or [T][mlp] in bf16 or fp32):
+
+    n = rmsnorm(h);  a = (W_q n + W_k n + W_v n) / sqrt(3);  h += W_o a
+    n = rmsnorm(h);  h += W_down( silu(W_gate n) * W_up n )
+
+The residual addition and the following normalisation are one kernel.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+LINEARS = ("q", "k", "v", "o", "gate", "up", "down")
+
+
+def upload(ht) -> torch.Tensor:
+    """Host tensor of the seeded generator (bits + dtype) -> device tensor of the same bits."""
+    if ht.dtype == "bf16":
+        return torch.from_numpy(ht.bits.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return torch.from_numpy(ht.bits.copy()).cuda()
+
+
+class _Linear:
+    """Device-resident factors of one BLR linear and the argument tuple of its forward call."""
+
+    def __init__(self, host):
+        self.n_in, self.n_out, self.r = host.n_in, host.n_out, host.r
+        self.dt = B.BF16 if host.dtype == "bf16" else B.F32
+        if hasattr(host, "R"):
+            self.op, self.nb = "monarch", host.nblocks
+            self.R, self.L = upload(host.R), upload(host.L)
+        else:
+            self.op, self.b = "blast", host.b
+            self.U, self.S, self.V = upload(host.U), upload(host.S), upload(host.V)
+            self.flags = 0
+            if B.blast_packed_bytes(self.n_in, self.n_out, self.b, self.r, self.dt) > 0:
+                self.packed = B.blast_pack(self.U, self.S, self.V, self.n_in, self.n_out, self.b, self.r)
+                self.flags = B.BLAST_PACKED
+                self.S = self.V = None                      # only the packed form is read from now on
+
+    def workspace_bytes(self, T):
+        if self.op == "monarch":
+            return B.monarch_workspace_bytes(T, self.n_in, self.n_out, self.nb, self.r, self.dt)
+        return B.blast_workspace_bytes(T, self.n_in, self.n_out, self.b, self.r, self.dt, self.flags)
+
+    def call_args(self, X, Y, ws):
+        if self.op == "monarch":
+            return (B.monarch_forward, X, self.R, self.L, Y, self.nb, self.r, 0, ws)
+        if self.flags & B.BLAST_PACKED:
+            return (B.blast_forward, X, self.U, None, self.packed, Y, self.b, self.r, self.flags, ws)
+        return (B.blast_forward, X, self.U, self.S, self.V, Y, self.b, self.r, self.flags, ws)
+
+
+class DeviceChain:
+    def __init__(self, host_layers, T, eps=1e-6):
+        first = host_layers[0]
+        self.T, self.eps = T, eps
+        self.hidden, self.mlp = first["q"].n_in, first["gate"].n_out
+        self.layers = [{name: _Linear(layer[name]) for name in LINEARS} for layer in host_layers]
+        td = torch.bfloat16 if first["q"].dtype == "bf16" else torch.float32
+        new = lambda d: torch.empty((T, d), dtype=td, device="cuda")
+        self.h, self.n = new(self.hidden), new(self.hidden)
+        self.q, self.k, self.v, self.a, self.o, self.dn = (new(self.hidden) for _ in range(6))
+        self.g, self.u = new(self.mlp), new(self.mlp)
+        need = max(lin.workspace_bytes(T) for layer in self.layers for lin in layer.values())
+        self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+    def call_list(self):
+        """[(label, (fn, *args)), ...] in execution order; h must hold the input when the first one runs."""
+        c = [("rmsnorm", (B.rmsnorm, self.h, self.n, self.eps))]
+        last = len(self.layers) - 1
+        for li, L in enumerate(self.layers):
+            c.append((f"{li}.q", L["q"].call_args(self.n, self.q, self.ws)))
+            c.append((f"{li}.k", L["k"].call_args(self.n, self.k, self.ws)))
+            c.append((f"{li}.v", L["v"].call_args(self.n, self.v, self.ws)))
+            c.append((f"{li}.a", (B.sum3_scaled, self.q, self.k, self.v, self.a, 1.0 / math.sqrt(3.0))))
+            c.append((f"{li}.o", L["o"].call_args(self.a, self.o, self.ws)))
+            c.append((f"{li}.h1", (B.residual_add_rmsnorm, self.h, self.o, self.n, self.eps)))
+            c.append((f"{li}.gate", L["gate"].call_args(self.n, self.g, self.ws)))
+            c.append((f"{li}.up", L["up"].call_args(self.n, self.u, self.ws)))
+            c.append((f"{li}.m", (B.silu_mul, self.g, self.u, self.g)))
+            c.append((f"{li}.down", L["down"].call_args(self.g, self.dn, self.ws)))
+            c.append((f"{li}.h2", (B.residual_add_rmsnorm, self.h, self.dn, None if li == last else self.n, self.eps)))
+        return c
+
+    def prepared(self):
+        """Zero-argument callables (arguments marshalled once) on the stream that is current now."""
+        return [B.prepared(*args) for _, args in self.call_list()]
+
+    def forward(self, x0, record=False):
+        """Run the chain on x0 [T][hidden] (device tensor); returns h. With record=True also returns, per
+        call label, a copy of the tensor that call wrote and of the tensor it read."""
+        self.h.copy_(x0)
+        taps = {}
+        for label, args in self.call_list():
+            if record:
+                src = args[1].clone()
+            args[0](*args[1:])
+            if record:
+                out = {B.rmsnorm: lambda a: a[2], B.sum3_scaled: lambda a: a[4], B.silu_mul: lambda a: a[3],
+                       B.residual_add_rmsnorm: lambda a: a[1], B.monarch_forward: lambda a: a[4],
+                       B.blast_forward: lambda a: a[5]}[args[0]](args)
+                taps[label] = (src, out.clone())
+        return (self.h, taps) if record else self.h

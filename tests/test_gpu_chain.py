@@ -1,0 +1,153 @@
+"""GPU parity of the decoder-layer chain: the glue kernels one by one against the numpy oracle, a
+small chain end to end and linear by linear (each GPU linear re-evaluated by the oracle on the
+GPU's own input), and the full benchmark chain on sampled token rows (rows are independent)."""
+import math
+
+import numpy as np
+import pytest
+
+import blr_inputs as bi
+import oracle
+from oracle import chain as oc
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+# End to end, rounding errors of the 7 * n_layers bf16 linears and of the bf16 residual stream add up;
+# each contributes about 2^-9 of the stream's scale and they are independent, so the bound grows
+# with the square root of the number of roundings on the path (measured values are printed).
+def chain_tol(n_layers, dtype):
+    return (2e-2 if dtype == "bf16" else 1e-5) * max(1.0, math.sqrt(n_layers / 2.0))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2512_20861_amd import binding
+    binding.lib()
+
+
+def _gu():
+    import gpu_util
+    return gpu_util
+
+
+def _oracle_linear(op):
+    if op == "monarch":
+        return lambda x, f: oracle.monarch_forward(x, f.R.f64, f.L.f64)
+    return lambda x, f: oracle.blast_forward(x, f.U.f64, f.S.f64, f.V.f64)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T,d", [(37, 2048), (5, 8192), (3, 100), (9, 7), (2, 16384 + 8)])
+def test_glue_kernels(T, d, dtype):
+    gu = _gu()
+    B = gu.B
+    H = bi.gaussian(7, 101, (T, d), 1.5, dtype)
+    Y = bi.gaussian(7, 102, (T, d), 0.7, dtype)
+    Z = bi.gaussian(7, 103, (T, d), 2.0, dtype)
+    tol = gu.TOL[dtype]
+    # rmsnorm
+    N = gu.empty_out(T, d, dtype)
+    B.rmsnorm(gu.to_dev(H), N, eps=oc.EPS)
+    assert gu.rel_err(gu.to_f64(N), oc.rmsnorm(H.f64)) <= tol
+    # residual add + rmsnorm, and the plain residual add
+    Hd, N2 = gu.to_dev(H), gu.empty_out(T, d, dtype)
+    B.residual_add_rmsnorm(Hd, gu.to_dev(Y), N2, eps=oc.EPS)
+    assert gu.rel_err(gu.to_f64(Hd), H.f64 + Y.f64) <= tol
+    assert gu.rel_err(gu.to_f64(N2), oc.rmsnorm(H.f64 + Y.f64)) <= tol
+    Hd2 = gu.to_dev(H)
+    B.residual_add_rmsnorm(Hd2, gu.to_dev(Y), None)
+    assert torch.equal(Hd2, Hd)
+    # scaled sum of three, SiLU gate (also in place)
+    A = gu.empty_out(T, d, dtype)
+    B.sum3_scaled(gu.to_dev(H), gu.to_dev(Y), gu.to_dev(Z), A, 1.0 / math.sqrt(3.0))
+    assert gu.rel_err(gu.to_f64(A), (H.f64 + Y.f64 + Z.f64) / math.sqrt(3.0)) <= tol
+    M, Gd = gu.empty_out(T, d, dtype), gu.to_dev(H)
+    B.silu_mul(Gd, gu.to_dev(Y), M)
+    assert gu.rel_err(gu.to_f64(M), oc.silu(H.f64) * Y.f64) <= (tol if dtype == "bf16" else 1e-5)
+    B.silu_mul(Gd, gu.to_dev(Y), Gd)
+    assert torch.equal(Gd, M)
+    torch.cuda.synchronize()
+
+
+def test_glue_status_codes():
+    gu = _gu()
+    B = gu.B
+    L = B.lib()
+    x = torch.zeros((4, 8), dtype=torch.bfloat16, device="cuda")
+    p = x.data_ptr()
+    assert L.blr_rmsnorm(p, p, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG          # aliasing
+    assert L.blr_rmsnorm(p, None, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_rmsnorm(None, None, 0, 8, 1e-6, B.BF16, None) == B.OK                  # no tokens: nothing to do
+    assert L.blr_rmsnorm(p, p, 4, 0, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_residual_add_rmsnorm(p, p, None, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_silu_mul(p, None, p, 4, 8, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_sum3_scaled(p, p, p, p, -1, 8, 1.0, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_sum3_scaled(p, p, p, p, 4, 8, 1.0, 7, None) == B.ERR_INVALID_ARG
+
+
+SMALL = {
+    "monarch": dict(nblocks=4, r_square=64, r_mlp=128),
+    "blast": dict(b=16, r_square=64, r_mlp=72),
+}
+
+
+@pytest.mark.parametrize("op", ["monarch", "blast"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_small_chain_end_to_end_and_per_linear(op, dtype):
+    gu = _gu()
+    from paper_2512_20861_amd.chain import DeviceChain
+    T, hidden, mlp, n_layers = 70, 256, 512, 3
+    layers = bi.chain_layers(op, n_layers=n_layers, hidden=hidden, mlp=mlp, params=SMALL[op], dtype=dtype)
+    x0 = bi.activations(T, hidden, dtype)
+    chain = DeviceChain(layers, T, eps=oc.EPS)
+    h, taps = chain.forward(gu.to_dev(x0), record=True)
+    torch.cuda.synchronize()
+    lin = _oracle_linear(op)
+    href = oc.chain_forward(x0.f64, layers, lin)
+    err = gu.rel_err(gu.to_f64(h), href)
+    print(f"chain {op} {dtype} {n_layers} layers: end-to-end rel err {err:.3e}")
+    assert err <= chain_tol(n_layers, dtype)
+    # every linear on its own: the oracle applied to the GPU's input of that call
+    worst = 0.0
+    for li, layer in enumerate(layers):
+        for name in bi.CHAIN_LINEARS:
+            src, out = taps[f"{li}.{name}"]
+            e = gu.rel_err(gu.to_f64(out), lin(gu.to_f64(src), layer[name]))
+            worst = max(worst, e)
+            assert e <= gu.TOL[dtype], (li, name, e)
+    print(f"chain {op} {dtype}: worst single linear rel err {worst:.3e}")
+    # glue steps on the GPU's own inputs
+    for li in range(n_layers):
+        q, k, v = (gu.to_f64(taps[f"{li}.{n}"][1]) for n in "qkv")
+        assert gu.rel_err(gu.to_f64(taps[f"{li}.a"][1]), (q + k + v) / math.sqrt(3.0)) <= gu.TOL[dtype]
+        g_in = gu.to_f64(taps[f"{li}.m"][0])
+        assert gu.rel_err(gu.to_f64(taps[f"{li}.m"][1]), oc.silu(g_in) * gu.to_f64(taps[f"{li}.up"][1])) <= gu.TOL[dtype]
+        h_before, h_after = gu.to_f64(taps[f"{li}.h1"][0]), gu.to_f64(taps[f"{li}.h1"][1])
+        assert gu.rel_err(h_after, h_before + gu.to_f64(taps[f"{li}.o"][1])) <= gu.TOL[dtype]
+
+
+@pytest.mark.parametrize("op", ["monarch", "blast"])
+def test_full_chain_sampled_rows(op):
+    """The benchmark configuration (16 layers, T = 2048, hidden 2048, MLP 8192) with prepared calls,
+    as bench.py runs it; the oracle recomputes a few token rows from x0."""
+    gu = _gu()
+    from paper_2512_20861_amd.chain import DeviceChain
+    c = bi.CHAIN
+    T = c["T"]
+    layers = bi.chain_layers(op)
+    x0 = bi.activations(T, c["hidden"], "bf16")
+    chain = DeviceChain(layers, T, eps=oc.EPS)
+    calls = chain.prepared()
+    chain.h.copy_(gu.to_dev(x0))
+    for f in calls:
+        f()
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 127, 128, 1000, T - 1], dtype=np.int64)
+    href = oc.chain_forward(x0.f64[rows], layers, _oracle_linear(op))
+    got = gu.to_f64(chain.h[torch.from_numpy(rows).cuda()])
+    err = gu.rel_err(got, href)
+    print(f"full chain {op}: {len(rows)} sampled rows, end-to-end rel err {err:.3e}")
+    assert err <= chain_tol(c["n_layers"], "bf16")
