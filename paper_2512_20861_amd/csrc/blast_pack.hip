@@ -60,35 +60,58 @@ __global__ __launch_bounds__(256) void pack_uf_kernel(const bf16_t* U, bf16_t* U
     Uf[id] = (rho < r) ? U[((int64_t)i * p + a) * r + rho] : (bf16_t)0;
 }
 
-// stand-alone coupling from the packed tiles: A[t][i][rho] = sum_j Sp[rho][i][j] * Z[t][j][rho]
-__global__ __launch_bounds__(256) void coupling_packed_kernel(const bf16_t* Z, const bf16_t* Sp, bf16_t* A, int64_t T, int b, int r) {
-    const int64_t total = T * b * r;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int rho = (int)(e % r);
-        const int i = (int)((e / r) % b);
-        const int64_t t = e / ((int64_t)r * b);
-        float acc = 0.f;
-        for (int j = 0; j < b; ++j)
-            acc = fmaf(bf16_to_float(Sp[(int64_t)rho * 256 + i * 16 + j]), bf16_to_float(Z[(t * b + j) * r + rho]), acc);
-        A[e] = float_to_bf16(acc);
+__global__ __launch_bounds__(256) void copy_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e < n) dst[e] = src[e];
+}
+
+// Stand-alone coupling for FEW tokens: A[t][i][rho] = sum_j S[i][j][rho] * Z[t][j][rho] from the
+// canonical S[b][b][r] (rank index contiguous). One thread per (token, output block, 8 rank indices):
+// 2 b independent 16-byte loads (all in flight at once), one 16-byte store; consecutive lanes take
+// consecutive groups of 8 rank indices, so a wavefront reads and writes contiguous kilobytes.
+__global__ __launch_bounds__(256) void coupling_small_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restrict__ S,
+                                                             bf16_t* __restrict__ A, int64_t total, int b, int r8) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int c = (int)(e % r8);
+    const int i = (int)((e / r8) % b);
+    const int64_t t = e / ((int64_t)r8 * b);
+    const int r = r8 * 8;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 16
+    for (int j = 0; j < b; ++j) {
+        const uint4 zv = *(const uint4*)(Z + (t * b + j) * r + c * 8);
+        const uint4 sv = *(const uint4*)(S + ((int64_t)i * b + j) * r + c * 8);
+        const uint32_t zw[4] = {zv.x, zv.y, zv.z, zv.w}, sw[4] = {sv.x, sv.y, sv.z, sv.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            acc[2 * k] = fmaf(__uint_as_float(sw[k] << 16), __uint_as_float(zw[k] << 16), acc[2 * k]);
+            acc[2 * k + 1] = fmaf(__uint_as_float(sw[k] & 0xFFFF0000u), __uint_as_float(zw[k] & 0xFFFF0000u), acc[2 * k + 1]);
+        }
     }
+    *(uint4*)(A + (t * b + i) * r + c * 8) =
+        make_uint4(pack2_bf16(acc[0], acc[1]), pack2_bf16(acc[2], acc[3]), pack2_bf16(acc[4], acc[5]), pack2_bf16(acc[6], acc[7]));
 }
 
 }  // namespace
 
-hipError_t launch_coupling_packed(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
-    const int64_t total = T * b * r;
+hipError_t launch_coupling_small(const void* Z, const void* S, void* A, int64_t T, int b, int r, hipStream_t s) {
+    const int64_t total = T * b * (r / 8);              // r is a multiple of 8
     if (total <= 0) return hipSuccess;
-    int64_t blocks = (total + 255) / 256;
-    if (blocks > 65536 * 16) blocks = 65536 * 16;
-    hipLaunchKernelGGL(coupling_packed_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                       (const bf16_t*)Z, (const bf16_t*)Sp, (bf16_t*)A, T, b, r);
+    hipLaunchKernelGGL(coupling_small_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       (const bf16_t*)Z, (const bf16_t*)S, (bf16_t*)A, total, b, r / 8);
     return hipGetLastError();
 }
 
-hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Vt, void* Vf, void* Uf,
+hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Sc, void* Vt, void* Vf, void* Uf,
                              int n_in, int n_out, int b, int r, hipStream_t s) {
     const int q = n_in / b, p = n_out / b;
+    if (Sc) {                                           // canonical S, for the few-token coupling
+        const int64_t total = (int64_t)b * b * r;
+        hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t*)S, (bf16_t*)Sc, total);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
     hipLaunchKernelGGL(pack_s_kernel, dim3((unsigned)r), dim3(256), 0, s, (const bf16_t*)S, (bf16_t*)Sp, b, r, Vf ? 1 : 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

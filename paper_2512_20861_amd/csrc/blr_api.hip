@@ -29,7 +29,7 @@ bool blast_shape_ok(int64_t T, int n_in, int n_out, int b, int r) {
 // Where the re-laid-out BLAST factors live inside the packed buffer.
 struct PackLayout {
     bool full;                       // served by the single-kernel path: fragment-ordered V and U
-    size_t off_Sp, off_Vt, off_Vf, off_Uf, total;
+    size_t off_Sp, off_Sc, off_Vt, off_Vf, off_Uf, total;   // Sc: canonical S (large-rank layouts only)
 };
 
 PackLayout pack_layout(int n_in, int n_out, int b, int r) {
@@ -42,6 +42,7 @@ PackLayout pack_layout(int n_in, int n_out, int b, int r) {
         pk.off_Uf = off; off += align_up(blast_uf_bytes(n_out, b, r));
     } else {
         pk.off_Vt = off; off += align_up((size_t)n_in * r * 2);
+        pk.off_Sc = off; off += align_up((size_t)b * b * r * 2);
     }
     pk.total = off;
     return pk;
@@ -96,7 +97,7 @@ BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt,
 blr_status run_pack(const void* U, const void* S, const void* V, void* packed, int n_in, int n_out, int b, int r, hipStream_t s) {
     const PackLayout pk = pack_layout(n_in, n_out, b, r);
     unsigned char* base = (unsigned char*)packed;
-    return from_hip(launch_blast_pack(U, S, V, base + pk.off_Sp, pk.full ? nullptr : base + pk.off_Vt,
+    return from_hip(launch_blast_pack(U, S, V, base + pk.off_Sp, pk.full ? nullptr : base + pk.off_Sc, pk.full ? nullptr : base + pk.off_Vt,
                                       pk.full ? base + pk.off_Vf : nullptr, pk.full ? base + pk.off_Uf : nullptr,
                                       n_in, n_out, b, r, s));
 }
@@ -257,7 +258,8 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
             s1.M = tc;
             blr_status st = run_gemm(s1, dt, true, s);
             if (st != BLR_OK) return st;
-            st = from_hip(launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
+            // few tokens: the 64-token tiles of the MFMA coupling would be mostly padding; one thread per output element then
+            st = from_hip(tc <= 32 ? launch_coupling_small(Zws, pack + pk.off_Sc, Aws, tc, b, r, s) : launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
             if (st != BLR_OK) return st;
         }
         if (last) {

@@ -80,6 +80,9 @@ hipError_t launch_coupling_valu(const void* Z, const void* S, void* A, int64_t T
 // bf16 MFMA kernels; `mfma_gemm_supported` states the alignment contract
 bool mfma_gemm_supported(const GemmDesc& d);
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s);
+// few tokens (M <= 32): weight-streaming kernel, split-K inside the workgroup; same alignment contract
+bool skinny_gemm_supported(const GemmDesc& d);
+hipError_t launch_gemm_skinny(const GemmDesc& d, bool cvec, hipStream_t s);
 
 // BLAST: fused stage 1 + coupling on MFMA. X[T][n_in], Vt[b][r][q], Sp[r][16][16] -> A[T][b][r] (bf16)
 bool blast_fused_supported(int64_t T, int n_in, int b, int r);
@@ -100,10 +103,10 @@ hipError_t launch_blast_full(const void* X, const void* Sp, const void* Vf, cons
                              int64_t T, int n_in, int n_out, int b, int r, hipStream_t s);
 
 // stand-alone coupling reading the packed tiles Sp[r][16][16] (bf16)
-hipError_t launch_coupling_packed(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s);
+hipError_t launch_coupling_small(const void* Z, const void* S, void* A, int64_t T, int b, int r, hipStream_t s);   // few tokens; canonical S
 
 // BLAST weight re-layout (bf16): Sp always; Vt (row-major transpose) if non-null; Vf and Uf if non-null
-hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Vt, void* Vf, void* Uf,
+hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Sc, void* Vt, void* Vf, void* Uf,
                              int n_in, int n_out, int b, int r, hipStream_t s);
 
 }  // namespace blr

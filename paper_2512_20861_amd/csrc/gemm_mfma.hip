@@ -120,9 +120,9 @@ __device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
     return v;
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int NSTAGES>
 struct DmaCfg {
-    static constexpr int BK = 32, NS = 4, PD = NS;   // stages in LDS = steps of loads in flight
+    static constexpr int BK = 32, NS = NSTAGES, PD = NS;   // stages in LDS = steps of loads in flight
     static constexpr int WAVES = WGM * WGN, THREADS = 64 * WAVES;
     static constexpr int ROWS = BM + BN;
     static constexpr int STAGE = ROWS * BK * 2;
@@ -139,9 +139,9 @@ struct DmaCfg {
 };
 
 // TAIL: K is not a multiple of 32, the last step is partial
-template <int BM, int BN, int WGM, int WGN, bool TAIL>
+template <int BM, int BN, int WGM, int WGN, int NS, bool TAIL>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int gfast) {
-    using C = DmaCfg<BM, BN, WGM, WGN>;
+    using C = DmaCfg<BM, BN, WGM, WGN, NS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -287,14 +287,14 @@ inline bool dma_offsets_fit(const GemmDesc& d, int bm) {
     return ((int64_t)bm * d.a_rs + 64) * 2 < (1ll << 32) && (max_brow * d.b_rs + 64) * 2 < (1ll << 32);
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int NS = 4>
 hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
-    using C = DmaCfg<BM, BN, WGM, WGN>;
+    using C = DmaCfg<BM, BN, WGM, WGN, NS>;
     static bool attr_set = false;   // benign if set twice
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_dma_kernel<BM, BN, WGM, WGN, false>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_dma_kernel<BM, BN, WGM, WGN, NS, false>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)gemm_dma_kernel<BM, BN, WGM, WGN, true>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        e = hipFuncSetAttribute((const void*)gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -304,9 +304,9 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
     const bool gfast = !vec && d.G > 1 && (int64_t)tiles_m * tiles_n * d.G < (1ll << 31);
     dim3 grid(gfast ? (unsigned)(tiles_m * tiles_n * d.G) : (unsigned)(tiles_m * tiles_n), gfast ? 1u : (unsigned)d.G);
     if (d.K % C::BK)
-        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
     else
-        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -319,6 +319,7 @@ bool mfma_gemm_supported(const GemmDesc& d) {
 }
 
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
+    if (skinny_gemm_supported(d)) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
     constexpr int kSmallK = 256;     // short contractions: 128 x 128 tiles, two workgroups per CU overlap prologue and epilogue
     // large problems: 256 x 256 tiles on 8 wavefronts (half the LDS and L2 traffic per FLOP of 128 x 128)
     if (d.M > 128 && d.N > 128 && d.K > kSmallK && (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.G >= 256)

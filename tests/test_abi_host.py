@@ -50,8 +50,8 @@ def test_workspace_sizes():
     assert unpacked == B.blast_packed_bytes(768, 768, 16, 96)
     # Sp (one 16x16 tile per rank index) + V and U in fragment order (1 KiB per block x tile x k-step)
     assert B.blast_packed_bytes(768, 768, 16, 96) == 96 * 512 + 16 * 3 * 3 * 1024 + 16 * 3 * 3 * 1024
-    # larger ranks: Sp + the row-major transpose of V
-    assert B.blast_packed_bytes(4096, 4096, 16, 640) == 640 * 512 + 4096 * 640 * 2
+    # larger ranks: Sp + the row-major transpose of V + a canonical copy of S (few-token coupling)
+    assert B.blast_packed_bytes(4096, 4096, 16, 640) == 640 * 512 + 4096 * 640 * 2 + 16 * 16 * 640 * 2
     # large ranks: Z and A of one chunk of tokens (three-kernel path), or A alone (fused stage 1 + coupling)
     assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED) == 2 * 512 * 16 * 640 * 2
     assert B.blast_workspace_bytes(512, 4096, 4096, 16, 640, B.BF16, B.BLAST_PACKED | B.BLAST_FUSED_STAGE12) == 512 * 16 * 640 * 2
