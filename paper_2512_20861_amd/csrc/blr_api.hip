@@ -62,6 +62,9 @@ constexpr size_t kChunkBytes = 48u << 20;
 // The fused stage 1 + coupling kernel runs one workgroup per compute unit; below this many tiles it
 // leaves too much of the chip idle and the three-kernel path (finer tiles) is faster.
 constexpr int64_t kFusedMinTiles = 128;
+// Up to this many tokens the coupling runs as one thread per 8 outputs (the 64-token tiles of the
+// MFMA coupling kernel would leave most of the chip idle).
+constexpr int64_t kSmallCouplingTokens = 128;
 
 BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
     BlastPlan pl{};
@@ -259,7 +262,7 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
             blr_status st = run_gemm(s1, dt, true, s);
             if (st != BLR_OK) return st;
             // few tokens: the 64-token tiles of the MFMA coupling would be mostly padding; one thread per output element then
-            st = from_hip(tc <= 32 ? launch_coupling_small(Zws, pack + pk.off_Sc, Aws, tc, b, r, s) : launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
+            st = from_hip(tc <= kSmallCouplingTokens ? launch_coupling_small(Zws, pack + pk.off_Sc, Aws, tc, b, r, s) : launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
             if (st != BLR_OK) return st;
         }
         if (last) {

@@ -321,13 +321,19 @@ bool mfma_gemm_supported(const GemmDesc& d) {
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     if (skinny_gemm_supported(d)) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
     constexpr int kSmallK = 256;     // short contractions: 128 x 128 tiles, two workgroups per CU overlap prologue and epilogue
+    auto tiles = [&](int bm, int bn) { return (int64_t)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.G; };
     // large problems: 256 x 256 tiles on 8 wavefronts (half the LDS and L2 traffic per FLOP of 128 x 128)
-    if (d.M > 128 && d.N > 128 && d.K > kSmallK && (int64_t)((d.M + 255) / 256) * ((d.N + 255) / 256) * d.G >= 256)
-        return launch_dma<256, 256, 2, 4>(d, s);
-    if (d.M > 64 && d.N > 64) return launch_dma<128, 128, 2, 2>(d, s);
+    if (d.M > 128 && d.N > 128 && d.K > kSmallK && tiles(256, 256) >= 256) return launch_dma<256, 256, 2, 4>(d, s);
+    // otherwise the largest tile that still gives every compute unit a workgroup
+    constexpr int64_t kFill = 200;
+    if (d.M > 64 && d.N > 64 && tiles(128, 128) >= kFill) return launch_dma<128, 128, 2, 2>(d, s);
+    if (d.M > 64 && tiles(128, 64) >= kFill) return launch_dma<128, 64, 2, 2>(d, s);
+    if (d.N > 64 && tiles(64, 128) >= kFill) return launch_dma<64, 128, 2, 2>(d, s);
+    if (tiles(64, 64) >= kFill || (d.M <= 64 && d.N <= 64)) return launch_dma<64, 64, 2, 2>(d, s);
+    // too small to fill the chip with any tile: fewest, largest tiles that fit the shape
+    if (d.M > 64 && d.N > 64) return tiles(64, 64) >= 64 ? launch_dma<64, 64, 2, 2>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
     if (d.M > 64) return launch_dma<128, 64, 2, 2>(d, s);
-    if (d.N > 64) return launch_dma<64, 128, 2, 2>(d, s);
-    return launch_dma<64, 64, 2, 2>(d, s);
+    return launch_dma<64, 128, 2, 2>(d, s);
 }
 
 }  // namespace blr
