@@ -234,6 +234,8 @@ def run_sweep(steps, warmup):
             mem, mfma = rf.floors(cfg["op"], T, **sa)
             dmem, dmfma = rf.floors("dense", T, cfg["n_in"], cfg["n_out"])
             ms_alt = {}
+            if cfg["op"] == "monarch":                      # the paper's optimisation 3: blocked output order, no final permutation
+                ms_alt["blocked_output"] = time_graph(lambda: layer.prepared(B.MONARCH_OUT_BLOCKED), steps, warmup)
             if cfg["op"] == "blast" and st is not None:     # both executions for large ranks, forced
                 for key, fl in (("fused_stage12", B.BLAST_FUSED_STAGE12), ("three_kernels", B.BLAST_THREE_KERNELS)):
                     ws_alt = torch.empty(max(B.blast_workspace_bytes(T, cfg["n_in"], cfg["n_out"], cfg["b"], cfg["r"], B.BF16,
