@@ -217,6 +217,33 @@ def dominant_roofline(layer, ms_total, stages):
             "traffic": None, "kernel": kern, "kernel_ms": ms, "algorithmic_flops": flo}
 
 
+def cold_copies(layer, min_bytes=512 << 20):
+    """Shallow copies of `layer` whose factor tensors are distinct device buffers, enough of them that
+    one round over all copies streams at least `min_bytes` of factors (far beyond every cache)."""
+    import copy
+    names = [n for n in ("R", "L", "U", "S", "V", "packed") if getattr(layer, n, None) is not None]
+    per = sum(getattr(layer, n).numel() * getattr(layer, n).element_size() for n in names)
+    out = []
+    for _ in range(max(2, -(-min_bytes // per))):
+        c = copy.copy(layer)
+        for n in names:
+            setattr(c, n, getattr(layer, n).clone())
+        out.append(c)
+    return out
+
+
+def time_cold(make_calls, steps, warmup):
+    """Like time_graph, but step i uses the i-th (mod n) of the prepared calls `make_calls()` returns."""
+    def make_call():
+        calls = make_calls()
+        state = {"i": 0}
+        def step():
+            calls[state["i"] % len(calls)]()
+            state["i"] += 1
+        return step
+    return time_graph(make_call, steps, warmup)
+
+
 def run_sweep(steps, warmup):
     import torch
     from paper_2512_20861_amd import binding as B
@@ -243,7 +270,18 @@ def run_sweep(steps, warmup):
                     mk = lambda: B.prepared(B.blast_forward, layer.X, layer.U, None, layer.packed, layer.Y, layer.b, layer.r,
                                             layer.flags | fl, ws_alt)
                     ms_alt[key] = time_graph(mk, steps, warmup)
-            row = {"config": name, "op": cfg["op"], "T": T, "ms": ms, "ms_variants": ms_alt, "tokens_per_s": T / (ms * 1e-3),
+            cold = None
+            if T <= 128 and name != "C1":                   # weight-streaming regime: also with cold caches
+                copies = cold_copies(layer)
+                n_cold = max(steps, len(copies))
+                ms_cold = time_cold(lambda: [c.prepared() for c in copies], n_cold, min(warmup, 3))
+                nW = max(2, -(-(512 << 20) // (W.numel() * W.element_size())))
+                Ws = [W.clone() for _ in range(nW)]
+                dense_cold = time_cold(lambda: [B.prepared(B.dense_reference_forward, layer.X, w, Yd) for w in Ws], max(steps, nW), min(warmup, 3))
+                cold = {"ms": ms_cold, "dense_ms": dense_cold, "frac_of_floor": max(mem, mfma) / (ms_cold * 1e-3),
+                        "dense_frac_of_floor": max(dmem, dmfma) / (dense_cold * 1e-3), "factor_copies": len(copies)}
+                del copies, Ws
+            row = {"config": name, "op": cfg["op"], "T": T, "ms": ms, "ms_variants": ms_alt, "cold": cold, "tokens_per_s": T / (ms * 1e-3),
                    "stage_ms": st, "floor_hbm_us": mem * 1e6, "floor_mfma_us": mfma * 1e6,
                    "bound": "hbm" if mem >= mfma else "mfma", "frac_of_floor": max(mem, mfma) / (ms * 1e-3),
                    "dense_ms": ms_dense, "dense_frac_of_floor": max(dmem, dmfma) / (ms_dense * 1e-3),
@@ -252,7 +290,8 @@ def run_sweep(steps, warmup):
             log(f"{name:4s} {cfg['op']:7s} T={T:5d}  {ms*1e3:9.1f} us  stages={None if st is None else [round(x*1e3,1) for x in st]}  "
                 f"floor {max(mem, mfma)*1e6:7.1f} us ({row['bound']}) frac {row['frac_of_floor']:.3f} | "
                 f"dense {ms_dense*1e3:9.1f} us frac {row['dense_frac_of_floor']:.3f} | speedup {row['speedup_vs_dense']:.2f}x"
-                + "".join(f" | {k} {v*1e3:.1f} us" for k, v in ms_alt.items()))
+                + "".join(f" | {k} {v*1e3:.1f} us" for k, v in ms_alt.items())
+                + (f" | cold {cold['ms']*1e3:.1f} us (frac {cold['frac_of_floor']:.3f}), dense cold {cold['dense_ms']*1e3:.1f} us" if cold else ""))
             del layer, Yd
         del W
         torch.cuda.empty_cache()
