@@ -70,14 +70,25 @@ __device__ __forceinline__ void load_s_group(const bf16_t* __restrict__ Sp, int 
 // Must be entered after a barrier that follows the last write to Zs.
 __device__ __forceinline__ void couple_group(unsigned char* grp, const s16x4 (&sfrag)[8]) {
     const int lane = threadIdx.x & 63, ci = lane & 15, cg = lane >> 4;
+    // Two batches of 16 fragment reads, each issued back to back before its MFMAs, so that the LDS
+    // latency is paid once per batch instead of once per MFMA.
     f32x4 d[TN / 16][8];
 #pragma unroll
-    for (int ri = 0; ri < 8; ++ri)
+    for (int half = 0; half < 2; ++half) {
+        s16x4 a[4][TN / 16];
 #pragma unroll
-        for (int tg = 0; tg < TN / 16; ++tg) {
-            const s16x4 a = *(const s16x4*)(grp + ri * ZSTR + (tg * 16 + ci) * 32 + cg * 8);
-            d[tg][ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, sfrag[ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-        }
+        for (int r4 = 0; r4 < 4; ++r4)
+#pragma unroll
+            for (int tg = 0; tg < TN / 16; ++tg)
+                a[r4][tg] = *(const s16x4*)(grp + (half * 4 + r4) * ZSTR + (tg * 16 + ci) * 32 + cg * 8);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+#pragma unroll
+            for (int tg = 0; tg < TN / 16; ++tg)
+                d[tg][half * 4 + r4] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[r4][tg], sfrag[half * 4 + r4], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     // d[tg][ri][e]: token tg*16 + 4*(lane/16) + e, output block i = lane%16
 #pragma unroll
     for (int tg = 0; tg < TN / 16; ++tg)
@@ -448,10 +459,11 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
     {
         const int cpr = n_in >> 3;                                   // 16-byte chunks per row
         const int total = FT * cpr;
-        for (int base = 0; base < total; base += FTHREADS * 4) {
-            uint4 v[4];
+        constexpr int XB = 8;                                        // loads in flight per thread: one round trip up to n_in = 1024
+        for (int base = 0; base < total; base += FTHREADS * XB) {
+            uint4 v[XB];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < XB; ++u) {
                 int id = base + u * FTHREADS + tid;
                 if (id > total - 1) id = total - 1;
                 const int row = id / cpr, cc = id - row * cpr;
@@ -460,7 +472,7 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
                 v[u] = *(const uint4*)(X + tx * n_in + cc * 8);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < XB; ++u) {
                 int id = base + u * FTHREADS + tid;
                 if (id > total - 1) id = total - 1;
                 const int row = id / cpr, cc = id - row * cpr;
@@ -544,13 +556,18 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
         if (wave + cc * FWAVES >= nchunks) continue;                // uniform; no global loads inside
         unsigned char* chunk = Zs + cw[cc] * FCHUNK;
         f32x4 d[2][8];
+        s16x4 a[8][2];                                             // all 16 fragment reads in flight before the first MFMA
 #pragma unroll
         for (int ri = 0; ri < 8; ++ri)
 #pragma unroll
-            for (int tg = 0; tg < 2; ++tg) {
-                const s16x4 a = *(const s16x4*)(chunk + ri * FZSTR + (tg * 16 + ci) * 32 + cg * 8);
-                d[tg][ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, sfr[cc][ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-            }
+            for (int tg = 0; tg < 2; ++tg) a[ri][tg] = *(const s16x4*)(chunk + ri * FZSTR + (tg * 16 + ci) * 32 + cg * 8);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ri = 0; ri < 8; ++ri)
+#pragma unroll
+            for (int tg = 0; tg < 2; ++tg)
+                d[tg][ri] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[ri][tg], sfr[cc][ri], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
         // every read of this chunk has been issued by this wavefront before the writes below, and
         // LDS operations of one wavefront complete in order; d[tg][ri][e]: token tg*16 + 4*cg + e, block ci
 #pragma unroll
@@ -572,18 +589,23 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
         const int i = wave + ii * FWAVES;
         if (i >= b) return;                                         // uniform; no global loads inside
         const int ic = i;
+        // the A fragments depend on the k-step only: read them all first, then run every MFMA on them
+        bf16x8 a0[NT], a1[NT];
+#pragma unroll
+        for (int ks = 0; ks < NT; ++ks) {
+            int c = ks * 4 + cg;                                    // group of 8 rank indices this lane multiplies
+            if (c > nchunks - 1) c = nchunks - 1;                   // past r the U fragment is zero; read a valid group
+            const unsigned char* chunk = Zs + c * FCHUNK;
+            a0[ks] = *(const bf16x8*)(chunk + (ic * FT + (ci ^ (ic & 7))) * 16);
+            a1[ks] = *(const bf16x8*)(chunk + (ic * FT + ((16 + ci) ^ (ic & 7))) * 16);
+        }
 #pragma unroll
         for (int nt = 0; nt < NPT; ++nt) {
             f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < NT; ++ks) {
-                int c = ks * 4 + cg;                                // group of 8 rank indices this lane multiplies
-                if (c > nchunks - 1) c = nchunks - 1;               // past r the U fragment is zero; read a valid group
-                const unsigned char* chunk = Zs + c * FCHUNK;
-                const bf16x8 a0 = *(const bf16x8*)(chunk + (ic * FT + (ci ^ (ic & 7))) * 16);
-                const bf16x8 a1 = *(const bf16x8*)(chunk + (ic * FT + ((16 + ci) ^ (ic & 7))) * 16);
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&ufr[ii][nt][ks], a0, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&ufr[ii][nt][ks], a1, acc1, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&ufr[ii][nt][ks], a0[ks], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&ufr[ii][nt][ks], a1[ks], acc1, 0, 0, 0);
             }
             // U is the first operand, so acc[e] is output feature i*p + nt*16 + 4*cg + e of token
             // (mt*16) + ci: four consecutive features per lane, one 8-byte LDS write each

@@ -72,27 +72,31 @@ __device__ __forceinline__ void store_c_tile(const GemmDesc& d, const f32x16 (&a
                                    pack2_bf16(acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]));
     }
     __syncthreads();
+    // A thread's column (group of 8 columns) is the same in every sweep of the workgroup over the
+    // rows, so the column map (two integer divisions) is evaluated once per thread, not per element.
     bf16_t* Cp = (bf16_t*)d.C;
     if (cvec) {
         // groups of 8 consecutive columns map to 8 consecutive, 16-byte aligned elements of C
         constexpr int CPRC = BN / 8;
-        for (int id = tid; id < BM * CPRC; id += THREADS) {
-            const int row = id / CPRC, cc = id % CPRC;
-            const int64_t m = m0 + row;
-            const int n = n0 + cc * 8;
-            if (m < d.M && n < d.N) {
-                const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
-                *(uint4*)(Cp + m * d.c_rs + col) = *(const uint4*)(Cs + row * CSTR + cc * 16);
+        static_assert(THREADS % CPRC == 0, "a thread keeps its column group");
+        const int cc = tid % CPRC;
+        const int n = n0 + cc * 8;
+        if (n < d.N) {
+            const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
+            for (int row = tid / CPRC; row < BM; row += THREADS / CPRC) {
+                const int64_t m = m0 + row;
+                if (m < d.M) *(uint4*)(Cp + m * d.c_rs + col) = *(const uint4*)(Cs + row * CSTR + cc * 16);
             }
         }
     } else {
-        for (int id = tid; id < BM * BN; id += THREADS) {
-            const int row = id / BN, nn = id % BN;
-            const int64_t m = m0 + row;
-            const int n = n0 + nn;
-            if (m < d.M && n < d.N) {
-                const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
-                Cp[m * d.c_rs + col] = *(const bf16_t*)(Cs + row * CSTR + nn * 2);
+        static_assert(THREADS % BN == 0, "a thread keeps its column");
+        const int nn = tid % BN;
+        const int n = n0 + nn;
+        if (n < d.N) {
+            const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
+            for (int row = tid / BN; row < BM; row += THREADS / BN) {
+                const int64_t m = m0 + row;
+                if (m < d.M) Cp[m * d.c_rs + col] = *(const bf16_t*)(Cs + row * CSTR + nn * 2);
             }
         }
     }
