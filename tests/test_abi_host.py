@@ -124,6 +124,30 @@ def test_dense_and_pack_argument_checks():
     assert lib.blr_blast_pack(FAKE, FAKE, FAKE, FAKE, 36, 30, 3, 10, B.BF16, None) == B.ERR_UNSUPPORTED
 
 
+def test_glue_argument_checks():
+    L = B.lib()
+    A, C, D = FAKE, FAKE + 0x1000, FAKE + 0x2000
+    # no tokens: nothing to do, pointers not looked at
+    assert L.blr_rmsnorm(None, None, 0, 8, 1e-6, B.BF16, None) == B.OK
+    assert L.blr_residual_add_rmsnorm(None, None, None, 0, 8, 1e-6, B.BF16, None) == B.OK
+    assert L.blr_sum3_scaled(None, None, None, None, 0, 8, 1.0, B.BF16, None) == B.OK
+    assert L.blr_silu_mul(None, None, None, 0, 8, B.F32, None) == B.OK
+    # bad shapes, dtype, eps
+    assert L.blr_rmsnorm(A, C, -1, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_rmsnorm(A, C, 4, 0, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_rmsnorm(A, C, 4, 8, -1.0, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_rmsnorm(A, C, 4, 8, 1e-6, 5, None) == B.ERR_INVALID_ARG
+    # null pointers and forbidden aliasing
+    assert L.blr_rmsnorm(A, None, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_rmsnorm(A, A, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_residual_add_rmsnorm(A, A, C, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_residual_add_rmsnorm(A, C, A, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_residual_add_rmsnorm(A, C, C, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_residual_add_rmsnorm(A, None, D, 4, 8, 1e-6, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_sum3_scaled(A, C, None, D, 4, 8, 1.0, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_silu_mul(A, None, D, 4, 8, B.BF16, None) == B.ERR_INVALID_ARG
+
+
 def test_missing_library_fails_loudly(tmp_path, monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
