@@ -125,30 +125,34 @@ __device__ __forceinline__ void store_a_tile(const unsigned char* Zs, bf16_t* __
 // Stand-alone coupling (the middle kernel of the three-kernel path): Z[T][b][r] -> A[T][b][r].
 // The Z tile is read with full-line loads (8 lanes per 128-byte row segment) and transposed on its
 // way into LDS; blocks j and j+1 travel together so that every LDS write is a bf16 pair.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(512)
 void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
                            int64_t T, int b, int r, int tiles_r, int nblk) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* Zs = smem;
+    constexpr int NTHR = 512;                            // 8 wavefronts: one group of 8 rank indices each
     const int tid = threadIdx.x;
     const int logical = xcd_contiguous(blockIdx.x, nblk);
     const int tile_t = logical / tiles_r, tile_r = logical % tiles_r;
     const int64_t t0 = (int64_t)tile_t * TN;
     const int rho0 = tile_r * TR;
+    s16x4 sfrag[8];
+    load_s_group(Sp, rho0, tid >> 6, r, sfrag);          // in flight while Z is brought in
     const int c8 = tid & 7;                              // which 8 rank indices of the 64
     int rho = rho0 + c8 * 8;
     if (rho > r - 8) rho = r - 8;                        // past r: repeat valid data, never stored (r is a multiple of 8)
     const int npair = (b + 1) >> 1;
     if (b < 16)
-        for (int i = tid * 16; i < ZS_BYTES; i += 256 * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
+        for (int i = tid * 16; i < ZS_BYTES; i += NTHR * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
     if (b < 16) __syncthreads();
     // work item = (token, block pair): 8 lanes cover its 128-byte segment; 4 items in flight per thread
     const int items = TN * npair;
-    for (int base = 0; base < items; base += 32 * 4) {
+    constexpr int IPS = NTHR / 8;                        // items per sweep of the workgroup
+    for (int base = 0; base < items; base += IPS * 4) {
         uint4 v0[4], v1[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            int it = base + u * 32 + (tid >> 3);
+            int it = base + u * IPS + (tid >> 3);
             if (it > items - 1) it = items - 1;
             const int t = it / npair, jp = it - t * npair;
             int64_t tok = t0 + t;
@@ -159,7 +163,7 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int it = base + u * 32 + (tid >> 3);
+            const int it = base + u * IPS + (tid >> 3);
             if (it < items) {
                 const int t = it / npair, jp = it - t * npair;
                 const bool has1 = 2 * jp + 1 < b;
@@ -176,15 +180,9 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
         }
     }
     __syncthreads();
-#pragma unroll 1
-    for (int cc = 0; cc < 2; ++cc) {                    // 4 wavefronts, 2 groups each
-        const int c = (tid >> 6) * 2 + cc;
-        s16x4 sfrag[8];
-        load_s_group(Sp, rho0, c, r, sfrag);
-        couple_group(Zs + c * GROUP, sfrag);
-    }
+    couple_group(Zs + (tid >> 6) * GROUP, sfrag);
     __syncthreads();
-    store_a_tile<4>(Zs, A, T, t0, rho0, b, r, [](int t) { return t; });
+    store_a_tile<8>(Zs, A, T, t0, rho0, b, r, [](int t) { return t; });
 }
 
 // Stage 1 + coupling. Per step (one 64-wide k chunk of one input block j) a stage of LDS holds 128
@@ -383,7 +381,7 @@ hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t
     }
     const int tiles_t = (int)((T + TN - 1) / TN), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
-    hipLaunchKernelGGL(blast_coupling_kernel, dim3((unsigned)nblk), dim3(256), ZS_BYTES, s,
+    hipLaunchKernelGGL(blast_coupling_kernel, dim3((unsigned)nblk), dim3(512), ZS_BYTES, s,
                        (const bf16_t*)Z, (const bf16_t*)Sp, (bf16_t*)A, T, b, r, tiles_r, nblk);
     return hipGetLastError();
 }
