@@ -340,22 +340,33 @@ def run_chain(args, op):
     # per-shape break-down, each linear timed alone in the chain's launch configuration
     parts, blr_ms, dense_ms, flops = [], 0.0, 0.0, 0.0
     dominant = None
-    for name, count in (("q", 4), ("gate", 2), ("down", 1)):
+    # (linear, calls per layer, flags it runs with inside the chain); a blocked-input call is timed with
+    # the canonical first factor, which has the same shape (values do not matter for the timing)
+    OB, IB = B.MONARCH_OUT_BLOCKED, B.MONARCH_IN_BLOCKED
+    plan = ([("q", 3, OB), ("o", 1, IB), ("gate", 2, OB), ("down", 1, IB)] if chain.blocked
+            else [("q", 4, 0), ("gate", 2, 0), ("down", 1, 0)])
+    for name, count, fl in plan:
         cfg = chain_linear_cfg(op, name)
         layer = GpuLayer(cfg, T)
-        t = time_graph(layer.prepared, 50, 5)
-        st = stage_times(layer, 50, 5)
+        t = time_graph(lambda: layer.prepared(fl), 50, 5)
+        try:
+            st = (time_graph(lambda: layer.prepared(fl | B.ONLY_FIRST_STAGE), 50, 5, 1),
+                  time_graph(lambda: layer.prepared(fl | B.ONLY_LAST_STAGE), 50, 5, 1))
+        except B.BlrError:
+            st = None
         W = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
         Yd = torch.empty_like(layer.Y)
         td = time_graph(lambda: B.prepared(B.dense_reference_forward, layer.X, W, Yd), 50, 5)
         sa = layer.shape_args()
-        fl = rf.flops(op, T, sa["n_in"], sa["n_out"], sa["r"], sa["b"])
+        fl_ops = rf.flops(op, T, sa["n_in"], sa["n_out"], sa["r"], sa["b"])
         n_calls = count * c["n_layers"]
-        parts.append({"linear": f"{cfg['n_in']}->{cfg['n_out']} r={cfg['r']}", "calls_per_step": n_calls, "ms": t,
-                      "stage_ms": st, "dense_ms": td, "frac_mfma": fl / (t * 1e-3) / rf.MFMA_BF16_PEAK})
+        parts.append({"linear": f"{name}: {cfg['n_in']}->{cfg['n_out']} r={cfg['r']}"
+                                + (" (blocked output)" if fl & OB else "") + (" (blocked input)" if fl & IB else ""),
+                      "calls_per_step": n_calls, "ms": t, "stage_ms": st, "dense_ms": td,
+                      "frac_mfma": fl_ops / (t * 1e-3) / rf.MFMA_BF16_PEAK})
         blr_ms += n_calls * t
         dense_ms += n_calls * td
-        flops += n_calls * fl
+        flops += n_calls * fl_ops
         worst = n_calls * (max(st) if st else t)
         if dominant is None or worst > dominant[0]:
             dominant = (worst, layer, t, st)

@@ -49,6 +49,12 @@ typedef void* blr_stream;      /* a hipStream_t */
  * are permuted offline. */
 #define BLR_MONARCH_OUT_INTERLEAVED 0u
 #define BLR_MONARCH_OUT_BLOCKED     1u
+/* flag of blr_monarch_forward: X is in the BLOCKED order of an upstream layer with the same nblocks
+ * (feature j*nblocks + k stored at k*(n_in/nblocks) + j), and R is the re-ordered first factor
+ * written by blr_monarch_permute_first_factor (paper Section 4, optimisation 3: the upstream
+ * layer's final permutation is folded into this layer's static weight; any elementwise step in
+ * between commutes with the permutation). Needs nblocks^2 | n_in. */
+#define BLR_MONARCH_IN_BLOCKED      4u
 /* flag of blr_blast_forward: the `V` argument is the buffer written by blr_blast_pack (the one-time
  * offline weight re-layout of paper Section 4, optimisations 1 and 5) and `S` is ignored. */
 #define BLR_BLAST_PACKED            2u
@@ -86,6 +92,15 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
                                int64_t T, int n_in, int n_out, int nblocks, int r,
                                blr_dtype dt, unsigned flags,
                                void* workspace, size_t workspace_bytes, blr_stream stream);
+
+/*
+ * One-time re-layout of a first Monarch factor for BLR_MONARCH_IN_BLOCKED:
+ *   Rp[l][c][k*(p/b) + jj] = R[l][c][jj*b + k],  p = n_in/nblocks, b = nblocks, jj < p/b, k < b.
+ * R and Rp are [nblocks][r][p] device tensors of type dt and must not overlap.
+ * BLR_ERR_INVALID_ARG if nblocks^2 does not divide n_in.
+ */
+blr_status blr_monarch_permute_first_factor(const void* R, void* Rp, int n_in, int nblocks, int r,
+                                            blr_dtype dt, blr_stream stream);
 
 /*
  * BLAST forward (paper Section 2.1 "BLAST"; Section 4 "BLAST", optimisations 4-5).

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libblr.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 MONARCH_OUT_INTERLEAVED, MONARCH_OUT_BLOCKED, BLAST_PACKED, FORCE_GENERIC = 0, 1, 2, 0x100
+MONARCH_IN_BLOCKED = 4
 ONLY_FIRST_STAGE, ONLY_LAST_STAGE = 0x200, 0x400
 BLAST_FUSED_STAGE12 = 0x800
 BLAST_THREE_KERNELS = 0x1000
@@ -26,7 +27,8 @@ BLAST_THREE_KERNELS = 0x1000
 EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forward",
            "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_bytes",
            "blr_blast_pack", "blr_dense_reference_forward",
-           "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul")
+           "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul",
+           "blr_monarch_permute_first_factor")
 # entry points that enqueue work and return a status: the ones prepared() can record
 _LAUNCHERS = ("blr_monarch_forward", "blr_blast_forward", "blr_dense_reference_forward",
               "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul")
@@ -65,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.blr_blast_pack.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
         L.blr_dense_reference_forward.restype = ci
         L.blr_dense_reference_forward.argtypes = [vp, vp, vp, i64, ci, ci, ci, cu, vp]
+        L.blr_monarch_permute_first_factor.restype = ci
+        L.blr_monarch_permute_first_factor.argtypes = [vp, vp, ci, ci, ci, ci, vp]
         cf = ctypes.c_float
         L.blr_rmsnorm.restype = ci
         L.blr_rmsnorm.argtypes = [vp, vp, i64, ci, cf, ci, vp]
@@ -126,6 +130,14 @@ def monarch_forward(X, R, L, Y, nblocks, r, flags=0, workspace=None, stream=None
     _check(lib().blr_monarch_forward(_ptr(X), _ptr(R), _ptr(L), _ptr(Y), T, n_in, n_out, nblocks, r, dt, flags,
                                      _ptr(workspace), workspace.numel(), _stream(stream)), "blr_monarch_forward")
     return Y
+
+
+def monarch_permute_first_factor(R, n_in, nblocks, r, stream=None):
+    """First factor re-ordered for MONARCH_IN_BLOCKED (one-time weight preparation); returns the new tensor."""
+    Rp = torch.empty_like(R)
+    _check(lib().blr_monarch_permute_first_factor(_ptr(R), _ptr(Rp), n_in, nblocks, r, _dt(R), _stream(stream)),
+           "blr_monarch_permute_first_factor")
+    return Rp
 
 
 def blast_workspace_bytes(T, n_in, n_out, b, r, dt, flags=0) -> int:

@@ -6,7 +6,10 @@ Wiring per layer (h is the residual stream, all tensors [T][hidden] or [T][mlp] 
     n = rmsnorm(h);  a = (W_q n + W_k n + W_v n) / sqrt(3);  h += W_o a
     n = rmsnorm(h);  h += W_down( silu(W_gate n) * W_up n )
 
-The residual addition and the following normalisation are one kernel.
+The residual addition and the following normalisation are one kernel. In an all-Monarch chain the
+linears whose output only meets elementwise steps before the next linear (q, k, v -> o; gate, up ->
+down) write the BLOCKED output order and their consumer reads it with a first factor re-ordered
+once at set-up (the paper's optimisation 3), so no interleaving permutation is ever executed there.
 """
 from __future__ import annotations
 
@@ -30,12 +33,18 @@ def upload(ht) -> torch.Tensor:
 class _Linear:
     """Device-resident factors of one BLR linear and the argument tuple of its forward call."""
 
-    def __init__(self, host):
+    def __init__(self, host, out_blocked=False, in_blocked=False):
         self.n_in, self.n_out, self.r = host.n_in, host.n_out, host.r
         self.dt = B.BF16 if host.dtype == "bf16" else B.F32
+        self.mflags = 0
         if hasattr(host, "R"):
             self.op, self.nb = "monarch", host.nblocks
             self.R, self.L = upload(host.R), upload(host.L)
+            if out_blocked:
+                self.mflags |= B.MONARCH_OUT_BLOCKED
+            if in_blocked:
+                self.R = B.monarch_permute_first_factor(self.R, self.n_in, self.nb, self.r)
+                self.mflags |= B.MONARCH_IN_BLOCKED
         else:
             self.op, self.b = "blast", host.b
             self.U, self.S, self.V = upload(host.U), upload(host.S), upload(host.V)
@@ -52,18 +61,25 @@ class _Linear:
 
     def call_args(self, X, Y, ws):
         if self.op == "monarch":
-            return (B.monarch_forward, X, self.R, self.L, Y, self.nb, self.r, 0, ws)
+            return (B.monarch_forward, X, self.R, self.L, Y, self.nb, self.r, self.mflags, ws)
         if self.flags & B.BLAST_PACKED:
             return (B.blast_forward, X, self.U, None, self.packed, Y, self.b, self.r, self.flags, ws)
         return (B.blast_forward, X, self.U, self.S, self.V, Y, self.b, self.r, self.flags, ws)
 
 
 class DeviceChain:
-    def __init__(self, host_layers, T, eps=1e-6):
+    OUT_BLOCKED = ("q", "k", "v", "gate", "up")          # only elementwise steps between these and their consumer
+    IN_BLOCKED = ("o", "down")
+
+    def __init__(self, host_layers, T, eps=1e-6, blocked_chaining=True):
         first = host_layers[0]
         self.T, self.eps = T, eps
         self.hidden, self.mlp = first["q"].n_in, first["gate"].n_out
-        self.layers = [{name: _Linear(layer[name]) for name in LINEARS} for layer in host_layers]
+        nb = getattr(first["q"], "nblocks", 0)
+        self.blocked = bool(blocked_chaining and nb and self.hidden % (nb * nb) == 0 and self.mlp % (nb * nb) == 0)
+        self.layers = [{name: _Linear(layer[name], self.blocked and name in self.OUT_BLOCKED,
+                                      self.blocked and name in self.IN_BLOCKED) for name in LINEARS}
+                       for layer in host_layers]
         td = torch.bfloat16 if first["q"].dtype == "bf16" else torch.float32
         new = lambda d: torch.empty((T, d), dtype=td, device="cuda")
         self.h, self.n = new(self.hidden), new(self.hidden)

@@ -130,8 +130,9 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
                                blr_dtype dt, unsigned flags,
                                void* workspace, size_t workspace_bytes, blr_stream stream) {
     if (!monarch_shape_ok(T, n_in, n_out, nblocks, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
-    if (flags & ~(BLR_MONARCH_OUT_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_MONARCH_OUT_BLOCKED | BLR_MONARCH_IN_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_MONARCH_IN_BLOCKED) && (n_in / nblocks) % nblocks) return BLR_ERR_INVALID_ARG;
     if (!R || !L) return BLR_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(R) || !aligned16(L) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
     if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null
@@ -148,6 +149,9 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
     s1.B = R; s1.b_gs = (int64_t)r * p; s1.b_rs = p; s1.b_ks = 1; s1.b_div = rp; s1.b_mul = b;
     s1.C = workspace; s1.c_rs = (int64_t)b * r; s1.c_gs = rp; s1.c_div = rp; s1.c_hi = r; s1.c_lo = 1;
     s1.M = T; s1.N = r; s1.K = p; s1.G = b;
+    if (flags & BLR_MONARCH_IN_BLOCKED) {             // input block l = b runs of p/b elements, run k at k*(n_in/b) + l*(p/b)
+        s1.a_gs = p / b; s1.a_seg = p / b; s1.a_seg_stride = n_in / b;
+    }
     if (!(flags & BLR_ONLY_LAST_STAGE)) {
         blr_status st = run_gemm(s1, dt, allow_mfma, s);
         if (st != BLR_OK || (flags & BLR_ONLY_FIRST_STAGE)) return st;
@@ -162,6 +166,13 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
     else { s2.c_gs = 1; s2.c_hi = b; }
     s2.M = T; s2.N = q; s2.K = r; s2.G = b;
     return run_gemm(s2, dt, allow_mfma, s);
+}
+
+blr_status blr_monarch_permute_first_factor(const void* R, void* Rp, int n_in, int nblocks, int r,
+                                            blr_dtype dt, blr_stream stream) {
+    if (!R || !Rp || R == Rp || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    if (n_in <= 0 || nblocks <= 0 || r <= 0 || n_in % nblocks || (n_in / nblocks) % nblocks) return BLR_ERR_INVALID_ARG;
+    return from_hip(launch_monarch_permute_first_factor(R, Rp, n_in, nblocks, r, dt == BLR_BF16 ? DType::BF16 : DType::F32, (hipStream_t)stream));
 }
 
 size_t blr_blast_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {

@@ -65,6 +65,7 @@ __device__ inline uint4 keep_if(bool ok, uint4 v) {
 // b_div = N, b_mul = 1... is written as b_div = 0 meaning brow(n) = n.
 struct GemmDesc {
     const void* A; int64_t a_gs; int64_t a_rs;
+    int a_seg; int64_t a_seg_stride;   // a_seg > 0: contraction index k of A lives at (k / a_seg) * a_seg_stride + k % a_seg
     const void* B; int64_t b_gs; int64_t b_rs; int64_t b_ks; int b_div; int b_mul;
     void* C; int64_t c_rs; int64_t c_gs; int c_div; int64_t c_hi; int64_t c_lo;
     int64_t M; int N; int K; int G;
@@ -76,6 +77,9 @@ enum class DType { F32 = 0, BF16 = 1 };
 hipError_t launch_gemm_valu(const GemmDesc& d, DType dt, hipStream_t s);
 // A[t][i][rho] = sum_j S[i][j][rho] * Z[t][j][rho], Z and A are [T][b][r]
 hipError_t launch_coupling_valu(const void* Z, const void* S, void* A, int64_t T, int b, int r, DType dt, hipStream_t s);
+
+// first Monarch factor re-ordered for an input in blocked order: Rp[l][c][k*(p/b)+jj] = R[l][c][jj*b+k]
+hipError_t launch_monarch_permute_first_factor(const void* R, void* Rp, int n_in, int nblocks, int r, DType dt, hipStream_t s);
 
 // bf16 MFMA kernels; `mfma_gemm_supported` states the alignment contract
 bool mfma_gemm_supported(const GemmDesc& d);

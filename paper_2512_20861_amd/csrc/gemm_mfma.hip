@@ -180,17 +180,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, in
         bad[h] = TAIL && (nk - 1) * C::BK + piece * 8 >= d.K;    // in the last step this piece lies past K
     }
     int kf = 0;                                         // fetch cursor (uniform); stops at the last step
+    // byte offset of the cursor's k range inside an A row: k itself, or, with a segmented contraction
+    // index, the segment's start plus the position inside the segment (a step never straddles segments)
+    int64_t a_koff = 0;
+    int a_pos = 0;
     // loads H0 .. H1-1 of the step under the cursor; advance = this completes the step's loads
     auto issue = [&](int stage_off, auto H0, auto H1, bool advance) {
         const bool lastk = TAIL && kf == nk - 1;
 #pragma unroll
         for (int h = decltype(H0)::value; h < decltype(H1)::value; ++h) {
             const bool isa = 16 * (C::LPW * wave + h) < BM;                 // uniform
-            const unsigned char* p = (isa ? Abase : Bbase) + (size_t)kf * (C::BK * 2) + off[h];
+            const unsigned char* p = (isa ? Abase + a_koff : Bbase + (size_t)kf * (C::BK * 2)) + off[h];
             if (TAIL) p = (lastk && bad[h]) ? zero_piece : p;
             __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 0);
         }
-        if (advance && kf < nk - 1) ++kf;
+        if (advance && kf < nk - 1) {
+            ++kf;
+            a_koff += C::BK * 2;
+            if (d.a_seg) {
+                a_pos += C::BK;
+                if (a_pos == d.a_seg) { a_pos = 0; a_koff += (d.a_seg_stride - d.a_seg) * 2; }
+            }
+        }
     };
     constexpr std::integral_constant<int, 0> L0{};
     constexpr std::integral_constant<int, (C::LPW + 1) / 2> LH{};
@@ -319,7 +330,8 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
 bool mfma_gemm_supported(const GemmDesc& d) {
     return d.b_ks == 1 && d.K % 8 == 0 && d.a_rs % 8 == 0 && d.a_gs % 8 == 0 && d.b_rs % 8 == 0 &&
            d.b_gs % 8 == 0 && aligned16(d.A) && aligned16(d.B) && d.M > 0 && d.N > 0 && d.K > 0 &&
-           (int64_t)((d.M + 63) / 64) * ((d.N + 63) / 64) < (1ll << 30) && d.G <= 65535 && dma_offsets_fit(d, 256);
+           (int64_t)((d.M + 63) / 64) * ((d.N + 63) / 64) < (1ll << 30) && d.G <= 65535 && dma_offsets_fit(d, 256) &&
+           (d.a_seg == 0 || (d.a_seg % 32 == 0 && d.a_seg_stride % 8 == 0));
 }
 
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {

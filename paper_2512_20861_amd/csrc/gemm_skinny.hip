@@ -59,8 +59,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
         int k = ks * 32 + kg * 8;
         if (k > d.K - 8) k = d.K - 8;                   // k groups past K re-read valid data (K is a multiple of 8)
         rw[slot] = *(const uint4*)(wp + k);
+        // segmented contraction index of A: a k32 step lies inside one segment (uniform division)
+        const int64_t ka = d.a_seg ? (int64_t)((ks * 32) / d.a_seg) * (d.a_seg_stride - d.a_seg) + k : k;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) rx[slot][mt] = *(const uint4*)(xp[mt] + k);
+        for (int mt = 0; mt < MT; ++mt) rx[slot][mt] = *(const uint4*)(xp[mt] + ka);
     };
     f32x4 acc[MT];
 #pragma unroll

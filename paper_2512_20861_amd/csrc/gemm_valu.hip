@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void gemm_valu_kernel(GemmDesc d) {
             const int64_t m = m0 + row;
             const int k = k0 + kk;
             float a = 0.f, b = 0.f;
-            if (m < d.M && k < d.K) a = load_as_float(A + m * d.a_rs + k);
+            if (m < d.M && k < d.K) a = load_as_float(A + m * d.a_rs + (d.a_seg ? (int64_t)(k / d.a_seg) * d.a_seg_stride + k % d.a_seg : k));
             const int n = n0 + row;
             if (n < d.N && k < d.K) {
                 const int64_t nr = d.b_div ? (int64_t)(n % d.b_div) * d.b_mul + n / d.b_div : n;

@@ -89,6 +89,12 @@ def test_monarch_argument_checks():
     assert _monarch(flags=B.ONLY_FIRST_STAGE | B.ONLY_LAST_STAGE) == B.ERR_INVALID_ARG
     assert _blast(flags=B.BLAST_FUSED_STAGE12 | B.BLAST_THREE_KERNELS) == B.ERR_INVALID_ARG
     assert _monarch(flags=B.BLAST_THREE_KERNELS) == B.ERR_INVALID_ARG
+    # blocked input needs nblocks^2 | n_in
+    assert _monarch(n_in=60, n_out=60, nb=6, r=12, flags=B.MONARCH_IN_BLOCKED) == B.ERR_INVALID_ARG
+    L = B.lib()
+    assert L.blr_monarch_permute_first_factor(FAKE, FAKE, 64, 4, 16, B.BF16, None) == B.ERR_INVALID_ARG      # in place
+    assert L.blr_monarch_permute_first_factor(FAKE, FAKE + 0x1000, 60, 6, 12, B.BF16, None) == B.ERR_INVALID_ARG
+    assert L.blr_monarch_permute_first_factor(None, FAKE, 64, 4, 16, B.BF16, None) == B.ERR_INVALID_ARG
     assert _monarch(X=FAKE + 2) == B.ERR_INVALID_ARG               # misaligned pointer
     assert _monarch(ws=None) == B.ERR_WORKSPACE
     assert _monarch(wsb=16) == B.ERR_WORKSPACE

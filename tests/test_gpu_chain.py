@@ -110,14 +110,29 @@ def test_small_chain_end_to_end_and_per_linear(op, dtype):
     err = gu.rel_err(gu.to_f64(h), href)
     print(f"chain {op} {dtype} {n_layers} layers: end-to-end rel err {err:.3e}")
     assert err <= chain_tol(n_layers, dtype)
-    # every linear on its own: the oracle applied to the GPU's input of that call
+    # every linear on its own: the oracle applied to the GPU's input of that call. In the Monarch chain
+    # some activations travel in the blocked order (feature j*b + k at k*(n/b) + j): bring them to the
+    # canonical order for the oracle
+    nb = SMALL["monarch"]["nblocks"]
+    def canon(x):          # blocked -> canonical
+        T_, n = x.shape
+        return x.reshape(T_, nb, n // nb).transpose(0, 2, 1).reshape(T_, n)
+    assert chain.blocked == (op == "monarch")
     worst = 0.0
     for li, layer in enumerate(layers):
         for name in bi.CHAIN_LINEARS:
-            src, out = taps[f"{li}.{name}"]
-            e = gu.rel_err(gu.to_f64(out), lin(gu.to_f64(src), layer[name]))
+            src, out = (gu.to_f64(t) for t in taps[f"{li}.{name}"])
+            if chain.blocked and name in chain.IN_BLOCKED:
+                src = canon(src)
+            if chain.blocked and name in chain.OUT_BLOCKED:
+                out = canon(out)
+            e = gu.rel_err(out, lin(src, layer[name]))
             worst = max(worst, e)
             assert e <= gu.TOL[dtype], (li, name, e)
+    if op == "monarch":    # the same chain with every activation in canonical order agrees to rounding
+        plain = DeviceChain(layers, T, eps=oc.EPS, blocked_chaining=False)
+        assert not plain.blocked
+        assert gu.rel_err(gu.to_f64(plain.forward(gu.to_dev(x0))), href) <= chain_tol(n_layers, dtype)
     print(f"chain {op} {dtype}: worst single linear rel err {worst:.3e}")
     # glue steps on the GPU's own inputs
     for li in range(n_layers):

@@ -88,6 +88,66 @@ def test_blast_parity(T, n_in, n_out, b, r, dtype, mode):
     assert err <= gu.TOL[dtype]
 
 
+def _to_blocked(X64, b):
+    """Feature j*b + k -> position k*(n/b) + j (the BLOCKED output order of a Monarch layer with b blocks)."""
+    T, n = X64.shape
+    return X64.reshape(T, n // b, b).transpose(0, 2, 1).reshape(T, n)
+
+
+@pytest.mark.parametrize("T,n_in,n_out,nb,r,dtype", [
+    (8, 256, 256, 4, 64, "f32"), (8, 256, 256, 4, 64, "bf16"), (333, 512, 768, 4, 256, "bf16"),
+    (100, 1024, 512, 2, 128, "bf16"), (1, 2048, 2048, 4, 512, "bf16"), (700, 8192, 2048, 4, 512, "bf16"),
+    (50, 144, 72, 3, 12, "bf16")])
+@pytest.mark.parametrize("generic", [False, True])
+def test_monarch_blocked_input(T, n_in, n_out, nb, r, dtype, generic):
+    """A layer fed an activation in the BLOCKED order of an upstream layer, with its first factor
+    re-ordered once by the library, equals the oracle's layer on the canonical activation."""
+    gu = _gu()
+    B = gu.B
+    lay = bi.monarch_layer(n_in, n_out, nb, r, dtype)
+    X = bi.activations(T, n_in, dtype)
+    # the same values in blocked order, in the storage type
+    Xd = gu.to_dev(X)
+    Xb = Xd.reshape(T, n_in // nb, nb).transpose(1, 2).reshape(T, n_in).contiguous()
+    Rp = B.monarch_permute_first_factor(gu.to_dev(lay.R), n_in, nb, r)
+    # the re-ordering is a pure permutation of each row of R
+    Rh = gu.to_f64(Rp).reshape(nb * r, n_in // nb)
+    ref_rows = lay.R.f64.reshape(nb * r, n_in // nb // nb, nb).transpose(0, 2, 1).reshape(nb * r, n_in // nb)
+    assert np.array_equal(Rh, ref_rows)
+    Y = gu.empty_out(T, n_out, dtype)
+    B.monarch_forward(Xb, Rp, gu.to_dev(lay.L), Y, nb, r, B.MONARCH_IN_BLOCKED | (B.FORCE_GENERIC if generic else 0))
+    torch.cuda.synchronize()
+    Yref = oracle.monarch_forward(X.f64, lay.R.f64, lay.L.f64)
+    err = gu.rel_err(gu.to_f64(Y), Yref)
+    print(f"monarch blocked input {T}x{n_in}->{n_out} b={nb} r={r} {dtype} generic={generic}: rel err {err:.3e}")
+    assert err <= gu.TOL[dtype]
+    assert np.array_equal(_to_blocked(X.f64, nb), gu.to_f64(Xb))
+
+
+def test_monarch_blocked_pair_equals_canonical_pair():
+    """Producer with BLOCKED output feeding a consumer with BLOCKED input (an elementwise step in
+    between) reproduces the canonical two-layer result: the permutation is never materialised."""
+    gu = _gu()
+    B = gu.B
+    T, n0, n1, n2, nb = 200, 512, 2048, 512, 4
+    A = bi.monarch_layer(n0, n1, nb, 128, "bf16", layer_id=3)
+    C = bi.monarch_layer(n1, n2, nb, 128, "bf16", layer_id=4)
+    X = bi.activations(T, n0, "bf16")
+    H = gu.empty_out(T, n1, "bf16")
+    B.monarch_forward(gu.to_dev(X), gu.to_dev(A.R), gu.to_dev(A.L), H, nb, 128, B.MONARCH_OUT_BLOCKED)
+    B.silu_mul(H, H, H)                                    # any elementwise map commutes with the permutation
+    Rp = B.monarch_permute_first_factor(gu.to_dev(C.R), n1, nb, 128)
+    Y = gu.empty_out(T, n2, "bf16")
+    B.monarch_forward(H, Rp, gu.to_dev(C.L), Y, nb, 128, B.MONARCH_IN_BLOCKED)
+    torch.cuda.synchronize()
+    from oracle import chain as oc
+    h = oracle.monarch_forward(X.f64, A.R.f64, A.L.f64)
+    yref = oracle.monarch_forward(oc.silu(h) * h, C.R.f64, C.L.f64)
+    err = gu.rel_err(gu.to_f64(Y), yref)
+    print(f"monarch blocked pair: rel err {err:.3e}")
+    assert err <= gu.TOL["bf16"]
+
+
 # ---------------------------------------------------------------- dense
 @pytest.mark.parametrize("T,n_in,n_out,dtype", [(200, 320, 200, "bf16"), (200, 320, 200, "f32"),
                                                 (129, 1024, 130, "bf16"), (5, 100, 7, "bf16"), (1, 64, 64, "f32")])
