@@ -1,0 +1,95 @@
+"""Seeded random shapes through every dispatch regime (few tokens, every tile size, partial tiles in
+all three GEMM dimensions, partial last k-step, batched/scattered outputs), each against the oracle."""
+import numpy as np
+import pytest
+
+import blr_inputs as bi
+import oracle
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2512_20861_amd import binding
+    binding.lib()
+
+
+def _gu():
+    import gpu_util
+    return gpu_util
+
+
+def _dense_shapes():
+    rng = np.random.default_rng(20861)
+    out = []
+    for _ in range(28):
+        M = int(rng.choice([1, 3, 16, 17, 31, 32, 33, 64, 65, 127, 129, 200, 300, 513, 700]))
+        N = int(rng.integers(1, 140)) * 8
+        K = int(rng.integers(1, 140)) * 8
+        out.append((M, K, N))
+    out += [(1100, 264, 2056), (260, 1048, 264), (33, 8, 8), (2, 4096, 16)]
+    return out
+
+
+@pytest.mark.parametrize("T,n_in,n_out", _dense_shapes())
+def test_dense_random_shape(T, n_in, n_out):
+    gu = _gu()
+    W = bi.dense_weight(n_in, n_out, "bf16", seed=T * 131 + n_in)
+    X = bi.activations(T, n_in, "bf16", seed=n_out)
+    Y = gu.empty_out(T, n_out, "bf16")
+    gu.B.dense_reference_forward(gu.to_dev(X), gu.to_dev(W), Y)
+    torch.cuda.synchronize()
+    err = gu.rel_err(gu.to_f64(Y), oracle.dense_forward(X.f64, W.f64))
+    assert err <= gu.TOL["bf16"], (T, n_in, n_out, err)
+
+
+def _monarch_shapes():
+    rng = np.random.default_rng(7)
+    out = []
+    for _ in range(16):
+        b = int(rng.choice([1, 2, 3, 4, 8]))
+        p, q, rp = (int(rng.integers(1, 40)) * 8 for _ in range(3))
+        T = int(rng.choice([1, 5, 16, 30, 33, 100, 257, 600]))
+        out.append((T, b * p, b * q, b, b * rp))
+    return out
+
+
+@pytest.mark.parametrize("T,n_in,n_out,nb,r", _monarch_shapes())
+@pytest.mark.parametrize("order", ["interleaved", "blocked"])
+def test_monarch_random_shape(T, n_in, n_out, nb, r, order):
+    gu = _gu()
+    lay = bi.monarch_layer(n_in, n_out, nb, r, "bf16", seed=T + n_in)
+    X = bi.activations(T, n_in, "bf16", seed=r)
+    blocked = order == "blocked"
+    Y = gu.to_f64(gu.run_monarch(X, lay, gu.B.MONARCH_OUT_BLOCKED if blocked else 0))
+    Yref = oracle.monarch_forward(X.f64, lay.R.f64, lay.L.f64, oracle.OUT_BLOCKED if blocked else oracle.OUT_INTERLEAVED)
+    err = gu.rel_err(Y, Yref)
+    assert err <= gu.TOL["bf16"], (T, n_in, n_out, nb, r, order, err)
+
+
+def _blast_shapes():
+    rng = np.random.default_rng(11)
+    out = []
+    for _ in range(16):
+        b = int(rng.choice([1, 2, 4, 5, 8, 16]))
+        q, p = (int(rng.integers(1, 24)) * 8 for _ in range(2))
+        r = int(rng.integers(1, 60)) * 8
+        T = int(rng.choice([1, 7, 16, 33, 100, 129, 300, 1100]))
+        out.append((T, b * q, b * p, b, r))
+    return out
+
+
+@pytest.mark.parametrize("T,n_in,n_out,b,r", _blast_shapes())
+@pytest.mark.parametrize("mode", ["packed", "fused12", "three"])
+def test_blast_random_shape(T, n_in, n_out, b, r, mode):
+    gu = _gu()
+    lay = bi.blast_layer(n_in, n_out, b, r, "bf16", seed=T + r)
+    X = bi.activations(T, n_in, "bf16", seed=n_in)
+    flags = {"fused12": gu.B.BLAST_FUSED_STAGE12, "three": gu.B.BLAST_THREE_KERNELS}.get(mode, 0)
+    Y = gu.to_f64(gu.run_blast(X, lay, flags, packed=True))
+    err = gu.rel_err(Y, oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64))
+    assert err <= gu.TOL["bf16"], (T, n_in, n_out, b, r, mode, err)
