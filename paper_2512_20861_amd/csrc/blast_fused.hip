@@ -37,8 +37,6 @@ static_assert(ST_ROWS % 64 == 0, "every wavefront issues the same number of load
 constexpr int ST_LPW = ST_ROWS / 64;         // direct-to-LDS loads per wavefront and stage (8 rows each)
 static_assert(ST_LPW * (ST_PD - 1) < 64, "vmcnt range");
 
-// 16 zero bytes in global memory: the source of operand pieces that lie past the end of a block
-__device__ __attribute__((aligned(16))) const unsigned char zero_piece[16] = {0};
 
 // workgroup id -> logical tile id such that each XCD (workgroups are dealt round-robin over 8 XCDs)
 // works on a contiguous range of logical ids, i.e. shares its X tiles in its own L2
@@ -185,20 +183,22 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
     store_a_tile<8>(Zs, A, T, t0, rho0, b, r, [](int t) { return t; });
 }
 
-// Stage 1 + coupling. Per step (one 64-wide k chunk of one input block j) a stage of LDS holds 128
-// X rows and 64 Vt rows of 128 bytes; its 16-byte pieces are XOR-swizzled by (row / 2) & 7 so that the
-// 16 lanes a ds_read_b128 serves per clock (16 consecutive rows) hit 16 different 16-byte columns of
-// the 64 banks, without the row padding that a direct-to-LDS load cannot produce (lane l of such a
-// load always lands at base + 16 l). Loads for step s + ST_PD are issued while
-// step s computes; vmcnt counts them, so one wait + one barrier per step is all the synchronisation.
+// Stage 1 + coupling. Per step (one chunk of 64 input columns of one input block j) a stage of LDS
+// holds 128 X rows and 64 Vt rows of 128 bytes; its 16-byte pieces are XOR-swizzled by (row / 2) & 7 so
+// that the 16 lanes a ds_read_b128 serves per clock (16 consecutive rows) hit 16 different 16-byte
+// columns of the 64 banks, without the row padding that a direct-to-LDS load cannot produce (lane l of
+// such a load always lands at base + 16 l). Loads for step s + ST_PD are issued while step s computes;
+// vmcnt counts them, so one wait + one barrier per step is all the synchronisation.
 // The fragment reads are inline assembly with their own lgkmcnt waits: reads that the compiler can
 // see make it wait for ALL outstanding direct-to-LDS loads first.
-// TAIL: q is not a multiple of 64, i.e. the last k chunk of every input block is partial.
-template <bool TAIL>
+// The chunks are aligned to 64 GLOBAL input columns (n_in is a multiple of 64), not to the start of the
+// block: block j walks chunks floor(j q / 64) .. ceil((j+1) q / 64) - 1, so every X piece is one whole
+// 128-byte line whatever q is. The columns of a boundary chunk that belong to a neighbouring block
+// meet zeros in Va (the chunk-aligned copy of Vt, rows of qp elements), so nothing has to be masked.
 __global__ __launch_bounds__(512)
-void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Vt,
+void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Va,
                           const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
-                          int64_t T, int n_in, int b, int r, int tiles_r, int nblk) {
+                          int64_t T, int n_in, int b, int r, int qp, int tiles_r, int nblk) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -208,13 +208,13 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
     const int64_t t0 = (int64_t)tile_t * ST_TT;
     const int rho0 = tile_r * TR;
     const int q = n_in / b;
-    const int nkc = (q + ST_BK - 1) / ST_BK;
-    const int nsteps = b * nkc;
+    auto chunk_begin = [&](int j) { return (j * q) >> 6; };
+    auto chunks_of = [&](int j) { return (((j + 1) * q + 63) >> 6) - ((j * q) >> 6); };
+    const int nsteps = [&] { int n = 0; for (int j = 0; j < b; ++j) n += chunks_of(j); return n; }();
 
     // Load h of this wavefront fills operand rows 8 (ST_LPW wave + h) .. + 7 of a stage: lane l brings
     // the piece that belongs at row l / 8 of those, slot l % 8.
     int off[ST_LPW];
-    bool bad[ST_LPW];
 #pragma unroll
     for (int h = 0; h < ST_LPW; ++h) {
         const int row = 8 * (ST_LPW * wave + h) + (lane >> 3);
@@ -226,29 +226,26 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
         } else {
             int vr = rho0 + row - ST_TT;
             if (vr > r - 1) vr = r - 1;
-            off[h] = (vr * q + piece * 8) * 2;              // bytes from Vt[j]
+            off[h] = (vr * qp + piece * 8) * 2;             // bytes from Va[j]
         }
-        bad[h] = TAIL && (nkc - 1) * ST_BK + piece * 8 >= q;   // in a block's last chunk this piece lies past q
     }
     const unsigned char* xs = (const unsigned char*)(X + t0 * n_in);
-    const unsigned char* vs = (const unsigned char*)Vt;
-    const int x_wrap = (q - (nkc - 1) * ST_BK) * 2;                        // last chunk of block j -> first chunk of j+1
-    const int64_t v_wrap = ((int64_t)r * q - (int64_t)(nkc - 1) * ST_BK) * 2;
+    const unsigned char* vs = (const unsigned char*)Va;
+    const int64_t v_block = (int64_t)r * qp * 2;        // bytes of one Va[j]
 
-    int pk = 0, fetched = 0;                            // fetch cursor (uniform)
+    int fj = 0, fk = 0, fetched = 0;                    // fetch cursor (uniform): block, chunk within the block
     auto issue = [&](int stage_off) {
-        const bool lastc = TAIL && pk == nkc - 1;
+        const unsigned char* xc = xs + (size_t)(chunk_begin(fj) + fk) * (ST_BK * 2);
+        const unsigned char* vc = vs + fj * v_block + (size_t)fk * (ST_BK * 2);
 #pragma unroll
         for (int h = 0; h < ST_LPW; ++h) {
             const bool isx = 8 * (ST_LPW * wave + h) < ST_TT;              // uniform
-            const unsigned char* p = (isx ? xs : vs) + off[h];
-            if (TAIL) p = (lastc && bad[h]) ? zero_piece : p;
-            __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (ST_LPW * wave + h) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(BLR_GPTR((isx ? xc : vc) + off[h]),
+                                             BLR_LPTR(smem + stage_off + (ST_LPW * wave + h) * 1024), 16, 0, 0);
         }
         if (fetched < nsteps - 1) {                     // the cursor stops at the last step; later issues repeat it
             ++fetched;
-            if (pk == nkc - 1) { pk = 0; xs += x_wrap; vs += v_wrap; }
-            else { ++pk; xs += ST_BK * 2; vs += ST_BK * 2; }
+            if (++fk == chunks_of(fj)) { fk = 0; ++fj; }
         }
     };
 
@@ -301,13 +298,15 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
             f32x16 acc;
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+            const int n0 = chunks_of(2 * jp);
 #pragma unroll 1
-            for (int kc = 0; kc < nkc; ++kc) step(acc);
+            for (int kc = 0; kc < n0; ++kc) step(acc);
 #pragma unroll
             for (int e = 0; e < 16; ++e) { zq[e][jp] = pack2_bf16(acc[e], 0.f); acc[e] = 0.f; }
             if (2 * jp + 1 < b) {
+                const int n1 = chunks_of(2 * jp + 1);
 #pragma unroll 1
-                for (int kc = 0; kc < nkc; ++kc) step(acc);
+                for (int kc = 0; kc < n1; ++kc) step(acc);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) zq[e][jp] |= pack2_bf16(0.f, acc[e]);
             }
@@ -346,29 +345,26 @@ bool blast_fused_supported(int64_t T, int n_in, int b, int r) {
     if (T <= 0 || b <= 0 || b > 16 || n_in % b) return false;
     const int q = n_in / b;
     const int64_t nblk = blast_fused_tiles(T, r);
-    return q % 8 == 0 && r % 8 == 0 && nblk < (1ll << 30);
+    // 64 | n_in: the chunk grid is aligned to 64 input columns and must end with the row
+    return q % 8 == 0 && r % 8 == 0 && n_in % 64 == 0 && nblk < (1ll << 30) &&
+           ((int64_t)ST_TT * n_in + 64) * 2 < (1ll << 31) && ((int64_t)r * blast_va_row(q) + 64) * 2 < (1ll << 31);
 }
 
 int64_t blast_fused_tiles(int64_t T, int r) { return ((T + ST_TT - 1) / ST_TT) * ((r + TR - 1) / TR); }
 
-hipError_t launch_blast_stage12(const void* X, const void* Vt, const void* Sp, void* A,
+hipError_t launch_blast_stage12(const void* X, const void* Va, const void* Sp, void* A,
                                 int64_t T, int n_in, int b, int r, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)blast_stage12_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS);
+        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles_t = (int)((T + ST_TT - 1) / ST_TT), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
-    if ((n_in / b) % ST_BK)
-        hipLaunchKernelGGL(blast_stage12_kernel<true>, dim3((unsigned)nblk), dim3(512), ST_LDS, s,
-                           (const bf16_t*)X, (const bf16_t*)Vt, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r, tiles_r, nblk);
-    else
-        hipLaunchKernelGGL(blast_stage12_kernel<false>, dim3((unsigned)nblk), dim3(512), ST_LDS, s,
-                           (const bf16_t*)X, (const bf16_t*)Vt, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r, tiles_r, nblk);
+    hipLaunchKernelGGL(blast_stage12_kernel, dim3((unsigned)nblk), dim3(512), ST_LDS, s,
+                       (const bf16_t*)X, (const bf16_t*)Va, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r,
+                       blast_va_row(n_in / b), tiles_r, nblk);
     return hipGetLastError();
 }
 

@@ -24,6 +24,21 @@ __global__ __launch_bounds__(256) void pack_v_kernel(const bf16_t* V, bf16_t* Vt
     }
 }
 
+// Vt re-laid for the fused stage 1 + coupling kernel when q is not a multiple of 64: row (j, rho) holds
+// the k chunks of 64 GLOBAL input columns that block j touches, chunk c of the row = columns
+// 64 (cb + c) .. + 63 with cb = floor(j q / 64); positions outside [j q, (j+1) q) are zero. The
+// kernel can then walk X in 128-byte-aligned pieces, whatever q is.
+__global__ __launch_bounds__(256) void pack_va_kernel(const bf16_t* __restrict__ V, bf16_t* __restrict__ Va, int q, int r, int qp, int64_t total) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int x = (int)(e % qp);
+    const int rho = (int)((e / qp) % r);
+    const int j = (int)(e / ((int64_t)qp * r));
+    const int64_t gcol = (((int64_t)j * q) >> 6) * 64 + x;           // global input column
+    const int64_t c = gcol - (int64_t)j * q;
+    Va[e] = (c >= 0 && c < q) ? V[((int64_t)j * q + c) * r + rho] : (bf16_t)0;
+}
+
 // perm: the slot order of the single-kernel path, slot j' = (j % 8)*2 + j/8 holds input block j
 __global__ __launch_bounds__(256) void pack_s_kernel(const bf16_t* S, bf16_t* Sp, int b, int r, int perm) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -103,7 +118,7 @@ hipError_t launch_coupling_small(const void* Z, const void* S, void* A, int64_t 
     return hipGetLastError();
 }
 
-hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Sc, void* Vt, void* Vf, void* Uf,
+hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Sc, void* Vt, void* Va, void* Vf, void* Uf,
                              int n_in, int n_out, int b, int r, hipStream_t s) {
     const int q = n_in / b, p = n_out / b;
     if (Sc) {                                           // canonical S, for the few-token coupling
@@ -118,6 +133,12 @@ hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* 
     if (Vt) {
         dim3 gv((unsigned)((r + 31) / 32), (unsigned)((q + 31) / 32), (unsigned)b);
         hipLaunchKernelGGL(pack_v_kernel, gv, dim3(256), 0, s, (const bf16_t*)V, (bf16_t*)Vt, q, r);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (Va) {
+        const int qp = blast_va_row(q);
+        const int64_t total = (int64_t)b * r * qp;
+        hipLaunchKernelGGL(pack_va_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t*)V, (bf16_t*)Va, q, r, qp, total);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (Vf) {

@@ -29,7 +29,7 @@ bool blast_shape_ok(int64_t T, int n_in, int n_out, int b, int r) {
 // Where the re-laid-out BLAST factors live inside the packed buffer.
 struct PackLayout {
     bool full;                       // served by the single-kernel path: fragment-ordered V and U
-    size_t off_Sp, off_Sc, off_Vt, off_Vf, off_Uf, total;   // Sc: canonical S (large-rank layouts only)
+    size_t off_Sp, off_Sc, off_Vt, off_Va, off_Vf, off_Uf, total;   // Sc: canonical S; Va: chunk-aligned Vt (= Vt if 64 | q)
 };
 
 PackLayout pack_layout(int n_in, int n_out, int b, int r) {
@@ -42,6 +42,9 @@ PackLayout pack_layout(int n_in, int n_out, int b, int r) {
         pk.off_Uf = off; off += align_up(blast_uf_bytes(n_out, b, r));
     } else {
         pk.off_Vt = off; off += align_up((size_t)n_in * r * 2);
+        const int q = n_in / b;
+        if (q % 64) { pk.off_Va = off; off += align_up((size_t)b * r * blast_va_row(q) * 2); }
+        else pk.off_Va = pk.off_Vt;
         pk.off_Sc = off; off += align_up((size_t)b * b * r * 2);
     }
     pk.total = off;
@@ -101,6 +104,7 @@ blr_status run_pack(const void* U, const void* S, const void* V, void* packed, i
     const PackLayout pk = pack_layout(n_in, n_out, b, r);
     unsigned char* base = (unsigned char*)packed;
     return from_hip(launch_blast_pack(U, S, V, base + pk.off_Sp, pk.full ? nullptr : base + pk.off_Sc, pk.full ? nullptr : base + pk.off_Vt,
+                                      (pk.full || pk.off_Va == pk.off_Vt) ? nullptr : base + pk.off_Va,
                                       pk.full ? base + pk.off_Vf : nullptr, pk.full ? base + pk.off_Uf : nullptr,
                                       n_in, n_out, b, r, s));
 }
@@ -258,7 +262,7 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
     }
     if (pl.path == BlastPlan::MFMA_STAGE12) {
         if (first) {
-            blr_status st = from_hip(launch_blast_stage12(X, Vt, Sp, Aws, T, n_in, b, r, s));
+            blr_status st = from_hip(launch_blast_stage12(X, pack + pk.off_Va, Sp, Aws, T, n_in, b, r, s));
             if (st != BLR_OK) return st;
         }
         return last ? run_gemm(s3, dt, true, s) : BLR_OK;

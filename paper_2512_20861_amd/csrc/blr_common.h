@@ -110,7 +110,9 @@ hipError_t launch_blast_full(const void* X, const void* Sp, const void* Vf, cons
 hipError_t launch_coupling_small(const void* Z, const void* S, void* A, int64_t T, int b, int r, hipStream_t s);   // few tokens; canonical S
 
 // BLAST weight re-layout (bf16): Sp always; Vt (row-major transpose) if non-null; Vf and Uf if non-null
-hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Sc, void* Vt, void* Vf, void* Uf,
+// elements per (j, rho) row of the chunk-aligned copy of Vt: the 64-column chunks a block of q columns can touch
+inline int blast_va_row(int q) { return q % 64 ? ((q + 63) / 64 + 1) * 64 : q; }
+hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Sc, void* Vt, void* Va, void* Vf, void* Uf,
                              int n_in, int n_out, int b, int r, hipStream_t s);
 
 }  // namespace blr
