@@ -118,7 +118,7 @@ def gaussian(seed: int, tid: int, shape, scale: float, dtype: str, rows=None) ->
 
 
 # tensor ids of the per-tensor random streams
-TID_X, TID_R, TID_L, TID_U, TID_S, TID_V, TID_W = 1, 2, 3, 4, 5, 6, 7
+TID_X, TID_R, TID_L, TID_U, TID_S, TID_V, TID_W, TID_LRV, TID_LRU = 1, 2, 3, 4, 5, 6, 7, 8, 9
 
 
 @dataclass
@@ -142,6 +142,24 @@ class BlastLayer:
     U: HostTensor = field(repr=False, default=None)
     S: HostTensor = field(repr=False, default=None)
     V: HostTensor = field(repr=False, default=None)
+
+
+@dataclass
+class LowRankLayer:
+    n_in: int
+    n_out: int
+    r: int
+    dtype: str
+    V: HostTensor = field(repr=False, default=None)
+    U: HostTensor = field(repr=False, default=None)
+
+
+def lowrank_layer(n_in, n_out, r, dtype, seed=BASE_SEED, layer_id=0):
+    """V[r][n_in] ~ N(0,1)/sqrt(n_in), U[n_out][r] ~ N(0,1)/sqrt(r)."""
+    off = 16 * layer_id
+    return LowRankLayer(n_in, n_out, r, dtype,
+                        V=gaussian(seed, TID_LRV + off, (r, n_in), 1.0 / math.sqrt(n_in), dtype),
+                        U=gaussian(seed, TID_LRU + off, (n_out, r), 1.0 / math.sqrt(r), dtype))
 
 
 def monarch_layer(n_in, n_out, nblocks, r, dtype, seed=BASE_SEED, scale_R=None, scale_L=None, layer_id=0):
@@ -187,10 +205,16 @@ CONFIGS = {
     # BLAST, Llama-7B attention projection and MLP down
     "C3a": dict(op="blast", n_in=4096, n_out=4096, b=16, r=640, dtype="bf16", T=T_SWEEP, x_scale=1.0),
     "C3b": dict(op="blast", n_in=11008, n_out=4096, b=16, r=1024, dtype="bf16", T=T_SWEEP, x_scale=1.0),
+    # plain low-rank at the attention-projection shape: the rank of the roofline example (Section 3,
+    # Table 2) and the small rank at which full fusion pays on the paper's hardware (Appendix, Full Fusion)
+    "LRa": dict(op="lowrank", n_in=4096, n_out=4096, r=1024, dtype="bf16", T=T_SWEEP, x_scale=1.0),
+    "LRb": dict(op="lowrank", n_in=4096, n_out=4096, r=128, dtype="bf16", T=T_SWEEP, x_scale=1.0),
 }
 
 
 def make_layer(cfg: dict, seed=BASE_SEED, layer_id=0):
+    if cfg["op"] == "lowrank":
+        return lowrank_layer(cfg["n_in"], cfg["n_out"], cfg["r"], cfg["dtype"], seed, layer_id=layer_id)
     if cfg["op"] == "monarch":
         return monarch_layer(cfg["n_in"], cfg["n_out"], cfg["nblocks"], cfg["r"], cfg["dtype"], seed, layer_id=layer_id)
     return blast_layer(cfg["n_in"], cfg["n_out"], cfg["b"], cfg["r"], cfg["dtype"], seed, layer_id=layer_id)

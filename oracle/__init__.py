@@ -1,4 +1,5 @@
 """CPU oracle (test infrastructure only; never imported by the product path)."""
 from .binding import (build, monarch_forward, blast_forward, dense_forward,
                       materialize_monarch, materialize_blast, monarch_middle_perm,
+                      lowrank_forward, materialize_lowrank,
                       OUT_INTERLEAVED, OUT_BLOCKED)

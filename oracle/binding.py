@@ -35,7 +35,8 @@ def _load():
         _lib = ctypes.CDLL(_LIB)
         for name in ("blr_oracle_dense_forward", "blr_oracle_monarch_forward", "blr_oracle_blast_forward",
                      "blr_oracle_materialize_monarch", "blr_oracle_materialize_blast",
-                     "blr_oracle_monarch_middle_perm"):
+                     "blr_oracle_monarch_middle_perm", "blr_oracle_lowrank_forward",
+                     "blr_oracle_materialize_lowrank"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -96,6 +97,33 @@ def blast_forward(X, U, S, V, nthreads=None, return_macs=False):
     if rc:
         raise ValueError("oracle: invalid argument")
     return (Y, macs.value) if return_macs else Y
+
+
+def lowrank_forward(X, V, U, nthreads=None, return_macs=False):
+    """Y = (X V^T) U^T with V[r][n_in], U[n_out][r]."""
+    X, V, U = _f64(X), _f64(V), _f64(U)
+    T, n_in = X.shape
+    r = V.shape[0]
+    n_out = U.shape[0]
+    assert V.shape == (r, n_in) and U.shape == (n_out, r)
+    Y = np.empty((T, n_out), dtype=np.float64)
+    macs = ctypes.c_int64(0)
+    rc = _load().blr_oracle_lowrank_forward(_p(X), _p(V), _p(U), _p(Y), ctypes.c_int64(T), n_in, n_out, r,
+                                            nthreads or default_threads(), ctypes.byref(macs))
+    if rc:
+        raise ValueError("oracle: invalid argument")
+    return (Y, macs.value) if return_macs else Y
+
+
+def materialize_lowrank(V, U):
+    V, U = _f64(V), _f64(U)
+    r, n_in = V.shape
+    n_out = U.shape[0]
+    W = np.empty((n_out, n_in), dtype=np.float64)
+    rc = _load().blr_oracle_materialize_lowrank(_p(V), _p(U), _p(W), n_in, n_out, r)
+    if rc:
+        raise ValueError("oracle: invalid argument")
+    return W
 
 
 def materialize_monarch(R, L, out_order=OUT_INTERLEAVED):

@@ -1,4 +1,4 @@
-// CPU oracle for the block low-rank (BLR) linear forward pass: Monarch, BLAST, dense.
+// CPU oracle for the block low-rank (BLR) linear forward pass: Monarch, BLAST, low-rank, dense.
 //
 // THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT. It exists so that the GPU
 // library can be checked against an independent, slow, obviously-correct
@@ -252,6 +252,58 @@ int blr_oracle_materialize_blast(const double* U, const double* S, const double*
                                V[((int64_t)j * q + c) * r + rho];
                     W[((int64_t)i * p + a) * n_in + j * q + c] = acc;
                 }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Low-rank forward (Section 2.1 "Low-Rank (LR)": W = V U, Y = (X V) U, with
+// V in R^{i x r}, U in R^{r x o}). Both factors are stored with their
+// contraction index contiguous: V[r][n_in] (the paper's V transposed) and
+// U[n_out][r] (the paper's U transposed).
+//   1. Z[t][c] = sum_a X[t][a] * V[c][a]
+//   2. Y[t][o] = sum_c Z[t][c] * U[o][c]
+// ---------------------------------------------------------------------------
+int blr_oracle_lowrank_forward(const double* X, const double* V, const double* U, double* Y,
+                               int64_t T, int n_in, int n_out, int r, int nthreads, int64_t* macs) {
+    if (!X || !V || !U || !Y || T < 0 || n_in <= 0 || n_out <= 0 || r <= 0) return 1;
+    std::vector<int64_t> counts(std::max(nthreads, 1) + 1, 0);
+    parallel_over_tokens(T, nthreads, [&](int64_t t0, int64_t t1, int w) {
+        std::vector<double> Z((size_t)r);
+        int64_t n = 0;
+        for (int64_t t = t0; t < t1; ++t) {
+            const double* x = X + t * n_in;
+            for (int c = 0; c < r; ++c) {
+                const double* vrow = V + (int64_t)c * n_in;
+                double acc = 0.0;
+                for (int a = 0; a < n_in; ++a) acc += x[a] * vrow[a];
+                Z[c] = acc;
+                n += n_in;
+            }
+            double* y = Y + t * n_out;
+            for (int o = 0; o < n_out; ++o) {
+                const double* urow = U + (int64_t)o * r;
+                double acc = 0.0;
+                for (int c = 0; c < r; ++c) acc += Z[c] * urow[c];
+                y[o] = acc;
+                n += r;
+            }
+        }
+        counts[w] = n;
+    });
+    if (macs) { int64_t s = 0; for (auto c : counts) s += c; *macs = s; }
+    return 0;
+}
+
+// Dense weight a low-rank layer stands for: W[o][a] = sum_c U[o][c] V[c][a]
+// (Section 2.1 "Low-Rank (LR)", W = V U in the out x in orientation).
+int blr_oracle_materialize_lowrank(const double* V, const double* U, double* W, int n_in, int n_out, int r) {
+    if (!V || !U || !W || n_in <= 0 || n_out <= 0 || r <= 0) return 1;
+    for (int o = 0; o < n_out; ++o)
+        for (int a = 0; a < n_in; ++a) {
+            double acc = 0.0;
+            for (int c = 0; c < r; ++c) acc += U[(int64_t)o * r + c] * V[(int64_t)c * n_in + a];
+            W[(int64_t)o * n_in + a] = acc;
+        }
     return 0;
 }
 
