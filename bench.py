@@ -63,6 +63,10 @@ class GpuLayer:
             self.ws = torch.empty(max(B.monarch_workspace_bytes(T, self.n_in, self.n_out, self.nb, self.r, dt), 16),
                                   dtype=torch.uint8, device="cuda")
             self.flags = 0
+        elif self.op == "lowrank":
+            self.V, self.U, self.r = to_dev(lay.V), to_dev(lay.U), cfg["r"]
+            self.ws = torch.empty(max(B.lowrank_workspace_bytes(T, self.n_in, self.n_out, self.r, dt), 16), dtype=torch.uint8, device="cuda")
+            self.flags = 0
         else:
             self.U, self.S, self.V = to_dev(lay.U), to_dev(lay.S), to_dev(lay.V)
             self.b, self.r = cfg["b"], cfg["r"]
@@ -80,6 +84,8 @@ class GpuLayer:
         B = self.B
         if self.op == "monarch":
             return (B.monarch_forward, self.X, self.R, self.L, self.Y, self.nb, self.r, self.flags | extra_flags, self.ws)
+        if self.op == "lowrank":
+            return (B.lowrank_forward, self.X, self.V, self.U, self.Y, self.flags | extra_flags, self.ws)
         if self.flags & B.BLAST_PACKED:
             return (B.blast_forward, self.X, self.U, None, self.packed, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
         return (B.blast_forward, self.X, self.U, self.S, self.V, self.Y, self.b, self.r, self.flags | extra_flags, self.ws)
@@ -165,6 +171,8 @@ def cpu_baseline(cfg, T_cpu):
     nthreads = oracle.binding.default_threads()
     if cfg["op"] == "monarch":
         fn = lambda: oracle.monarch_forward(X.f64, lay.R.f64, lay.L.f64, nthreads=nthreads)
+    elif cfg["op"] == "lowrank":
+        fn = lambda: oracle.lowrank_forward(X.f64, lay.V.f64, lay.U.f64, nthreads=nthreads)
     else:
         fn = lambda: oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64, nthreads=nthreads)
     fn()                                                 # warm-up
@@ -196,8 +204,13 @@ def dominant_roofline(layer, ms_total, stages):
     else:
         first_dom = stages[0] >= stages[1]
         ms = stages[0] if first_dom else stages[1]
-        inter = T * b * r * es                       # Z' (Monarch) or A (BLAST), written by the first, read by the last
-        if cfg["op"] == "monarch":
+        inter = T * b * r * es                       # Z' (Monarch), A (BLAST) or Z (low-rank, b = 1), written by the first, read by the last
+        if cfg["op"] == "lowrank":
+            if first_dom:
+                kern, byt, flo = "stage 1 (X V^T)", es * (T * n_in + r * n_in) + inter, 2 * T * r * n_in
+            else:
+                kern, byt, flo = "stage 2 (Z U^T)", inter + es * (r * n_out + T * n_out), 2 * T * r * n_out
+        elif cfg["op"] == "monarch":
             if first_dom:
                 kern, byt, flo = "stage 1 (block-diagonal R + permutation)", es * (T * n_in + r * n_in) + inter, 2 * T * r * n_in
             else:
@@ -244,11 +257,13 @@ def time_cold(make_calls, steps, warmup):
     return time_graph(make_call, steps, warmup)
 
 
-def run_sweep(steps, warmup):
+def run_sweep(steps, warmup, only=None):
     import torch
     from paper_2512_20861_amd import binding as B
     rows = []
-    for name in ("C1", "C2a", "C2b", "C3a", "C3b"):
+    for name in ("C1", "C2a", "C2b", "C3a", "C3b", "LRa", "LRb"):
+        if only and name not in only:
+            continue
         cfg = bi.CONFIGS[name]
         W = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
         for T in cfg["T"]:
@@ -418,6 +433,7 @@ def main():
     ap.add_argument("--workload", default="C1", choices=sorted(bi.CONFIGS) + ["C4-monarch", "C4-blast"])
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
     ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--sweep-configs", default="", help="comma-separated subset of the configurations for --sweep")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run an elementwise pass over 64 MiB in / 64 MiB out (scales the HBM byte counters)")
@@ -488,7 +504,7 @@ def main():
         T_cpu = min(T, {"C1": 6304, "C0": 8}.get(args.workload, 512))
         out["cpu_baseline"] = cpu_baseline(cfg, T_cpu)
     if args.sweep:
-        out["sweep"] = run_sweep(max(args.steps // 4, 20), max(args.warmup // 2, 5))
+        out["sweep"] = run_sweep(max(args.steps // 4, 20), max(args.warmup // 2, 5), set(filter(None, args.sweep_configs.split(","))))
     print(json.dumps(out), flush=True)
 
 

@@ -103,6 +103,23 @@ blr_status blr_monarch_permute_first_factor(const void* R, void* Rp, int n_in, i
                                             blr_dtype dt, blr_stream stream);
 
 /*
+ * Low-rank forward (paper Section 2.1 "Low-Rank (LR)": W = V U, Y = (X V) U; Section 3 uses it as the
+ * compute-bound structured baseline; Appendix "Full Fusion" discusses its single-kernel form):
+ *   Z[t][c] = sum_a X[t][a] * V[c][a],   Y[t][o] = sum_c Z[t][c] * U[o][c].
+ * X[T][n_in]; V[r][n_in] and U[n_out][r] are the paper's factors stored transposed, so that both
+ * contraction indices are contiguous (a one-time offline transposition of static weights);
+ * Y[T][n_out]. workspace: at least blr_lowrank_workspace_bytes(...) bytes (holds Z, T*r elements).
+ * flags: BLR_FORCE_GENERIC, BLR_ONLY_FIRST_STAGE, BLR_ONLY_LAST_STAGE. Errors as for the other
+ * forwards (BLR_ERR_INVALID_ARG for null factors, non-positive sizes, pointers not 16-byte aligned,
+ * unknown flags; BLR_ERR_WORKSPACE; T == 0 returns BLR_OK without launching).
+ */
+size_t     blr_lowrank_workspace_bytes(int64_t T, int n_in, int n_out, int r, blr_dtype dt);
+blr_status blr_lowrank_forward(const void* X, const void* V, const void* U, void* Y,
+                               int64_t T, int n_in, int n_out, int r,
+                               blr_dtype dt, unsigned flags,
+                               void* workspace, size_t workspace_bytes, blr_stream stream);
+
+/*
  * BLAST forward (paper Section 2.1 "BLAST"; Section 4 "BLAST", optimisations 4-5).
  * With q = n_in/b, p = n_out/b:
  *   Z[t][j][rho]  = sum_c X[t][j*q+c] * V[j][c][rho]

@@ -28,9 +28,9 @@ EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forw
            "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_bytes",
            "blr_blast_pack", "blr_dense_reference_forward",
            "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul",
-           "blr_monarch_permute_first_factor")
+           "blr_monarch_permute_first_factor", "blr_lowrank_workspace_bytes", "blr_lowrank_forward")
 # entry points that enqueue work and return a status: the ones prepared() can record
-_LAUNCHERS = ("blr_monarch_forward", "blr_blast_forward", "blr_dense_reference_forward",
+_LAUNCHERS = ("blr_monarch_forward", "blr_blast_forward", "blr_dense_reference_forward", "blr_lowrank_forward",
               "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul")
 
 _lib = None
@@ -57,6 +57,10 @@ def lib() -> ctypes.CDLL:
         L.blr_monarch_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci]
         L.blr_monarch_forward.restype = ci
         L.blr_monarch_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, cu, vp, sz, vp]
+        L.blr_lowrank_workspace_bytes.restype = sz
+        L.blr_lowrank_workspace_bytes.argtypes = [i64, ci, ci, ci, ci]
+        L.blr_lowrank_forward.restype = ci
+        L.blr_lowrank_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, cu, vp, sz, vp]
         L.blr_blast_workspace_bytes.restype = sz
         L.blr_blast_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.blr_blast_forward.restype = ci
@@ -136,8 +140,26 @@ def monarch_permute_first_factor(R, n_in, nblocks, r, stream=None):
     """First factor re-ordered for MONARCH_IN_BLOCKED (one-time weight preparation); returns the new tensor."""
     Rp = torch.empty_like(R)
     _check(lib().blr_monarch_permute_first_factor(_ptr(R), _ptr(Rp), n_in, nblocks, r, _dt(R), _stream(stream)),
-           "blr_monarch_permute_first_factor")
+           "blr_monarch_permute_first_factor", "blr_lowrank_workspace_bytes", "blr_lowrank_forward")
     return Rp
+
+
+def lowrank_workspace_bytes(T, n_in, n_out, r, dt) -> int:
+    return lib().blr_lowrank_workspace_bytes(T, n_in, n_out, r, dt)
+
+
+def lowrank_forward(X, V, U, Y, flags=0, workspace=None, stream=None):
+    """Y[T][n_out] <- (X[T][n_in] V[r][n_in]^T) U[n_out][r]^T."""
+    T, n_in = X.shape
+    n_out, r = U.shape
+    dt = _dt(X)
+    if workspace is None:
+        workspace = torch.empty(max(lowrank_workspace_bytes(T, n_in, n_out, r, dt), 16), dtype=torch.uint8, device=X.device)
+    global _last_workspace
+    _last_workspace = workspace
+    _check(lib().blr_lowrank_forward(_ptr(X), _ptr(V), _ptr(U), _ptr(Y), T, n_in, n_out, r, dt, flags,
+                                     _ptr(workspace), workspace.numel(), _stream(stream)), "blr_lowrank_forward")
+    return Y
 
 
 def blast_workspace_bytes(T, n_in, n_out, b, r, dt, flags=0) -> int:

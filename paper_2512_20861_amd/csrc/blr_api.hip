@@ -1,6 +1,7 @@
 // C-ABI front end: argument validation, workspace planning, kernel selection. Host code only.
 #include "../../include/blr.h"
 #include "blr_common.h"
+#include <algorithm>
 
 using namespace blr;
 
@@ -169,6 +170,50 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
     if (flags & BLR_MONARCH_OUT_BLOCKED) { s2.c_gs = q; s2.c_hi = 1; }
     else { s2.c_gs = 1; s2.c_hi = b; }
     s2.M = T; s2.N = q; s2.K = r; s2.G = b;
+    return run_gemm(s2, dt, allow_mfma, s);
+}
+
+size_t blr_lowrank_workspace_bytes(int64_t T, int n_in, int n_out, int r, blr_dtype dt) {
+    if (T < 0 || T >= (1ll << 31) || n_in <= 0 || n_out <= 0 || r <= 0 || !dtype_ok(dt)) return 0;
+    size_t split = 0;                                   // fp32 partial tiles of a split contraction (either stage)
+    if (dt == BLR_BF16) split = std::max(gemm_split_scratch_bytes(T, r, n_in, 1), gemm_split_scratch_bytes(T, n_out, r, 1));
+    return align_up((size_t)T * r * elem_size(dt)) + align_up(split);
+}
+
+blr_status blr_lowrank_forward(const void* X, const void* V, const void* U, void* Y,
+                               int64_t T, int n_in, int n_out, int r, blr_dtype dt, unsigned flags,
+                               void* workspace, size_t workspace_bytes, blr_stream stream) {
+    if (T < 0 || T >= (1ll << 31) || n_in <= 0 || n_out <= 0 || r <= 0 || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if (!V || !U) return BLR_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(V) || !aligned16(U) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
+    if (T == 0) return BLR_OK;
+    if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < blr_lowrank_workspace_bytes(T, n_in, n_out, r, dt)) return BLR_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const bool allow_mfma = !(flags & BLR_FORCE_GENERIC);
+    // Z[T][r] = X V^T, then Y = Z U^T: two plain NT products, the narrow intermediate in the workspace.
+    // With few tokens and a narrow rank the first product has few tiles and a long contraction index:
+    // the rest of the workspace lets the GEMM split that index over several workgroups per tile.
+    const size_t z_bytes = align_up((size_t)T * r * elem_size(dt));
+    float* scratch = workspace_bytes > z_bytes ? (float*)((char*)workspace + z_bytes) : nullptr;
+    GemmDesc s1{};
+    s1.split_scratch = scratch; s1.split_scratch_bytes = workspace_bytes - z_bytes;
+    s1.A = X; s1.a_rs = n_in;
+    s1.B = V; s1.b_rs = n_in; s1.b_ks = 1;
+    s1.C = workspace; s1.c_rs = r; s1.c_div = 1; s1.c_hi = 1;
+    s1.M = T; s1.N = r; s1.K = n_in; s1.G = 1;
+    if (!(flags & BLR_ONLY_LAST_STAGE)) {
+        blr_status st = run_gemm(s1, dt, allow_mfma, s);
+        if (st != BLR_OK || (flags & BLR_ONLY_FIRST_STAGE)) return st;
+    }
+    GemmDesc s2{};
+    s2.split_scratch = scratch; s2.split_scratch_bytes = workspace_bytes - z_bytes;
+    s2.A = workspace; s2.a_rs = r;
+    s2.B = U; s2.b_rs = r; s2.b_ks = 1;
+    s2.C = Y; s2.c_rs = n_out; s2.c_div = 1; s2.c_hi = 1;
+    s2.M = T; s2.N = n_out; s2.K = r; s2.G = 1;
     return run_gemm(s2, dt, allow_mfma, s);
 }
 

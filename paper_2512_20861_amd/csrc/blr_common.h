@@ -69,6 +69,7 @@ struct GemmDesc {
     const void* B; int64_t b_gs; int64_t b_rs; int64_t b_ks; int b_div; int b_mul;
     void* C; int64_t c_rs; int64_t c_gs; int c_div; int64_t c_hi; int64_t c_lo;
     int64_t M; int N; int K; int G;
+    float* split_scratch; size_t split_scratch_bytes;   // optional: room for fp32 partial tiles of a split contraction
 };
 
 enum class DType { F32 = 0, BF16 = 1 };
@@ -84,6 +85,9 @@ hipError_t launch_monarch_permute_first_factor(const void* R, void* Rp, int n_in
 // bf16 MFMA kernels; `mfma_gemm_supported` states the alignment contract
 bool mfma_gemm_supported(const GemmDesc& d);
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s);
+// scratch bytes with which launch_gemm_mfma may split the contraction index of an (M, N, K, G) product
+// over several workgroups per tile (0: it would not split)
+size_t gemm_split_scratch_bytes(int64_t M, int N, int K, int G);
 // few tokens (M <= 32): weight-streaming kernel, split-K inside the workgroup; same alignment contract
 bool skinny_gemm_supported(const GemmDesc& d);
 hipError_t launch_gemm_skinny(const GemmDesc& d, bool cvec, hipStream_t s);

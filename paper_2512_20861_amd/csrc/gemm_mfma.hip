@@ -144,7 +144,7 @@ struct DmaCfg {
 
 // TAIL: K is not a multiple of 32, the last step is partial
 template <int BM, int BN, int WGM, int WGN, int NS, bool TAIL>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int gfast) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int gfast, int kspan) {
     using C = DmaCfg<BM, BN, WGM, WGN, NS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -154,15 +154,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, in
     workgroup_tile(d, tiles_m, tiles_n, gfast, g, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     const int n0 = tile_n * BN;
+    // Split contraction: workgroup z of a tile covers k steps [z kspan, (z+1) kspan) and leaves its fp32
+    // accumulators in the scratch buffer; a second kernel adds the parts in a fixed order.
+    const int kb = blockIdx.z * kspan * C::BK;         // first contraction index of this workgroup
+    const int Kloc = d.K - kb < kspan * C::BK ? d.K - kb : kspan * C::BK;
     const unsigned char* Abase = (const unsigned char*)((const bf16_t*)d.A + (int64_t)g * d.a_gs + m0 * d.a_rs);
-    const unsigned char* Bbase = (const unsigned char*)((const bf16_t*)d.B + (int64_t)g * d.b_gs);
+    const unsigned char* Bbase = (const unsigned char*)((const bf16_t*)d.B + (int64_t)g * d.b_gs + kb);
 
     // Direct load h of this wavefront fills stage rows 16 (LPW wave + h) .. + 15 (A rows first, then B
     // rows): lane l brings the piece that belongs at row l / 4 of those, slot l % 4. Offsets are bytes
     // from Abase / Bbase (the launcher checks that they fit 32 bits).
     unsigned off[C::LPW];
     bool bad[C::LPW];
-    const int nk = (d.K + C::BK - 1) / C::BK;
+    const int nk = (Kloc + C::BK - 1) / C::BK;
 #pragma unroll
     for (int h = 0; h < C::LPW; ++h) {
         const int row = 16 * (C::LPW * wave + h) + (lane >> 2);
@@ -177,13 +181,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, in
             const int64_t nr = d.b_div ? (int64_t)(n % d.b_div) * d.b_mul + n / d.b_div : n;
             off[h] = (unsigned)((nr * d.b_rs + piece * 8) * 2);
         }
-        bad[h] = TAIL && (nk - 1) * C::BK + piece * 8 >= d.K;    // in the last step this piece lies past K
+        bad[h] = TAIL && (nk - 1) * C::BK + piece * 8 >= Kloc;   // in the last step this piece lies past K
     }
     int kf = 0;                                         // fetch cursor (uniform); stops at the last step
     // byte offset of the cursor's k range inside an A row: k itself, or, with a segmented contraction
     // index, the segment's start plus the position inside the segment (a step never straddles segments)
-    int64_t a_koff = 0;
-    int a_pos = 0;
+    int a_pos = d.a_seg ? kb % d.a_seg : 0;
+    int64_t a_koff = d.a_seg ? ((int64_t)(kb / d.a_seg) * d.a_seg_stride + a_pos) * 2 : (int64_t)kb * 2;
     // loads H0 .. H1-1 of the step under the cursor; advance = this completes the step's loads
     auto issue = [&](int stage_off, auto H0, auto H1, bool advance) {
         const bool lastk = TAIL && kf == nk - 1;
@@ -283,11 +287,81 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, in
         issue(fstage, L0, LH, false);                   // first half of the loads of step kt + PD
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the repeated loads of the last steps have landed too
+    if (gridDim.z > 1) {                                // split contraction: fp32 partial tile, accumulator order
+        const int64_t tile = ((int64_t)g * tiles_m + tile_m) * tiles_n + tile_n;
+        float* P = d.split_scratch + ((int64_t)blockIdx.z * tiles_m * tiles_n * d.G + tile) * (BM * BN);
+#pragma unroll
+        for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *(float4*)(P + ((((i * C::NI + j) * 4 + q4) * C::THREADS + tid) << 2)) =
+                        make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]);
+        return;
+    }
     __syncthreads();
     store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
 }
 
+// Second kernel of a split contraction: adds the nsplit partial tiles in index order (so the result
+// does not depend on timing) and writes C through the column map. One thread per group of four
+// consecutive columns (one float4 of the partial tile, which is in accumulator order: element e of
+// float4 (q4, tid) of a 64 x 64 tile on 2 x 2 wavefronts is row wm*32 + lane%32, column
+// wn*32 + 8*q4 + 4*(lane/32) + e); the loads of four parts are in flight together.
+__global__ __launch_bounds__(256) void gemm_split_reduce_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec4, int nsplit) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q4 = blockIdx.x & 3;
+    const int64_t tile = blockIdx.x >> 2;                                    // (g * tiles_m + tile_m) * tiles_n + tile_n
+    const int tile_n = (int)(tile % tiles_n), tile_m = (int)((tile / tiles_n) % tiles_m), g = (int)(tile / ((int64_t)tiles_n * tiles_m));
+    const int64_t part = (int64_t)tiles_m * tiles_n * d.G * 4096;             // floats per part
+    const float* P = d.split_scratch + tile * 4096 + ((q4 * 256 + tid) << 2);
+    float4 v = *(const float4*)P;
+    for (int z = 1; z < nsplit; z += 4) {
+        float4 w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w[u] = *(const float4*)(P + (z + u < nsplit ? z + u : nsplit - 1) * part);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (z + u < nsplit) { v.x += w[u].x; v.y += w[u].y; v.z += w[u].z; v.w += w[u].w; }
+    }
+    const int64_t m = (int64_t)tile_m * 64 + (wave >> 1) * 32 + (lane & 31);
+    const int n = tile_n * 64 + (wave & 1) * 32 + 8 * q4 + 4 * (lane >> 5);
+    if (m >= d.M || n >= d.N) return;
+    bf16_t* Cp = (bf16_t*)d.C + m * d.c_rs;
+    if (cvec4) {                                                             // four consecutive columns are 8 contiguous bytes of C
+        const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
+        *(uint2*)(Cp + col) = make_uint2(pack2_bf16(v.x, v.y), pack2_bf16(v.z, v.w));
+    } else {
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (n + i < d.N) {
+                const int ni = n + i;
+                Cp[(int64_t)g * d.c_gs + (int64_t)(ni / d.c_div) * d.c_hi + (int64_t)(ni % d.c_div) * d.c_lo] = float_to_bf16(e[i]);
+            }
+    }
+}
+
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// How many workgroups share the contraction index of one tile, and how many k steps each takes.
+// Splitting pays when a call has too few tiles to keep the chip's memory pipes full: every
+// workgroup has a bounded number of bytes in flight, so the bandwidth a call can draw grows with
+// the number of workgroups. Parts of at least 8 steps; about 384 workgroups; at most 16 parts.
+struct SplitPlan { int nsplit, kspan; };
+inline SplitPlan split_plan(int64_t ntiles, int K) {
+    const int nk = (K + 31) / 32;
+    SplitPlan sp{1, nk};
+    if (ntiles >= 256 || nk < 16) return sp;
+    int want = (int)((384 + ntiles - 1) / ntiles);
+    if (want > 16) want = 16;
+    if (want > nk / 8) want = nk / 8;
+    if (want < 2) return sp;
+    sp.kspan = (nk + want - 1) / want;
+    sp.nsplit = (nk + sp.kspan - 1) / sp.kspan;
+    return sp;
+}
 
 // can 8 consecutive (8-aligned) tile columns be stored as one 16-byte vector?
 inline bool c_map_vectorizes(const GemmDesc& d) {
@@ -303,7 +377,7 @@ inline bool dma_offsets_fit(const GemmDesc& d, int bm) {
 }
 
 template <int BM, int BN, int WGM, int WGN, int NS = 4>
-hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
+hipError_t launch_dma(const GemmDesc& d, hipStream_t s, bool allow_split = false) {
     using C = DmaCfg<BM, BN, WGM, WGN, NS>;
     static bool attr_set = false;   // benign if set twice
     if (!attr_set) {
@@ -317,12 +391,23 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s) {
     const int tiles_n = (d.N + BN - 1) / BN;
     const bool vec = c_map_vectorizes(d);
     const bool gfast = !vec && d.G > 1 && (int64_t)tiles_m * tiles_n * d.G < (1ll << 31);
-    dim3 grid(gfast ? (unsigned)(tiles_m * tiles_n * d.G) : (unsigned)(tiles_m * tiles_n), gfast ? 1u : (unsigned)d.G);
+    const int64_t ntiles = (int64_t)tiles_m * tiles_n * d.G;
+    SplitPlan sp = split_plan(ntiles, d.K);
+    if (!allow_split || !d.split_scratch || (size_t)sp.nsplit * ntiles * BM * BN * sizeof(float) > d.split_scratch_bytes)
+        sp = SplitPlan{1, (d.K + C::BK - 1) / C::BK};
+    dim3 grid(gfast ? (unsigned)(tiles_m * tiles_n * d.G) : (unsigned)(tiles_m * tiles_n), gfast ? 1u : (unsigned)d.G, (unsigned)sp.nsplit);
     if (d.K % C::BK)
-        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0, sp.kspan);
     else
-        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
-    return hipGetLastError();
+        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0, sp.kspan);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || sp.nsplit == 1) return e;
+    if constexpr (BM == 64 && BN == 64 && WGM == 2 && WGN == 2) {   // the only tile the split plan is used with
+        // (a column map that keeps groups of 8 columns contiguous keeps groups of 4 contiguous too)
+        hipLaunchKernelGGL(gemm_split_reduce_kernel, dim3((unsigned)(ntiles * 4)), dim3(256), 0, s, d, tiles_m, tiles_n, vec ? 1 : 0, sp.nsplit);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace
@@ -332,6 +417,13 @@ bool mfma_gemm_supported(const GemmDesc& d) {
            d.b_gs % 8 == 0 && aligned16(d.A) && aligned16(d.B) && d.M > 0 && d.N > 0 && d.K > 0 &&
            (int64_t)((d.M + 63) / 64) * ((d.N + 63) / 64) < (1ll << 30) && d.G <= 65535 && dma_offsets_fit(d, 256) &&
            (d.a_seg == 0 || (d.a_seg % 32 == 0 && d.a_seg_stride % 8 == 0));
+}
+
+size_t gemm_split_scratch_bytes(int64_t M, int N, int K, int G) {
+    if (M <= 32) return 0;                              // the few-token kernel splits inside its workgroups
+    const int64_t ntiles = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * G;
+    const SplitPlan sp = split_plan(ntiles, K);
+    return sp.nsplit > 1 ? (size_t)sp.nsplit * ntiles * 64 * 64 * sizeof(float) : 0;
 }
 
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
@@ -345,6 +437,8 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     if (d.M > 64 && d.N > 64 && tiles(128, 128) >= kFill) return launch_dma<128, 128, 2, 2>(d, s);
     if (d.M > 64 && tiles(128, 64) >= kFill) return launch_dma<128, 64, 2, 2>(d, s);
     if (d.N > 64 && tiles(64, 128) >= kFill) return launch_dma<64, 128, 2, 2>(d, s);
+    // few tiles and a long contraction: 64 x 64 tiles, contraction index split over several workgroups
+    if (d.split_scratch && split_plan(tiles(64, 64), d.K).nsplit > 1) return launch_dma<64, 64, 2, 2>(d, s, true);
     if (tiles(64, 64) >= kFill || (d.M <= 64 && d.N <= 64)) return launch_dma<64, 64, 2, 2>(d, s);
     // too small to fill the chip with any tile: fewest, largest tiles that fit the shape
     if (d.M > 64 && d.N > 64) return tiles(64, 64) >= 64 ? launch_dma<64, 64, 2, 2>(d, s) : launch_dma<128, 128, 2, 2>(d, s);

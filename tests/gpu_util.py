@@ -42,6 +42,13 @@ def run_monarch(X, lay, flags=0):
     return Y
 
 
+def run_lowrank(X, lay, flags=0):
+    Y = empty_out(X.shape[0], lay.n_out, lay.dtype)
+    B.lowrank_forward(to_dev(X), to_dev(lay.V), to_dev(lay.U), Y, flags)
+    torch.cuda.synchronize()
+    return Y
+
+
 def run_blast(X, lay, flags=0, packed=False):
     Xd, Ud, Sd, Vd = to_dev(X), to_dev(lay.U), to_dev(lay.S), to_dev(lay.V)
     Y = empty_out(X.shape[0], lay.n_out, lay.dtype)

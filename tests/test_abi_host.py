@@ -118,6 +118,30 @@ def test_blast_argument_checks():
     assert _blast(T=64, n_in=4096, n_out=4096, b=16, r=640, ws=None, wsb=0) == B.ERR_WORKSPACE
 
 
+def _lowrank(T=4, n_in=64, n_out=48, r=16, dt=B.BF16, flags=0, X=FAKE, V=FAKE, U=FAKE, Y=FAKE, ws=FAKE, wsb=1 << 20):
+    return B.lib().blr_lowrank_forward(X, V, U, Y, T, n_in, n_out, r, dt, flags, ws, wsb, None)
+
+
+def test_lowrank_argument_checks():
+    assert B.lowrank_workspace_bytes(8192, 4096, 4096, 128, B.BF16) == 8192 * 128 * 2     # Z[T][r]
+    assert B.lowrank_workspace_bytes(3, 10, 10, 5, B.F32) == 256                          # rounded up to 256 bytes
+    assert B.lowrank_workspace_bytes(3, 10, 0, 5, B.F32) == 0
+    assert _lowrank(T=0) == B.OK
+    assert _lowrank(T=0, X=None, Y=None) == B.OK
+    assert _lowrank(T=-1) == B.ERR_INVALID_ARG
+    assert _lowrank(V=None) == B.ERR_INVALID_ARG
+    assert _lowrank(U=None) == B.ERR_INVALID_ARG
+    assert _lowrank(Y=None) == B.ERR_INVALID_ARG
+    assert _lowrank(r=0) == B.ERR_INVALID_ARG
+    assert _lowrank(n_in=-4) == B.ERR_INVALID_ARG
+    assert _lowrank(dt=5) == B.ERR_INVALID_ARG
+    assert _lowrank(flags=B.MONARCH_OUT_BLOCKED) == B.ERR_INVALID_ARG
+    assert _lowrank(flags=B.ONLY_FIRST_STAGE | B.ONLY_LAST_STAGE) == B.ERR_INVALID_ARG
+    assert _lowrank(U=FAKE + 4) == B.ERR_INVALID_ARG
+    assert _lowrank(ws=None) == B.ERR_WORKSPACE
+    assert _lowrank(wsb=64) == B.ERR_WORKSPACE
+
+
 def test_dense_and_pack_argument_checks():
     lib = B.lib()
     assert lib.blr_dense_reference_forward(FAKE, FAKE, FAKE, 0, 8, 8, B.BF16, 0, None) == B.OK

@@ -164,6 +164,59 @@ def test_dense_parity(T, n_in, n_out, dtype, generic):
     assert err <= gu.TOL[dtype]
 
 
+# ---------------------------------------------------------------- low-rank
+# ranks below, at and above a tile; token counts in every GEMM regime (few-token stream, small and
+# large tiles); ragged sizes; a row length that is not 16-byte aligned (portable kernels)
+LOWRANK_CASES = [
+    (8, 256, 256, 64, "f32"),
+    (70, 256, 192, 32, "bf16"),
+    (1, 512, 384, 128, "bf16"),
+    (17, 1024, 520, 96, "bf16"),
+    (300, 768, 3072, 128, "bf16"),
+    (515, 1000, 776, 200, "bf16"),
+    (1100, 2048, 2048, 256, "bf16"),
+    (130, 100, 36, 10, "bf16"),
+    (33, 100, 36, 10, "f32"),
+]
+
+
+@pytest.mark.parametrize("T,n_in,n_out,r,dtype", LOWRANK_CASES)
+@pytest.mark.parametrize("generic", [False, True])
+def test_lowrank_parity(T, n_in, n_out, r, dtype, generic):
+    gu = _gu()
+    lay = bi.lowrank_layer(n_in, n_out, r, dtype)
+    X = bi.activations(T, n_in, dtype)
+    Y = gu.run_lowrank(X, lay, gu.B.FORCE_GENERIC if generic else 0)
+    err = gu.rel_err(gu.to_f64(Y), oracle.lowrank_forward(X.f64, lay.V.f64, lay.U.f64))
+    print(f"lowrank T={T} {n_in}->{n_out} r={r} {dtype} generic={generic}: rel err {err:.3e}")
+    assert err <= gu.TOL[dtype]
+
+
+def test_lowrank_stage_flags_and_bit_identity():
+    gu = _gu()
+    B = gu.B
+    lay = bi.lowrank_layer(1024, 768, 128, "bf16")
+    X = bi.activations(600, 1024, "bf16")
+    Xd, Vd, Ud = gu.to_dev(X), gu.to_dev(lay.V), gu.to_dev(lay.U)
+    ws = torch.empty(B.lowrank_workspace_bytes(600, 1024, 768, 128, B.BF16), dtype=torch.uint8, device="cuda")
+    Y0 = gu.empty_out(600, 768, "bf16")
+    B.lowrank_forward(Xd, Vd, Ud, Y0, 0, ws)
+    Y1 = gu.empty_out(600, 768, "bf16")
+    B.lowrank_forward(Xd, Vd, Ud, Y1, B.ONLY_FIRST_STAGE, ws)
+    torch.cuda.synchronize()
+    assert torch.isnan(Y1).all()                        # the first stage alone does not touch Y
+    Z = gu.to_f64(ws[:600 * 128 * 2].view(torch.bfloat16).view(600, 128))   # Z comes first in the workspace
+    assert gu.rel_err(Z, X.f64 @ lay.V.f64.T) <= gu.TOL["bf16"]
+    B.lowrank_forward(Xd, Vd, Ud, Y1, B.ONLY_LAST_STAGE, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y1)
+    for _ in range(3):
+        Y2 = gu.empty_out(600, 768, "bf16")
+        B.lowrank_forward(Xd, Vd, Ud, Y2, 0, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(Y0, Y2)
+
+
 # ---------------------------------------------------------------- edge cases and properties
 def test_zero_tokens_and_status_codes():
     gu = _gu()
