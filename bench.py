@@ -71,7 +71,7 @@ class GpuLayer:
             self.U, self.S, self.V = to_dev(lay.U), to_dev(lay.S), to_dev(lay.V)
             self.b, self.r = cfg["b"], cfg["r"]
             self.flags = 0
-            if self.dtype == "bf16" and (self.n_in // self.b) % 8 == 0 and self.r % 8 == 0 and self.b <= 16:
+            if B.blast_packed_bytes(self.n_in, self.n_out, self.b, self.r, dt) > 0:
                 self.packed = B.blast_pack(self.U, self.S, self.V, self.n_in, self.n_out, self.b, self.r)
                 self.flags = B.BLAST_PACKED
             self.ws = torch.empty(max(B.blast_workspace_bytes(T, self.n_in, self.n_out, self.b, self.r, dt, self.flags), 16),
@@ -316,6 +316,41 @@ def run_sweep(steps, warmup, only=None):
     return rows
 
 
+def run_table3(steps, warmup):
+    """Every layer shape of the paper's Table 3 (Appendix, Layer Details) with every method, against the
+    same-shape dense GEMM; rows go to gpurun_out/table3.json and to stderr."""
+    import torch
+    from paper_2512_20861_amd import binding as B
+    rows = []
+    for t3 in bi.TABLE3:
+        model, lname, n_in, n_out, n, methods = t3
+        W = to_dev(bi.dense_weight(n_in, n_out, "bf16"))
+        X = torch.randn((n, n_in), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        Yd = torch.empty((n, n_out), device="cuda", dtype=torch.bfloat16)
+        ms_dense = time_graph(lambda: B.prepared(B.dense_reference_forward, X, W, Yd), steps, warmup)
+        for method in methods:
+            cfg = bi.table3_cfg(t3, method)
+            layer = GpuLayer(cfg, n, random_x=False)
+            layer.set_x(X)
+            ms = time_graph(layer.prepared, steps, warmup)
+            sa = layer.shape_args()
+            mem, mfma = rf.floors(method, n, **sa)
+            row = {"model": model, "layer": lname, "n_in": n_in, "n_out": n_out, "T": n, "method": method, "r": sa["r"], "b": sa["b"],
+                   "ms": ms, "dense_ms": ms_dense, "speedup_vs_dense": ms_dense / ms, "tokens_per_s": n / (ms * 1e-3),
+                   "floor_us": max(mem, mfma) * 1e6, "bound": "hbm" if mem >= mfma else "mfma", "frac_of_floor": max(mem, mfma) / (ms * 1e-3),
+                   "compression": rf.params("dense", n_in, n_out) / rf.params(method, n_in, n_out, sa["r"], sa["b"])}
+            rows.append(row)
+            log(f"{model:13s} {lname:13s} {n_in:5d}->{n_out:5d} T={n:4d} {method:8s} (r,b)=({sa['r']},{sa['b']})  {ms*1e3:8.1f} us | dense {ms_dense*1e3:8.1f} us | "
+                f"speedup {row['speedup_vs_dense']:.2f}x | floor {row['floor_us']:.1f} us ({row['bound']}) frac {row['frac_of_floor']:.3f} | CF {row['compression']:.2f}")
+            del layer
+        del W, X, Yd
+        torch.cuda.empty_cache()
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "table3.json"), "w") as f:
+        json.dump(rows, f, indent=1)
+    return rows
+
+
 def chain_linear_cfg(op, name):
     """Benchmark-style configuration of one linear of the chain."""
     c = bi.CHAIN
@@ -433,6 +468,7 @@ def main():
     ap.add_argument("--workload", default="C1", choices=sorted(bi.CONFIGS) + ["C4-monarch", "C4-blast"])
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
     ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--table3", action="store_true", help="also time every layer shape of the paper's Table 3")
     ap.add_argument("--sweep-configs", default="", help="comma-separated subset of the configurations for --sweep")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -503,6 +539,8 @@ def main():
     if not args.no_cpu:
         T_cpu = min(T, {"C1": 6304, "C0": 8}.get(args.workload, 512))
         out["cpu_baseline"] = cpu_baseline(cfg, T_cpu)
+    if args.table3:
+        out["table3"] = run_table3(max(args.steps // 4, 20), max(args.warmup // 2, 5))
     if args.sweep:
         out["sweep"] = run_sweep(max(args.steps // 4, 20), max(args.warmup // 2, 5), set(filter(None, args.sweep_configs.split(","))))
     print(json.dumps(out), flush=True)

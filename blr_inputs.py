@@ -212,6 +212,43 @@ CONFIGS = {
 }
 
 
+# Layer shapes of the paper's Table 3 (Appendix, Layer Details): (model, layer, n_in, n_out, tokens,
+# {method: (r, b)}); for Monarch r is the paper's r (per-block rank r' = r / b), which is also the
+# width of one middle block at the library boundary. The token count n is "determined by the model
+# and application" in the paper and not printed: 1024 (the roofline example's n) for the language
+# models, 197 for ViT-B, 256 for DiT-XL/2 are this build's stand-ins.
+TABLE3 = (
+    ("Llama-7B", "qkvo_proj", 4096, 4096, 1024, {"lowrank": (1024, 1), "monarch": (1024, 16), "blast": (1024, 16)}),
+    ("Llama-7B", "gate_up_proj", 4096, 11008, 1024, {"lowrank": (1488, 1), "monarch": (1536, 16), "blast": (1488, 16)}),
+    ("Llama-7B", "down_proj", 11008, 4096, 1024, {"lowrank": (1488, 1), "monarch": (1536, 16), "blast": (1488, 16)}),
+    ("Llama-3.2-1B", "qo_proj", 2048, 2048, 1024, {"lowrank": (256, 1), "monarch": (256, 16), "blast": (256, 16)}),
+    ("Llama-3.2-1B", "gate_proj", 2048, 8192, 1024, {"lowrank": (512, 1), "monarch": (512, 16), "blast": (512, 16)}),
+    ("Llama-3.2-1B", "up_proj", 2048, 8192, 1024, {"lowrank": (768, 1), "monarch": (768, 16), "blast": (768, 16)}),
+    ("Llama-3.2-1B", "down_proj", 8192, 2048, 1024, {"lowrank": (768, 1), "monarch": (768, 16), "blast": (768, 16)}),
+    ("GPT2-S", "c_attn", 768, 2304, 1024, {"lowrank": (192, 1), "monarch": (192, 4), "blast": (192, 6)}),
+    ("GPT2-S", "c_fc", 768, 3072, 1024, {"lowrank": (192, 1), "monarch": (192, 4), "blast": (192, 6)}),
+    ("GPT2-S", "c_proj", 3072, 768, 1024, {"lowrank": (192, 1), "monarch": (192, 4), "blast": (192, 6)}),
+    ("ViT-B", "attn_qkv", 768, 2304, 197, {"lowrank": (128, 1), "monarch": (128, 4), "blast": (128, 3)}),
+    ("ViT-B", "fc1", 768, 3072, 197, {"lowrank": (128, 1), "monarch": (128, 4), "blast": (128, 3)}),
+    ("ViT-B", "fc2", 3072, 768, 197, {"lowrank": (128, 1), "monarch": (128, 4), "blast": (128, 3)}),
+    ("DiT-XL/2", "qkv_proj", 1152, 3456, 256, {"lowrank": (384, 1), "blast": (384, 9)}),
+    ("DiT-XL/2", "fc1", 1152, 4608, 256, {"lowrank": (256, 1), "blast": (256, 9)}),
+    ("DiT-XL/2", "adaLN_proj", 1152, 6912, 256, {"lowrank": (256, 1), "blast": (256, 9)}),
+)
+
+
+def table3_cfg(row, method: str) -> dict:
+    """Configuration dictionary (as in CONFIGS) of one Table 3 row and method."""
+    _, _, n_in, n_out, n, methods = row
+    r, b = methods[method]
+    cfg = dict(op=method, n_in=n_in, n_out=n_out, r=r, dtype="bf16", T=(n,), x_scale=1.0)
+    if method == "monarch":
+        cfg["nblocks"] = b
+    elif method == "blast":
+        cfg["b"] = b
+    return cfg
+
+
 def make_layer(cfg: dict, seed=BASE_SEED, layer_id=0):
     if cfg["op"] == "lowrank":
         return lowrank_layer(cfg["n_in"], cfg["n_out"], cfg["r"], cfg["dtype"], seed, layer_id=layer_id)
