@@ -411,6 +411,16 @@ static_assert(16 * FT * 16 <= FCHUNK, "in-place A must fit in the chunk it repla
 // r <= 32*NT rank indices; KG k-steps of 16 fetched per round; NPT = (n_out/b)/16 output tiles per block.
 // Every global load is unconditional (indices are clamped, work that does not exist is computed on
 // repeated data and not written) so that each wait counts exactly the loads older than the data it needs.
+// 16-byte global load the compiler can neither move nor count: the caller waits on vmcnt itself
+// (the count being the number of vector-memory operations issued after this one) and ties the
+// result to that wait before using it. The "memory" clobber keeps other loads from crossing it.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4 global_load_b128_pinned(const void* uniform_base, unsigned lane_offset) {
+    u32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(lane_offset), "s"(uniform_base) : "memory");
+    return v;
+}
+
 template <int NT, int KG, int NPT>
 __global__ __launch_bounds__(FTHREADS) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Sp, const bf16_t* __restrict__ Vf,
@@ -421,7 +431,9 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
     unsigned char* Zs = smem;
     unsigned char* XY = smem + NT * 4 * FCHUNK;                      // X tile [FT][n_in], later Y tile [FT][n_out]
     const int xstr = n_in * 2 + 16, ystr = n_out * 2 + 16;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: block and fragment offsets stay on the scalar unit
+    const unsigned lane16 = (unsigned)lane * 16u;
     const int64_t t0 = (int64_t)blockIdx.x * FT;
     const int q = n_in / b, p = n_out / b;
     const int nks = (q + 15) >> 4;
@@ -430,6 +442,27 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
     // this wavefront's input blocks (phase 1), rank groups (phase 2) and output blocks (phase 3)
     const int jw[2] = {wave < b ? wave : b - 1, wave + FWAVES < b ? wave + FWAVES : b - 1};
     const int cw[2] = {wave < nchunks ? wave : nchunks - 1, wave + FWAVES < nchunks ? wave + FWAVES : nchunks - 1};
+
+    // ---- phase 0a: the X tile is requested first, so that it is the first thing the vector-memory
+    // pipe (64 bytes per clock and CU) delivers; the factor fragments queue up behind it and arrive
+    // while the tile is written to LDS and the first products run. A wavefront brings 4 token rows,
+    // 64 16-byte pieces per load (rows past T repeat the last row; lanes past the row end load and
+    // later store the row's last piece once more, so that no load or store sits under a per-lane
+    // condition, which would let the compiler move the load down to its use).
+    constexpr int XH = 2;                                            // pieces of 64 x 16 bytes per row and round
+    const int cpr_in = n_in >> 3;                                    // 16-byte pieces per row
+    u32x4 xv[FT / FWAVES][XH];
+#pragma unroll
+    for (int u = 0; u < FT / FWAVES; ++u) {
+        int64_t tx = t0 + wave * (FT / FWAVES) + u;
+        if (tx > T - 1) tx = T - 1;
+        const unsigned char* src = (const unsigned char*)(X + tx * n_in);
+#pragma unroll
+        for (int h = 0; h < XH; ++h) {
+            const int cc = h * 64 + lane < cpr_in ? h * 64 + lane : cpr_in - 1;
+            xv[u][h] = global_load_b128_pinned(src, (unsigned)cc * 16u);   // (the compiler would sink plain loads to their use, behind the factor loads)
+        }
+    }
 
     // V fragments (first round of k-steps)
     uint4 braw[2][KG][NT];
@@ -442,50 +475,64 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
                 if (ks > nks - 1) ks = nks - 1;
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    braw[jj][u][nt] = *(const uint4*)(Vf + (((int64_t)(jw[jj] * NT + nt) * nks + ks) * 64 + lane) * 8);
+                    braw[jj][u][nt] = *(const uint4*)((const unsigned char*)Vf + (((size_t)(jw[jj] * NT + nt) * nks + ks) << 10) + lane16);
             }
     };
     load_vf(0);
+    // the 2 KG NT fragment loads above are the only vector-memory operations younger than the tile's
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * KG * NT) : "memory");
+#pragma unroll
+    for (int u = 0; u < FT / FWAVES; ++u)
+#pragma unroll
+        for (int h = 0; h < XH; ++h) asm volatile("" : "+v"(xv[u][h]));
 
-    // ---- phase 0: X tile -> LDS with coalesced 16-byte loads (rows past T repeat the last row; the
-    // 16 pad bytes of a row are zeroed because the last k-step of the last block may read them
-    // against zero V fragments)
+    // ---- phase 0b: X tile -> LDS. The 16 pad bytes of a row are zeroed because the last k-step of
+    // the last block may read them against zero V fragments.
     {
-        const int cpr = n_in >> 3;                                   // 16-byte chunks per row
-        const int total = FT * cpr;
-        constexpr int XB = 8;                                        // loads in flight per thread: one round trip up to n_in = 1024
-        for (int base = 0; base < total; base += FTHREADS * XB) {
-            uint4 v[XB];
-#pragma unroll
-            for (int u = 0; u < XB; ++u) {
-                int id = base + u * FTHREADS + tid;
-                if (id > total - 1) id = total - 1;
-                const int row = id / cpr, cc = id - row * cpr;
-                int64_t tx = t0 + row;
-                if (tx > T - 1) tx = T - 1;
-                v[u] = *(const uint4*)(X + tx * n_in + cc * 8);
-            }
-#pragma unroll
-            for (int u = 0; u < XB; ++u) {
-                int id = base + u * FTHREADS + tid;
-                if (id > total - 1) id = total - 1;
-                const int row = id / cpr, cc = id - row * cpr;
-                *(uint4*)(XY + row * xstr + cc * 16) = v[u];
-            }
-        }
         if (tid < FT) *(uint4*)(XY + tid * xstr + n_in * 2) = make_uint4(0, 0, 0, 0);
         if (b < 16)                                                 // unused j slots must read as zero
             for (int i = tid * 16; i < NT * 4 * FCHUNK; i += FTHREADS * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < FT / FWAVES; ++u)
+#pragma unroll
+            for (int h = 0; h < XH; ++h) {
+                const int cc = h * 64 + lane < cpr_in ? h * 64 + lane : cpr_in - 1;
+                *(u32x4*)(XY + (wave * (FT / FWAVES) + u) * xstr + cc * 16) = xv[u][h];
+            }
+        if (XH * 64 < cpr_in) {                                     // rows longer than 2 KiB (n_in <= 2048): a second round
+            uint4 xw[FT / FWAVES][XH];
+#pragma unroll
+            for (int u = 0; u < FT / FWAVES; ++u) {
+                int64_t tx = t0 + wave * (FT / FWAVES) + u;
+                if (tx > T - 1) tx = T - 1;
+                const unsigned char* src = (const unsigned char*)(X + tx * n_in);
+#pragma unroll
+                for (int h = 0; h < XH; ++h) {
+                    const int cc = (XH + h) * 64 + lane < cpr_in ? (XH + h) * 64 + lane : cpr_in - 1;
+                    xw[u][h] = *(const uint4*)(src + (unsigned)cc * 16u);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < FT / FWAVES; ++u)
+#pragma unroll
+                for (int h = 0; h < XH; ++h) {
+                    const int cc = (XH + h) * 64 + lane < cpr_in ? (XH + h) * 64 + lane : cpr_in - 1;
+                    *(uint4*)(XY + (wave * (FT / FWAVES) + u) * xstr + cc * 16) = xw[u][h];
+                }
+        }
     }
     __syncthreads();
 
     // S tiles of this wavefront's rank groups: in flight during phase 1
     s16x4 sfr[2][8];
+    {
+        const unsigned soff = (unsigned)((lane & 15) * 32 + (lane >> 4) * 8);
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc)
+        for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-        for (int ri = 0; ri < 8; ++ri)
-            sfr[cc][ri] = *(const s16x4*)(Sp + (int64_t)(cw[cc] * 8 + ri) * 256 + ci * 16 + cg * 4);
+            for (int ri = 0; ri < 8; ++ri)
+                sfr[cc][ri] = *(const s16x4*)((const unsigned char*)Sp + ((size_t)(cw[cc] * 8 + ri) << 9) + soff);
+    }
 
     // ---- phase 1: both blocks of this wavefront, then one 4-byte LDS write per (token, rank index)
     // holding the pair (slots 2*wave, 2*wave+1 of the permuted block order j' = (j%8)*2 + j/8, which
@@ -498,7 +545,7 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
         for (int nt = 0; nt < NPT; ++nt)
 #pragma unroll
             for (int ks = 0; ks < NT; ++ks)
-                ufr[ii][nt][ks] = *(const uint4*)(Uf + (((int64_t)(i * NPT + nt) * NT + ks) * 64 + lane) * 8);
+                ufr[ii][nt][ks] = *(const uint4*)((const unsigned char*)Uf + ((size_t)((i * NPT + nt) * NT + ks) << 10) + lane16);
     };
     {
         f32x16 zacc[2][NT];
@@ -610,12 +657,28 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
     });
     __syncthreads();
 
-    // ---- coalesced copy of the staged output tile
+    // ---- coalesced copy of the staged output tile: a wavefront writes 4 token rows, 1 KiB per store;
+    // all LDS reads first, then the stores
     {
-        const int cpr = n_out >> 3;                                  // 16-byte chunks per row
-        for (int id = tid; id < FT * cpr; id += FTHREADS) {
-            const int row = id / cpr, cc = id - row * cpr;
-            if (t0 + row < T) *(uint4*)(Y + (t0 + row) * n_out + cc * 8) = *(const uint4*)(XY + row * ystr + cc * 16);
+        const int cpr = n_out >> 3;                                  // 16-byte pieces per row
+        uint4 yv[FT / FWAVES][XH];                                  // n_out <= 1024: at most 2 x 64 pieces per row
+#pragma unroll
+        for (int u = 0; u < FT / FWAVES; ++u)
+#pragma unroll
+            for (int h = 0; h < XH; ++h) {
+                const int cc = h * 64 + lane < cpr ? h * 64 + lane : cpr - 1;
+                yv[u][h] = *(const uint4*)(XY + (wave * (FT / FWAVES) + u) * ystr + cc * 16);
+            }
+#pragma unroll
+        for (int u = 0; u < FT / FWAVES; ++u) {
+            const int row = wave * (FT / FWAVES) + u;
+            unsigned char* dst = (unsigned char*)(Y + (t0 + row) * n_out);
+            if (t0 + row < T)                                        // uniform
+#pragma unroll
+                for (int h = 0; h < XH; ++h) {
+                    const int cc = h * 64 + lane < cpr ? h * 64 + lane : cpr - 1;
+                    *(uint4*)(dst + cc * 16) = yv[u][h];
+                }
         }
     }
 }
@@ -631,7 +694,7 @@ inline int full_fusion_lds_bytes(int n_in, int n_out, int r) {
 bool blast_full_fusion_shape_ok(int n_in, int n_out, int b, int r) {
     if (b <= 0 || b > 16 || n_in <= 0 || n_out <= 0 || r <= 0 || n_in % b || n_out % b) return false;
     const int q = n_in / b, p = n_out / b;
-    if (q % 8 || r % 8 || p % 16 || p > 64 || r > 128) return false;
+    if (q % 8 || r % 8 || p % 16 || p > 64 || r > 128 || n_in > 2048) return false;   // (rows are moved in at most 4 x 64 pieces)
     return full_fusion_lds_bytes(n_in, n_out, r) <= 160 * 1024;
 }
 
