@@ -93,7 +93,7 @@ __device__ __forceinline__ void couple_group(unsigned char* grp, const s16x4 (&s
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int tok = tg * 16 + 4 * cg + e;
-            *(uint4*)(grp + (ci * TN + (tok ^ (ci & 7))) * 16) =
+            *(uint4*)(grp + (ci * TN + (tok ^ ci)) * 16) =
                 make_uint4(pack2_bf16(d[tg][0][e], d[tg][1][e]), pack2_bf16(d[tg][2][e], d[tg][3][e]),
                            pack2_bf16(d[tg][4][e], d[tg][5][e]), pack2_bf16(d[tg][6][e], d[tg][7][e]));
         }
@@ -114,7 +114,7 @@ __device__ __forceinline__ void store_a_tile(const unsigned char* Zs, bf16_t* __
     for (; v < TN * b; v += PER) {
         const int64_t tg = t0 + tok(t);
         if (tg < T && rho_ok)
-            *(uint4*)(A + (tg * b + i) * r + rho0 + c8 * 8) = *(const uint4*)(src + (i * TN + (t ^ (i & 7))) * 16);
+            *(uint4*)(A + (tg * b + i) * r + rho0 + c8 * 8) = *(const uint4*)(src + (i * TN + (t ^ (i & 15))) * 16);
         i += di; t += dt;
         if (i >= b) { i -= b; ++t; }
     }
@@ -581,10 +581,14 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
             for (int nt = 0; nt < NT; ++nt) {
                 const int rho = nt * 32 + l32;
                 if (rho < r) {
-                    unsigned char* zrow = Zs + rho * FZSTR + (4 * kg) * 32 + wave * 4;
+                    // The four 8-byte units of a token's 32 bytes (4 blocks each) are stored XOR 2 for tokens
+                    // 8..15 of every 16: the 32 lanes that phase 2 serves per clock (16 tokens x 2 units)
+                    // then touch all 64 banks once instead of half of them twice.
+                    unsigned char* zrow = Zs + rho * FZSTR + (4 * kg) * 32 + (wave & 1) * 4;
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
-                        *(uint32_t*)(zrow + (8 * (e / 4) + (e % 4)) * 32) = pack2_bf16(zacc[0][nt][e], has1 ? zacc[1][nt][e] : 0.f);
+                        *(uint32_t*)(zrow + (8 * (e / 4) + (e % 4)) * 32 + ((wave >> 1) ^ (2 * ((e / 4) & 1))) * 8) =
+                            pack2_bf16(zacc[0][nt][e], has1 ? zacc[1][nt][e] : 0.f);
                 }
             }
         }
@@ -601,7 +605,7 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
 #pragma unroll
         for (int ri = 0; ri < 8; ++ri)
 #pragma unroll
-            for (int tg = 0; tg < 2; ++tg) a[ri][tg] = *(const s16x4*)(chunk + ri * FZSTR + (tg * 16 + ci) * 32 + cg * 8);
+            for (int tg = 0; tg < 2; ++tg) a[ri][tg] = *(const s16x4*)(chunk + ri * FZSTR + (tg * 16 + ci) * 32 + (cg ^ (2 * (ci >> 3))) * 8);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ri = 0; ri < 8; ++ri)
@@ -616,7 +620,7 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int tok = tg * 16 + 4 * cg + e;
-                *(uint4*)(chunk + (ci * FT + (tok ^ (ci & 7))) * 16) =
+                *(uint4*)(chunk + (ci * FT + (tok ^ ci)) * 16) =
                     make_uint4(pack2_bf16(d[tg][0][e], d[tg][1][e]), pack2_bf16(d[tg][2][e], d[tg][3][e]),
                                pack2_bf16(d[tg][4][e], d[tg][5][e]), pack2_bf16(d[tg][6][e], d[tg][7][e]));
             }
@@ -637,8 +641,8 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
             int c = ks * 4 + cg;                                    // group of 8 rank indices this lane multiplies
             if (c > nchunks - 1) c = nchunks - 1;                   // past r the U fragment is zero; read a valid group
             const unsigned char* chunk = Zs + c * FCHUNK;
-            a0[ks] = *(const bf16x8*)(chunk + (ic * FT + (ci ^ (ic & 7))) * 16);
-            a1[ks] = *(const bf16x8*)(chunk + (ic * FT + ((16 + ci) ^ (ic & 7))) * 16);
+            a0[ks] = *(const bf16x8*)(chunk + (ic * FT + (ci ^ (ic & 15))) * 16);
+            a1[ks] = *(const bf16x8*)(chunk + (ic * FT + ((16 + ci) ^ (ic & 15))) * 16);
         }
 #pragma unroll
         for (int nt = 0; nt < NPT; ++nt) {
