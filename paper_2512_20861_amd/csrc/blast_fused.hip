@@ -65,7 +65,9 @@ __device__ __forceinline__ void load_s_group(const bf16_t* __restrict__ Sp, int 
     }
 }
 
-// Must be entered after a barrier that follows the last write to Zs.
+// Must be entered after a barrier that follows the last write to Zs. The four 8-byte units (4 blocks
+// each) of a token's 32 bytes are stored XOR 2 for tokens 8..15 of every 16, so that the 32 lanes a
+// fragment read serves per clock (16 tokens x 2 units) touch all 64 banks once.
 __device__ __forceinline__ void couple_group(unsigned char* grp, const s16x4 (&sfrag)[8]) {
     const int lane = threadIdx.x & 63, ci = lane & 15, cg = lane >> 4;
     // Two batches of 16 fragment reads, each issued back to back before its MFMAs, so that the LDS
@@ -78,7 +80,7 @@ __device__ __forceinline__ void couple_group(unsigned char* grp, const s16x4 (&s
         for (int r4 = 0; r4 < 4; ++r4)
 #pragma unroll
             for (int tg = 0; tg < TN / 16; ++tg)
-                a[r4][tg] = *(const s16x4*)(grp + (half * 4 + r4) * ZSTR + (tg * 16 + ci) * 32 + cg * 8);
+                a[r4][tg] = *(const s16x4*)(grp + (half * 4 + r4) * ZSTR + (tg * 16 + ci) * 32 + (cg ^ (2 * (ci >> 3))) * 8);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4)
@@ -167,7 +169,7 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
                 const bool has1 = 2 * jp + 1 < b;
                 const uint32_t w0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w};
                 const uint32_t w1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
-                unsigned char* dst = Zs + (c8 * 8) * ZSTR + t * 32 + jp * 4;
+                unsigned char* dst = Zs + (c8 * 8) * ZSTR + t * 32 + ((jp >> 1) ^ (2 * ((t >> 3) & 1))) * 8 + (jp & 1) * 4;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const uint32_t hi = has1 ? w1[e] : 0u;
@@ -329,7 +331,8 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
             for (int e2 = 0; e2 < 8; ++e2) {
                 unsigned char* dst = zrow + (8 * (e2 / 4) + (e2 % 4)) * 32;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) *(uint2*)(dst + v * 8) = make_uint2(zq[8 * hf + e2][2 * v], zq[8 * hf + e2][2 * v + 1]);
+                for (int v = 0; v < 4; ++v)
+                    *(uint2*)(dst + (v ^ (2 * ((e2 / 4) & 1))) * 8) = make_uint2(zq[8 * hf + e2][2 * v], zq[8 * hf + e2][2 * v + 1]);
             }
             __syncthreads();
             couple_group(Zs + wave * GROUP, sfrag);
