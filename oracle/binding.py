@@ -36,7 +36,7 @@ def _load():
         for name in ("blr_oracle_dense_forward", "blr_oracle_monarch_forward", "blr_oracle_blast_forward",
                      "blr_oracle_materialize_monarch", "blr_oracle_materialize_blast",
                      "blr_oracle_monarch_middle_perm", "blr_oracle_lowrank_forward",
-                     "blr_oracle_materialize_lowrank"):
+                     "blr_oracle_materialize_lowrank", "blr_oracle_monarch_rect_forward"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -78,6 +78,24 @@ def monarch_forward(X, R, L, out_order=OUT_INTERLEAVED, nthreads=None, return_ma
     rc = _load().blr_oracle_monarch_forward(_p(X), _p(R), _p(L), _p(Y), ctypes.c_int64(T), n_in, n_out,
                                             nblocks, r, out_order, nthreads or default_threads(),
                                             ctypes.byref(macs))
+    if rc:
+        raise ValueError("oracle: invalid argument")
+    return (Y, macs.value) if return_macs else Y
+
+
+def monarch_rect_forward(X, R, L, b1, b2, out_order=OUT_INTERLEAVED, nthreads=None, return_macs=False):
+    """Monarch with b1 input blocks and b2 output blocks: R[b1][r'*b2][n_in/b1], L[b2][n_out/b2][b1*r']."""
+    X, R, L = _f64(X), _f64(R), _f64(L)
+    T, n_in = X.shape
+    p = R.shape[2]
+    q = L.shape[1]
+    rp = R.shape[1] // b2
+    assert R.shape == (b1, rp * b2, p) and L.shape == (b2, q, b1 * rp) and b1 * p == n_in
+    n_out = b2 * q
+    Y = np.empty((T, n_out), dtype=np.float64)
+    macs = ctypes.c_int64(0)
+    rc = _load().blr_oracle_monarch_rect_forward(_p(X), _p(R), _p(L), _p(Y), ctypes.c_int64(T), n_in, n_out,
+                                                 b1, b2, rp, out_order, nthreads or default_threads(), ctypes.byref(macs))
     if rc:
         raise ValueError("oracle: invalid argument")
     return (Y, macs.value) if return_macs else Y

@@ -177,6 +177,61 @@ int blr_oracle_materialize_monarch(const double* R, const double* L, double* W,
 }
 
 // ---------------------------------------------------------------------------
+// Monarch with different block counts on the two sides (Section 2.1 "Monarch":
+// b2 x b1 blocks, l in [0, b1) input blocks of p = n_in/b1 features, k in
+// [0, b2) output blocks of q = n_out/b2 features, per-block rank r').
+// Stored factors follow the same two orders as the square case:
+//   R[b1][r'*b2][p], middle index rho*b2 + k;  L[b2][q][b1*r'], innermost l*r' + rho.
+//   1. Z[t][l][c]    = sum_a X[t][l*p + a] * R[l][c][a],          c < r'*b2
+//   2. Z'[t][k][m]   = Z[t][l][rho*b2 + k],   m = l*r' + rho      (b1 <=> b2)
+//   3. Yb[t][k][j]   = sum_m Z'[t][k][m] * L[k][j][m],            m < b1*r'
+//   4. interleaved: Y[t][j*b2 + k];  blocked: Y[t][k*q + j]
+// ---------------------------------------------------------------------------
+int blr_oracle_monarch_rect_forward(const double* X, const double* R, const double* L, double* Y,
+                                    int64_t T, int n_in, int n_out, int b1, int b2, int rp,
+                                    int out_order, int nthreads, int64_t* macs) {
+    if (!X || !R || !L || !Y || T < 0 || n_in <= 0 || n_out <= 0 || b1 <= 0 || b2 <= 0 || rp <= 0) return 1;
+    if (n_in % b1 || n_out % b2) return 1;
+    if (out_order != BLR_ORACLE_OUT_INTERLEAVED && out_order != BLR_ORACLE_OUT_BLOCKED) return 1;
+    const int p = n_in / b1, q = n_out / b2, w1 = rp * b2, w2 = b1 * rp;
+    std::vector<int64_t> counts(std::max(nthreads, 1) + 1, 0);
+    parallel_over_tokens(T, nthreads, [&](int64_t t0, int64_t t1, int w) {
+        std::vector<double> Z((size_t)b1 * w1), Zp((size_t)b2 * w2), Yb((size_t)b2 * q);
+        int64_t n = 0;
+        for (int64_t t = t0; t < t1; ++t) {
+            const double* x = X + t * n_in;
+            for (int l = 0; l < b1; ++l)
+                for (int c = 0; c < w1; ++c) {
+                    const double* row = R + ((int64_t)l * w1 + c) * p;
+                    double acc = 0.0;
+                    for (int a = 0; a < p; ++a) acc += x[l * p + a] * row[a];
+                    Z[(size_t)l * w1 + c] = acc;
+                    n += p;
+                }
+            for (int k = 0; k < b2; ++k)
+                for (int l = 0; l < b1; ++l)
+                    for (int rho = 0; rho < rp; ++rho)
+                        Zp[(size_t)k * w2 + l * rp + rho] = Z[(size_t)l * w1 + rho * b2 + k];
+            for (int k = 0; k < b2; ++k)
+                for (int j = 0; j < q; ++j) {
+                    const double* row = L + ((int64_t)k * q + j) * w2;
+                    double acc = 0.0;
+                    for (int m = 0; m < w2; ++m) acc += Zp[(size_t)k * w2 + m] * row[m];
+                    Yb[(size_t)k * q + j] = acc;
+                    n += w2;
+                }
+            double* y = Y + t * n_out;
+            for (int k = 0; k < b2; ++k)
+                for (int j = 0; j < q; ++j)
+                    y[(out_order == BLR_ORACLE_OUT_INTERLEAVED) ? j * b2 + k : k * q + j] = Yb[(size_t)k * q + j];
+        }
+        counts[w] = n;
+    });
+    if (macs) { int64_t s = 0; for (auto c : counts) s += c; *macs = s; }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
 // BLAST forward, factor by factor (Section 2.1 "BLAST":
 // Y_k = (sum_l (X_l V_l) S_{l,k}) U_k with S diagonal), q = n_in/b, p = n_out/b.
 //   1. Z[t][j][rho] = sum_c X[t][j*q + c] * V[j][c][rho]
