@@ -94,6 +94,24 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
                                void* workspace, size_t workspace_bytes, blr_stream stream);
 
 /*
+ * Monarch forward with different block counts on the two sides (paper Section 2.1 "Monarch": the
+ * weight is divided into b2 x b1 blocks W_{l,k} = V_{l,k} U_{l,k} of rank r', l < b1 input blocks of
+ * p = n_in/b1 features, k < b2 output blocks of q = n_out/b2 features). With b1 = b_in, b2 = b_out,
+ * r' = r_block:
+ *   Z'[t][k][l*r'+rho] = sum_a X[t][l*p+a] * R[l][rho*b2+k][a]
+ *   Y[t][o(k,j)]       = sum_m Z'[t][k][m] * L[k][j][m],   o = j*b2+k (default) or k*q+j (BLR_MONARCH_OUT_BLOCKED)
+ * R[b1][r'*b2][p], L[b2][q][b1*r'] (the same two storage orders as blr_monarch_forward, which is the
+ * case b1 = b2 = nblocks, r' = r/nblocks). b_in must divide n_in and b_out must divide n_out.
+ * flags: BLR_MONARCH_OUT_BLOCKED, BLR_FORCE_GENERIC, BLR_ONLY_FIRST_STAGE, BLR_ONLY_LAST_STAGE.
+ * workspace: at least blr_monarch_rect_workspace_bytes(...) bytes (holds Z', T*b1*b2*r' elements).
+ */
+size_t     blr_monarch_rect_workspace_bytes(int64_t T, int n_in, int n_out, int b_in, int b_out, int r_block, blr_dtype dt);
+blr_status blr_monarch_rect_forward(const void* X, const void* R, const void* L, void* Y,
+                                    int64_t T, int n_in, int n_out, int b_in, int b_out, int r_block,
+                                    blr_dtype dt, unsigned flags,
+                                    void* workspace, size_t workspace_bytes, blr_stream stream);
+
+/*
  * One-time re-layout of a first Monarch factor for BLR_MONARCH_IN_BLOCKED:
  *   Rp[l][c][k*(p/b) + jj] = R[l][c][jj*b + k],  p = n_in/nblocks, b = nblocks, jj < p/b, k < b.
  * R and Rp are [nblocks][r][p] device tensors of type dt and must not overlap.

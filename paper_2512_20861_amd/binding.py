@@ -28,9 +28,10 @@ EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forw
            "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_bytes",
            "blr_blast_pack", "blr_dense_reference_forward",
            "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul",
-           "blr_monarch_permute_first_factor", "blr_lowrank_workspace_bytes", "blr_lowrank_forward")
+           "blr_monarch_permute_first_factor", "blr_lowrank_workspace_bytes", "blr_lowrank_forward",
+           "blr_monarch_rect_workspace_bytes", "blr_monarch_rect_forward")
 # entry points that enqueue work and return a status: the ones prepared() can record
-_LAUNCHERS = ("blr_monarch_forward", "blr_blast_forward", "blr_dense_reference_forward", "blr_lowrank_forward",
+_LAUNCHERS = ("blr_monarch_forward", "blr_blast_forward", "blr_dense_reference_forward", "blr_lowrank_forward", "blr_monarch_rect_forward",
               "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul")
 
 _lib = None
@@ -57,6 +58,10 @@ def lib() -> ctypes.CDLL:
         L.blr_monarch_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci]
         L.blr_monarch_forward.restype = ci
         L.blr_monarch_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, cu, vp, sz, vp]
+        L.blr_monarch_rect_workspace_bytes.restype = sz
+        L.blr_monarch_rect_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, ci]
+        L.blr_monarch_rect_forward.restype = ci
+        L.blr_monarch_rect_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, cu, vp, sz, vp]
         L.blr_lowrank_workspace_bytes.restype = sz
         L.blr_lowrank_workspace_bytes.argtypes = [i64, ci, ci, ci, ci]
         L.blr_lowrank_forward.restype = ci
@@ -136,11 +141,30 @@ def monarch_forward(X, R, L, Y, nblocks, r, flags=0, workspace=None, stream=None
     return Y
 
 
+def monarch_rect_workspace_bytes(T, n_in, n_out, b_in, b_out, r_block, dt) -> int:
+    return lib().blr_monarch_rect_workspace_bytes(T, n_in, n_out, b_in, b_out, r_block, dt)
+
+
+def monarch_rect_forward(X, R, L, Y, b_in, b_out, r_block, flags=0, workspace=None, stream=None):
+    """Monarch with b_in input and b_out output blocks: R[b_in][r_block*b_out][n_in/b_in], L[b_out][n_out/b_out][b_in*r_block]."""
+    T, n_in = X.shape
+    n_out = Y.shape[1]
+    dt = _dt(X)
+    if workspace is None:
+        workspace = torch.empty(max(monarch_rect_workspace_bytes(T, n_in, n_out, b_in, b_out, r_block, dt), 16),
+                                dtype=torch.uint8, device=X.device)
+    global _last_workspace
+    _last_workspace = workspace
+    _check(lib().blr_monarch_rect_forward(_ptr(X), _ptr(R), _ptr(L), _ptr(Y), T, n_in, n_out, b_in, b_out, r_block, dt, flags,
+                                          _ptr(workspace), workspace.numel(), _stream(stream)), "blr_monarch_rect_forward")
+    return Y
+
+
 def monarch_permute_first_factor(R, n_in, nblocks, r, stream=None):
     """First factor re-ordered for MONARCH_IN_BLOCKED (one-time weight preparation); returns the new tensor."""
     Rp = torch.empty_like(R)
     _check(lib().blr_monarch_permute_first_factor(_ptr(R), _ptr(Rp), n_in, nblocks, r, _dt(R), _stream(stream)),
-           "blr_monarch_permute_first_factor", "blr_lowrank_workspace_bytes", "blr_lowrank_forward")
+           "blr_monarch_permute_first_factor")
     return Rp
 
 

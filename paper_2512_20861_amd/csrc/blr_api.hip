@@ -125,6 +125,48 @@ const char* blr_status_string(blr_status s) {
     return "unknown status";
 }
 
+namespace {
+
+// Both Monarch entry points: b1 input blocks, b2 output blocks, per-block rank rp.
+blr_status monarch_run(const void* X, const void* R, const void* L, void* Y, int64_t T, int n_in, int n_out,
+                       int b1, int b2, int rp, blr_dtype dt, unsigned flags, void* workspace, hipStream_t s) {
+    const int p = n_in / b1, q = n_out / b2;
+    const int w1 = rp * b2, w2 = b1 * rp;               // widths of one middle block before / after the permutation
+    const bool allow_mfma = !(flags & BLR_FORCE_GENERIC);
+
+    // stage 1: block-diagonal R; tile column n' = k*r' + rho reads row rho*b2 + k of R[l] (the
+    // re-layout of the first factor done in the load index) and lands at Z'[t][k][l*r' + rho]
+    GemmDesc s1{};
+    s1.A = X; s1.a_gs = p; s1.a_rs = n_in;
+    s1.B = R; s1.b_gs = (int64_t)w1 * p; s1.b_rs = p; s1.b_ks = 1; s1.b_div = rp; s1.b_mul = b2;
+    s1.C = workspace; s1.c_rs = (int64_t)b2 * w2; s1.c_gs = rp; s1.c_div = rp; s1.c_hi = w2; s1.c_lo = 1;
+    s1.M = T; s1.N = w1; s1.K = p; s1.G = b1;
+    if (flags & BLR_MONARCH_IN_BLOCKED) {             // input block l = b runs of p/b elements, run k at k*(n_in/b) + l*(p/b)
+        s1.a_gs = p / b1; s1.a_seg = p / b1; s1.a_seg_stride = n_in / b1;
+    }
+    if (!(flags & BLR_ONLY_LAST_STAGE)) {
+        blr_status st = run_gemm(s1, dt, allow_mfma, s);
+        if (st != BLR_OK || (flags & BLR_ONLY_FIRST_STAGE)) return st;
+    }
+
+    // stage 2: block-diagonal L; the output order is a column map of the store
+    GemmDesc s2{};
+    s2.A = workspace; s2.a_gs = w2; s2.a_rs = (int64_t)b2 * w2;
+    s2.B = L; s2.b_gs = (int64_t)q * w2; s2.b_rs = w2; s2.b_ks = 1; s2.b_div = 0; s2.b_mul = 0;
+    s2.C = Y; s2.c_rs = n_out; s2.c_div = 1; s2.c_lo = 0;
+    if (flags & BLR_MONARCH_OUT_BLOCKED) { s2.c_gs = q; s2.c_hi = 1; }
+    else { s2.c_gs = 1; s2.c_hi = b2; }
+    s2.M = T; s2.N = q; s2.K = w2; s2.G = b2;
+    return run_gemm(s2, dt, allow_mfma, s);
+}
+
+bool monarch_rect_shape_ok(int64_t T, int n_in, int n_out, int b1, int b2, int rp) {
+    return T >= 0 && n_in > 0 && n_out > 0 && b1 > 0 && b2 > 0 && rp > 0 && n_in % b1 == 0 && n_out % b2 == 0 &&
+           (int64_t)b1 * b2 * rp < (1ll << 30);
+}
+
+}  // namespace
+
 size_t blr_monarch_workspace_bytes(int64_t T, int n_in, int n_out, int nblocks, int r, blr_dtype dt) {
     if (!monarch_shape_ok(T, n_in, n_out, nblocks, r) || !dtype_ok(dt)) return 0;
     return align_up((size_t)T * nblocks * r * elem_size(dt));
@@ -143,34 +185,27 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
     if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null
     if (!X || !Y) return BLR_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < blr_monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt)) return BLR_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
-    const int b = nblocks, p = n_in / b, q = n_out / b, rp = r / b;
-    const bool allow_mfma = !(flags & BLR_FORCE_GENERIC);
+    return monarch_run(X, R, L, Y, T, n_in, n_out, nblocks, nblocks, r / nblocks, dt, flags, workspace, (hipStream_t)stream);
+}
 
-    // stage 1: block-diagonal R; tile column n' = k*r' + rho reads row rho*b + k of R[l] (the
-    // re-layout of the first factor done in the load index) and lands at Z'[t][k][l*r' + rho]
-    GemmDesc s1{};
-    s1.A = X; s1.a_gs = p; s1.a_rs = n_in;
-    s1.B = R; s1.b_gs = (int64_t)r * p; s1.b_rs = p; s1.b_ks = 1; s1.b_div = rp; s1.b_mul = b;
-    s1.C = workspace; s1.c_rs = (int64_t)b * r; s1.c_gs = rp; s1.c_div = rp; s1.c_hi = r; s1.c_lo = 1;
-    s1.M = T; s1.N = r; s1.K = p; s1.G = b;
-    if (flags & BLR_MONARCH_IN_BLOCKED) {             // input block l = b runs of p/b elements, run k at k*(n_in/b) + l*(p/b)
-        s1.a_gs = p / b; s1.a_seg = p / b; s1.a_seg_stride = n_in / b;
-    }
-    if (!(flags & BLR_ONLY_LAST_STAGE)) {
-        blr_status st = run_gemm(s1, dt, allow_mfma, s);
-        if (st != BLR_OK || (flags & BLR_ONLY_FIRST_STAGE)) return st;
-    }
+size_t blr_monarch_rect_workspace_bytes(int64_t T, int n_in, int n_out, int b_in, int b_out, int r_block, blr_dtype dt) {
+    if (!monarch_rect_shape_ok(T, n_in, n_out, b_in, b_out, r_block) || !dtype_ok(dt)) return 0;
+    return align_up((size_t)T * b_in * b_out * r_block * elem_size(dt));
+}
 
-    // stage 2: block-diagonal L; the output order is a column map of the store
-    GemmDesc s2{};
-    s2.A = workspace; s2.a_gs = r; s2.a_rs = (int64_t)b * r;
-    s2.B = L; s2.b_gs = (int64_t)q * r; s2.b_rs = r; s2.b_ks = 1; s2.b_div = 0; s2.b_mul = 0;
-    s2.C = Y; s2.c_rs = n_out; s2.c_div = 1; s2.c_lo = 0;
-    if (flags & BLR_MONARCH_OUT_BLOCKED) { s2.c_gs = q; s2.c_hi = 1; }
-    else { s2.c_gs = 1; s2.c_hi = b; }
-    s2.M = T; s2.N = q; s2.K = r; s2.G = b;
-    return run_gemm(s2, dt, allow_mfma, s);
+blr_status blr_monarch_rect_forward(const void* X, const void* R, const void* L, void* Y,
+                                    int64_t T, int n_in, int n_out, int b_in, int b_out, int r_block,
+                                    blr_dtype dt, unsigned flags,
+                                    void* workspace, size_t workspace_bytes, blr_stream stream) {
+    if (!monarch_rect_shape_ok(T, n_in, n_out, b_in, b_out, r_block) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_MONARCH_OUT_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if (!R || !L) return BLR_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(R) || !aligned16(L) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
+    if (T == 0) return BLR_OK;
+    if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < blr_monarch_rect_workspace_bytes(T, n_in, n_out, b_in, b_out, r_block, dt)) return BLR_ERR_WORKSPACE;
+    return monarch_run(X, R, L, Y, T, n_in, n_out, b_in, b_out, r_block, dt, flags, workspace, (hipStream_t)stream);
 }
 
 size_t blr_lowrank_workspace_bytes(int64_t T, int n_in, int n_out, int r, blr_dtype dt) {

@@ -100,6 +100,29 @@ def test_monarch_argument_checks():
     assert _monarch(wsb=16) == B.ERR_WORKSPACE
 
 
+def test_monarch_rect_argument_checks():
+    L = B.lib()
+    def call(T=4, n_in=60, n_out=64, b1=3, b2=4, rp=2, dt=B.BF16, flags=0, X=FAKE, R=FAKE, Lf=FAKE, Y=FAKE, ws=FAKE, wsb=1 << 20):
+        return L.blr_monarch_rect_forward(X, R, Lf, Y, T, n_in, n_out, b1, b2, rp, dt, flags, ws, wsb, None)
+    assert B.monarch_rect_workspace_bytes(10, 60, 64, 3, 4, 2, B.BF16) == (10 * 3 * 4 * 2 * 2 + 255) // 256 * 256
+    assert B.monarch_rect_workspace_bytes(10, 61, 64, 3, 4, 2, B.BF16) == 0
+    # the square case needs exactly what blr_monarch_forward needs
+    assert B.monarch_rect_workspace_bytes(512, 4096, 4096, 4, 4, 256, B.BF16) == B.monarch_workspace_bytes(512, 4096, 4096, 4, 1024, B.BF16)
+    assert call(T=0) == B.OK
+    assert call(T=0, X=None, Y=None) == B.OK
+    assert call(n_in=61) == B.ERR_INVALID_ARG                      # b_in does not divide n_in
+    assert call(n_out=62) == B.ERR_INVALID_ARG                     # b_out does not divide n_out
+    assert call(rp=0) == B.ERR_INVALID_ARG
+    assert call(b1=0) == B.ERR_INVALID_ARG
+    assert call(R=None) == B.ERR_INVALID_ARG
+    assert call(Y=None) == B.ERR_INVALID_ARG
+    assert call(flags=B.MONARCH_IN_BLOCKED) == B.ERR_INVALID_ARG   # blocked input is defined for equal block counts only
+    assert call(flags=B.BLAST_PACKED) == B.ERR_INVALID_ARG
+    assert call(Lf=FAKE + 8) == B.ERR_INVALID_ARG
+    assert call(ws=None) == B.ERR_WORKSPACE
+    assert call(wsb=100) == B.ERR_WORKSPACE
+
+
 def test_blast_argument_checks():
     assert _blast(T=0) == B.OK
     assert _blast(T=-3) == B.ERR_INVALID_ARG

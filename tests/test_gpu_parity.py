@@ -164,6 +164,40 @@ def test_dense_parity(T, n_in, n_out, dtype, generic):
     assert err <= gu.TOL[dtype]
 
 
+# ---------------------------------------------------------------- Monarch, different block counts on the two sides
+# (T, n_in, n_out, b_in, b_out, r_block, dtype): MFMA-aligned and ragged shapes, few and many tokens
+MONARCH_RECT_CASES = [
+    (8, 256, 192, 4, 2, 16, "f32"),
+    (70, 512, 768, 2, 4, 32, "bf16"),
+    (1, 1024, 512, 8, 2, 16, "bf16"),
+    (300, 768, 2304, 4, 12, 16, "bf16"),
+    (515, 1024, 1024, 16, 4, 8, "bf16"),
+    (130, 60, 84, 3, 4, 5, "bf16"),
+    (33, 60, 84, 5, 2, 3, "f32"),
+    (200, 1152, 3456, 9, 3, 24, "bf16"),
+]
+
+
+@pytest.mark.parametrize("T,n_in,n_out,b1,b2,rp,dtype", MONARCH_RECT_CASES)
+@pytest.mark.parametrize("order", ["interleaved", "blocked"])
+@pytest.mark.parametrize("generic", [False, True])
+def test_monarch_rect_parity(T, n_in, n_out, b1, b2, rp, dtype, order, generic):
+    gu = _gu()
+    B = gu.B
+    p, q = n_in // b1, n_out // b2
+    R = bi.gaussian(bi.BASE_SEED, 41, (b1, rp * b2, p), 1.0 / np.sqrt(p), dtype)
+    L = bi.gaussian(bi.BASE_SEED, 42, (b2, q, b1 * rp), 1.0 / np.sqrt(b1 * rp), dtype)
+    X = bi.activations(T, n_in, dtype)
+    Y = gu.empty_out(T, n_out, dtype)
+    flags = (B.MONARCH_OUT_BLOCKED if order == "blocked" else 0) | (B.FORCE_GENERIC if generic else 0)
+    B.monarch_rect_forward(gu.to_dev(X), gu.to_dev(R), gu.to_dev(L), Y, b1, b2, rp, flags)
+    torch.cuda.synchronize()
+    Yref = oracle.monarch_rect_forward(X.f64, R.f64, L.f64, b1, b2, oracle.OUT_BLOCKED if order == "blocked" else oracle.OUT_INTERLEAVED)
+    err = gu.rel_err(gu.to_f64(Y), Yref)
+    print(f"monarch rect T={T} {n_in}->{n_out} b=({b1},{b2}) r'={rp} {dtype} {order} generic={generic}: rel err {err:.3e}")
+    assert err <= gu.TOL[dtype]
+
+
 # ---------------------------------------------------------------- low-rank
 # ranks below, at and above a tile; token counts in every GEMM regime (few-token stream, small and
 # large tiles); ragged sizes; a row length that is not 16-byte aligned (portable kernels)
