@@ -206,3 +206,45 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         B.lib()
+
+
+def test_python_wrappers_marshal_every_entry_point(monkeypatch):
+    """Every wrapper of the binding builds a call the C prototype accepts (argument count and types),
+    checked on the CPU with host tensors standing in for device tensors and a recorder standing in
+    for the launching entry points (size queries run for real)."""
+    torch = pytest.importorskip("torch")
+    real = B.lib()
+    calls = []
+
+    class Recorder:
+        def __getattr__(self, name):
+            fn = getattr(real, name)
+            if name not in B._LAUNCHERS and name not in ("blr_blast_pack", "blr_monarch_permute_first_factor"):
+                return fn
+            def rec(*args):
+                assert len(args) == len(fn.argtypes), (name, len(args), len(fn.argtypes))
+                for t, a in zip(fn.argtypes, args):
+                    t(a) if not isinstance(a, t) else a          # raises if the value does not fit the C type
+                calls.append(name)
+                return B.OK
+            return rec
+
+    monkeypatch.setattr(B, "_lib", Recorder())
+    monkeypatch.setattr(B, "_ptr", lambda t: None if t is None else t.data_ptr())
+    monkeypatch.setattr(B, "_stream", lambda s: None)
+    bf = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16)
+    ws = torch.zeros(1 << 22, dtype=torch.uint8)
+    T, n, b, r = 8, 64, 4, 16
+    B.monarch_forward(bf(T, n), bf(b, r, n // b), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
+    B.monarch_rect_forward(bf(T, n), bf(2, 4 * b, n // 2), bf(b, n // b, 2 * 4), bf(T, n), 2, b, 4, 0, ws)
+    B.monarch_permute_first_factor(bf(b, r, n // b), n, b, r)
+    B.lowrank_forward(bf(T, n), bf(r, n), bf(48, r), bf(T, 48), 0, ws)
+    B.blast_forward(bf(T, n), bf(b, n // b, r), bf(b, b, r), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
+    B.blast_pack(bf(16, 48, 96), bf(16, 16, 96), bf(16, 48, 96), 768, 768, 16, 96)
+    B.dense_reference_forward(bf(T, n), bf(n, n), bf(T, n))
+    B.rmsnorm(bf(T, n), bf(T, n))
+    B.residual_add_rmsnorm(bf(T, n), bf(T, n), bf(T, n))
+    B.residual_add_rmsnorm(bf(T, n), bf(T, n), None)
+    B.sum3_scaled(bf(T, n), bf(T, n), bf(T, n), bf(T, n), 0.5)
+    B.silu_mul(bf(T, n), bf(T, n), bf(T, n))
+    assert set(calls) == set(B._LAUNCHERS) | {"blr_blast_pack", "blr_monarch_permute_first_factor"}
