@@ -527,15 +527,18 @@ void blast_full_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ 
     __syncthreads();
 
     // S tiles of this wavefront's rank groups: in flight during phase 1
+    // (Sp is in fragment order, two rank indices per 16 bytes: an 8-byte load costs the address path
+    // of the memory pipe as much as a 16-byte one)
     s16x4 sfr[2][8];
-    {
-        const unsigned soff = (unsigned)((lane & 15) * 32 + (lane >> 4) * 8);
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc)
+    for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
-            for (int ri = 0; ri < 8; ++ri)
-                sfr[cc][ri] = *(const s16x4*)((const unsigned char*)Sp + ((size_t)(cw[cc] * 8 + ri) << 9) + soff);
-    }
+        for (int rp = 0; rp < 4; ++rp) {
+            const uint4 t = *(const uint4*)((const unsigned char*)Sp + ((size_t)(cw[cc] * 4 + rp) << 10) + lane16);
+            const uint2 lo = make_uint2(t.x, t.y), hi = make_uint2(t.z, t.w);
+            sfr[cc][2 * rp] = *(const s16x4*)&lo;
+            sfr[cc][2 * rp + 1] = *(const s16x4*)&hi;
+        }
 
     // ---- phase 1: both blocks of this wavefront, then one 4-byte LDS write per (token, rank index)
     // holding the pair (slots 2*wave, 2*wave+1 of the permuted block order j' = (j%8)*2 + j/8, which

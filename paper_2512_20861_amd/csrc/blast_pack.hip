@@ -39,14 +39,18 @@ __global__ __launch_bounds__(256) void pack_va_kernel(const bf16_t* __restrict__
     Va[e] = (c >= 0 && c < q) ? V[((int64_t)j * q + c) * r + rho] : (bf16_t)0;
 }
 
-// perm: the slot order of the single-kernel path, slot j' = (j % 8)*2 + j/8 holds input block j
+// perm: the form the single-kernel path reads. Slot j' = (j % 8)*2 + j/8 holds input block j, and the
+// tiles are in the fragment order of v_mfma_f32_16x16x16_bf16 with two rank indices per 16 bytes:
+//   Sq[rho/2][lane][rho%2][v] = S'[rho][i = lane%16][slot 4 (lane/16) + v]
+// so that a lane fetches the B operands of two rank indices with one 16-byte load.
 __global__ __launch_bounds__(256) void pack_s_kernel(const bf16_t* S, bf16_t* Sp, int b, int r, int perm) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= (int64_t)r * 256) return;
     const int slot = (int)(e & 15), i = (int)((e >> 4) & 15);
     const int j = perm ? (slot >> 1) + (slot & 1) * 8 : slot;
     const int rho = (int)(e >> 8);
-    Sp[e] = (i < b && j < b) ? S[((int64_t)i * b + j) * r + rho] : (bf16_t)0;
+    const int64_t dst = perm ? (((int64_t)(rho >> 1) * 64 + (slot >> 2) * 16 + i) * 8 + (rho & 1) * 4 + (slot & 3)) : e;
+    Sp[dst] = (i < b && j < b) ? S[((int64_t)i * b + j) * r + rho] : (bf16_t)0;
 }
 
 // V in the fragment order of v_mfma_f32_32x32x16_bf16 (see blr_common.h), zero-filled past q and r
