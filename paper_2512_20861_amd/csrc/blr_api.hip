@@ -110,23 +110,6 @@ blr_status run_pack(const void* U, const void* S, const void* V, void* packed, i
                                       n_in, n_out, b, r, s));
 }
 
-}  // namespace
-
-extern "C" {
-
-const char* blr_status_string(blr_status s) {
-    switch (s) {
-        case BLR_OK: return "ok";
-        case BLR_ERR_INVALID_ARG: return "invalid argument";
-        case BLR_ERR_UNSUPPORTED: return "unsupported configuration";
-        case BLR_ERR_WORKSPACE: return "workspace missing or too small";
-        case BLR_ERR_LAUNCH: return "kernel launch failed";
-    }
-    return "unknown status";
-}
-
-namespace {
-
 // Both Monarch entry points: b1 input blocks, b2 output blocks, per-block rank rp.
 blr_status monarch_run(const void* X, const void* R, const void* L, void* Y, int64_t T, int n_in, int n_out,
                        int b1, int b2, int rp, blr_dtype dt, unsigned flags, void* workspace, hipStream_t s) {
@@ -166,6 +149,19 @@ bool monarch_rect_shape_ok(int64_t T, int n_in, int n_out, int b1, int b2, int r
 }
 
 }  // namespace
+
+extern "C" {
+
+const char* blr_status_string(blr_status s) {
+    switch (s) {
+        case BLR_OK: return "ok";
+        case BLR_ERR_INVALID_ARG: return "invalid argument";
+        case BLR_ERR_UNSUPPORTED: return "unsupported configuration";
+        case BLR_ERR_WORKSPACE: return "workspace missing or too small";
+        case BLR_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
 
 size_t blr_monarch_workspace_bytes(int64_t T, int n_in, int n_out, int nblocks, int r, blr_dtype dt) {
     if (!monarch_shape_ok(T, n_in, n_out, nblocks, r) || !dtype_ok(dt)) return 0;
