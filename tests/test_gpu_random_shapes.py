@@ -93,3 +93,56 @@ def test_blast_random_shape(T, n_in, n_out, b, r, mode):
     Y = gu.to_f64(gu.run_blast(X, lay, flags, packed=True))
     err = gu.rel_err(Y, oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64))
     assert err <= gu.TOL["bf16"], (T, n_in, n_out, b, r, mode, err)
+
+
+def _lowrank_shapes():
+    # narrow ranks with long contraction indices and few tiles hit the split contraction; the rest the plain tiles
+    rng = np.random.default_rng(29)
+    out = []
+    for _ in range(16):
+        T = int(rng.choice([1, 7, 33, 64, 100, 130, 300, 520, 900]))
+        n_in = int(rng.integers(8, 400)) * 8
+        n_out = int(rng.integers(1, 200)) * 8
+        r = int(rng.choice([8, 16, 40, 64, 96, 128, 200, 256, 384]))
+        out.append((T, n_in, n_out, r))
+    out += [(512, 4096, 512, 128), (96, 8192, 64, 64), (40, 1000, 1000, 24)]
+    return out
+
+
+@pytest.mark.parametrize("T,n_in,n_out,r", _lowrank_shapes())
+def test_lowrank_random_shape(T, n_in, n_out, r):
+    gu = _gu()
+    lay = bi.lowrank_layer(n_in, n_out, r, "bf16", seed=T + n_out)
+    X = bi.activations(T, n_in, "bf16", seed=r + 1)
+    Y = gu.to_f64(gu.run_lowrank(X, lay))
+    err = gu.rel_err(Y, oracle.lowrank_forward(X.f64, lay.V.f64, lay.U.f64))
+    assert err <= gu.TOL["bf16"], (T, n_in, n_out, r, err)
+
+
+def _monarch_rect_shapes():
+    rng = np.random.default_rng(37)
+    out = []
+    for _ in range(16):
+        b1, b2 = int(rng.choice([1, 2, 3, 4, 8, 16])), int(rng.choice([1, 2, 3, 4, 6, 9, 16]))
+        p, q = int(rng.integers(1, 30)) * 8, int(rng.integers(1, 30)) * 8
+        rp = int(rng.choice([8, 16, 24, 32, 64]))
+        T = int(rng.choice([1, 5, 16, 33, 100, 257, 600]))
+        out.append((T, b1 * p, b2 * q, b1, b2, rp))
+    return out
+
+
+@pytest.mark.parametrize("T,n_in,n_out,b1,b2,rp", _monarch_rect_shapes())
+@pytest.mark.parametrize("order", ["interleaved", "blocked"])
+def test_monarch_rect_random_shape(T, n_in, n_out, b1, b2, rp, order):
+    gu = _gu()
+    p, q = n_in // b1, n_out // b2
+    R = bi.gaussian(T + n_in, 41, (b1, rp * b2, p), 1.0 / np.sqrt(p), "bf16")
+    L = bi.gaussian(T + n_in, 42, (b2, q, b1 * rp), 1.0 / np.sqrt(b1 * rp), "bf16")
+    X = bi.activations(T, n_in, "bf16", seed=rp)
+    blocked = order == "blocked"
+    Y = gu.empty_out(T, n_out, "bf16")
+    gu.B.monarch_rect_forward(gu.to_dev(X), gu.to_dev(R), gu.to_dev(L), Y, b1, b2, rp, gu.B.MONARCH_OUT_BLOCKED if blocked else 0)
+    torch.cuda.synchronize()
+    Yref = oracle.monarch_rect_forward(X.f64, R.f64, L.f64, b1, b2, oracle.OUT_BLOCKED if blocked else oracle.OUT_INTERLEAVED)
+    err = gu.rel_err(gu.to_f64(Y), Yref)
+    assert err <= gu.TOL["bf16"], (T, n_in, n_out, b1, b2, rp, order, err)
