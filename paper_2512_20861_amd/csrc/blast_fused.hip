@@ -68,34 +68,36 @@ __device__ __forceinline__ void load_s_group(const bf16_t* __restrict__ Sp, int 
 // Must be entered after a barrier that follows the last write to Zs. The four 8-byte units (4 blocks
 // each) of a token's 32 bytes are stored XOR 2 for tokens 8..15 of every 16, so that the 32 lanes a
 // fragment read serves per clock (16 tokens x 2 units) touch all 64 banks once.
+template <int TNT = TN>                                  // tokens in the tile (rows of Zs hold TNT tokens)
 __device__ __forceinline__ void couple_group(unsigned char* grp, const s16x4 (&sfrag)[8]) {
+    constexpr int ZSTR = TNT * 32 + 8;
     const int lane = threadIdx.x & 63, ci = lane & 15, cg = lane >> 4;
     // Two batches of 16 fragment reads, each issued back to back before its MFMAs, so that the LDS
     // latency is paid once per batch instead of once per MFMA.
-    f32x4 d[TN / 16][8];
+    f32x4 d[TNT / 16][8];
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-        s16x4 a[4][TN / 16];
+        s16x4 a[4][TNT / 16];
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4)
 #pragma unroll
-            for (int tg = 0; tg < TN / 16; ++tg)
+            for (int tg = 0; tg < TNT / 16; ++tg)
                 a[r4][tg] = *(const s16x4*)(grp + (half * 4 + r4) * ZSTR + (tg * 16 + ci) * 32 + (cg ^ (2 * (ci >> 3))) * 8);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4)
 #pragma unroll
-            for (int tg = 0; tg < TN / 16; ++tg)
+            for (int tg = 0; tg < TNT / 16; ++tg)
                 d[tg][half * 4 + r4] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[r4][tg], sfrag[half * 4 + r4], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
     // d[tg][ri][e]: token tg*16 + 4*(lane/16) + e, output block i = lane%16
 #pragma unroll
-    for (int tg = 0; tg < TN / 16; ++tg)
+    for (int tg = 0; tg < TNT / 16; ++tg)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int tok = tg * 16 + 4 * cg + e;
-            *(uint4*)(grp + (ci * TN + (tok ^ ci)) * 16) =
+            *(uint4*)(grp + (ci * TNT + (tok ^ ci)) * 16) =
                 make_uint4(pack2_bf16(d[tg][0][e], d[tg][1][e]), pack2_bf16(d[tg][2][e], d[tg][3][e]),
                            pack2_bf16(d[tg][4][e], d[tg][5][e]), pack2_bf16(d[tg][6][e], d[tg][7][e]));
         }
@@ -104,7 +106,7 @@ __device__ __forceinline__ void couple_group(unsigned char* grp, const s16x4 (&s
 // A[t][i][rho0 .. rho0+63] from the in-place groups: 8 lanes write the 128 contiguous bytes of one
 // (token, block). tok(t) is the token (relative to t0) that row t of the tile stands for.
 // Must be entered after a barrier that follows couple_group.
-template <int NW, class TokMap>                        // NW wavefronts in the workgroup
+template <int NW, class TokMap, int TNT = TN>          // NW wavefronts in the workgroup, TNT tokens in the tile
 __device__ __forceinline__ void store_a_tile(const unsigned char* Zs, bf16_t* __restrict__ A,
                                              int64_t T, int64_t t0, int rho0, int b, int r, TokMap tok) {
     const int tid = threadIdx.x, c8 = tid & 7;
@@ -112,11 +114,11 @@ __device__ __forceinline__ void store_a_tile(const unsigned char* Zs, bf16_t* __
     const int di = PER % b, dt = PER / b;
     int v = tid >> 3, i = v % b, t = v / b;
     const bool rho_ok = rho0 + c8 * 8 < r;
-    const unsigned char* src = Zs + c8 * GROUP;
-    for (; v < TN * b; v += PER) {
+    const unsigned char* src = Zs + c8 * (8 * (TNT * 32 + 8));
+    for (; v < TNT * b; v += PER) {
         const int64_t tg = t0 + tok(t);
         if (tg < T && rho_ok)
-            *(uint4*)(A + (tg * b + i) * r + rho0 + c8 * 8) = *(const uint4*)(src + (i * TN + (t ^ (i & 15))) * 16);
+            *(uint4*)(A + (tg * b + i) * r + rho0 + c8 * 8) = *(const uint4*)(src + (i * TNT + (t ^ (i & 15))) * 16);
         i += di; t += dt;
         if (i >= b) { i -= b; ++t; }
     }
@@ -125,16 +127,20 @@ __device__ __forceinline__ void store_a_tile(const unsigned char* Zs, bf16_t* __
 // Stand-alone coupling (the middle kernel of the three-kernel path): Z[T][b][r] -> A[T][b][r].
 // The Z tile is read with full-line loads (8 lanes per 128-byte row segment) and transposed on its
 // way into LDS; blocks j and j+1 travel together so that every LDS write is a bf16 pair.
+// TNT tokens per workgroup: 64, or 32 when 64-token tiles would leave most of the chip idle.
+template <int TNT>
 __global__ __launch_bounds__(512)
 void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
                            int64_t T, int b, int r, int tiles_r, int nblk) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* Zs = smem;
+    constexpr int ZSTR = TNT * 32 + 8, GROUP = 8 * ZSTR, ZS_BYTES = TR * ZSTR;   // (shadow the 64-token values)
+    static_assert(16 * TNT * 16 <= GROUP && ZS_BYTES % 16 == 0, "in-place A must fit; Zs is cleared with 16-byte stores");
     constexpr int NTHR = 512;                            // 8 wavefronts: one group of 8 rank indices each
     const int tid = threadIdx.x;
     const int logical = xcd_contiguous(blockIdx.x, nblk);
     const int tile_t = logical / tiles_r, tile_r = logical % tiles_r;
-    const int64_t t0 = (int64_t)tile_t * TN;
+    const int64_t t0 = (int64_t)tile_t * TNT;
     const int rho0 = tile_r * TR;
     s16x4 sfrag[8];
     load_s_group(Sp, rho0, tid >> 6, r, sfrag);          // in flight while Z is brought in
@@ -146,7 +152,7 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
         for (int i = tid * 16; i < ZS_BYTES; i += NTHR * 16) *(uint4*)(Zs + i) = make_uint4(0, 0, 0, 0);
     if (b < 16) __syncthreads();
     // work item = (token, block pair): 8 lanes cover its 128-byte segment; 4 items in flight per thread
-    const int items = TN * npair;
+    const int items = TNT * npair;
     constexpr int IPS = NTHR / 8;                        // items per sweep of the workgroup
     for (int base = 0; base < items; base += IPS * 4) {
         uint4 v0[4], v1[4];
@@ -180,9 +186,10 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
         }
     }
     __syncthreads();
-    couple_group(Zs + (tid >> 6) * GROUP, sfrag);
+    couple_group<TNT>(Zs + (tid >> 6) * GROUP, sfrag);
     __syncthreads();
-    store_a_tile<8>(Zs, A, T, t0, rho0, b, r, [](int t) { return t; });
+    auto same = [](int t) { return t; };
+    store_a_tile<8, decltype(same), TNT>(Zs, A, T, t0, rho0, b, r, same);
 }
 
 // Stage 1 + coupling. Per step (one chunk of 64 input columns of one input block j) a stage of LDS
@@ -371,18 +378,27 @@ hipError_t launch_blast_stage12(const void* X, const void* Va, const void* Sp, v
     return hipGetLastError();
 }
 
-hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
+template <int TNT>
+static hipError_t launch_coupling_inst(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
+    constexpr int lds = TR * (TNT * 32 + 8);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)blast_coupling_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ZS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)blast_coupling_kernel<TNT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles_t = (int)((T + TN - 1) / TN), tiles_r = (r + TR - 1) / TR;
+    const int tiles_t = (int)((T + TNT - 1) / TNT), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
-    hipLaunchKernelGGL(blast_coupling_kernel, dim3((unsigned)nblk), dim3(512), ZS_BYTES, s,
+    hipLaunchKernelGGL(blast_coupling_kernel<TNT>, dim3((unsigned)nblk), dim3(512), lds, s,
                        (const bf16_t*)Z, (const bf16_t*)Sp, (bf16_t*)A, T, b, r, tiles_r, nblk);
     return hipGetLastError();
+}
+
+hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
+    // 64-token tiles unless they would leave most compute units without a workgroup
+    const int64_t tiles64 = ((T + 63) / 64) * ((r + TR - 1) / TR);
+    if (tiles64 < 200) return launch_coupling_inst<32>(Z, Sp, A, T, b, r, s);
+    return launch_coupling_inst<64>(Z, Sp, A, T, b, r, s);
 }
 
 namespace {
