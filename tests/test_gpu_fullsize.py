@@ -150,3 +150,48 @@ def test_graph_replay_and_prepared_calls_match_eager():
     B.prepared(B.blast_forward, Xb, Ud, None, packed, Yb, 16, 96, B.BLAST_PACKED)()
     torch.cuda.synchronize()
     assert torch.equal(Yb.view(torch.int16), Yb_e.view(torch.int16))
+
+
+@pytest.mark.parametrize("op", ["monarch", "blast", "lowrank", "dense"])
+def test_many_tokens_sampled(op):
+    """100 000 tokens on narrow layers (thousands of workgroups; several token chunks in the BLAST
+    paths that walk the tokens in chunks); the oracle recomputes sampled rows."""
+    gu = _gu()
+    B = gu.B
+    T = 100_000
+    rows = _sample_rows(T, 40)
+    sel = torch.from_numpy(rows).cuda()
+    if op == "monarch":
+        lay = bi.monarch_layer(512, 384, 4, 256, "bf16", seed=5)
+        X = bi.activations(T, 512, "bf16", seed=6)
+        Y = gu.run_monarch(X, lay)
+        Yref = oracle.monarch_forward(X.f64[rows], lay.R.f64, lay.L.f64)
+    elif op == "blast":
+        lay = bi.blast_layer(1024, 512, 16, 256, "bf16", seed=5)      # too wide for the single kernel: chunked three-kernel / fused paths
+        X = bi.activations(T, 1024, "bf16", seed=6)
+        Yref = oracle.blast_forward(X.f64[rows], lay.U.f64, lay.S.f64, lay.V.f64)
+        for flag in (0, B.BLAST_THREE_KERNELS):
+            Xd, Ud, Sd, Vd = gu.to_dev(X), gu.to_dev(lay.U), gu.to_dev(lay.S), gu.to_dev(lay.V)
+            packed = B.blast_pack(Ud, Sd, Vd, 1024, 512, 16, 256)
+            Y = gu.empty_out(T, 512, "bf16")
+            B.blast_forward(Xd, Ud, None, packed, Y, 16, 256, B.BLAST_PACKED | flag)
+            torch.cuda.synchronize()
+            assert torch.isfinite(Y.float()).all()
+            assert gu.rel_err(gu.to_f64(Y[sel]), Yref) <= gu.TOL["bf16"]
+        return
+    elif op == "lowrank":
+        lay = bi.lowrank_layer(512, 384, 64, "bf16", seed=5)
+        X = bi.activations(T, 512, "bf16", seed=6)
+        Y = gu.run_lowrank(X, lay)
+        Yref = oracle.lowrank_forward(X.f64[rows], lay.V.f64, lay.U.f64)
+    else:
+        W = bi.dense_weight(512, 384, "bf16", seed=5)
+        X = bi.activations(T, 512, "bf16", seed=6)
+        Y = gu.empty_out(T, 384, "bf16")
+        B.dense_reference_forward(gu.to_dev(X), gu.to_dev(W), Y)
+        torch.cuda.synchronize()
+        Yref = oracle.dense_forward(X.f64[rows], W.f64)
+    assert torch.isfinite(Y.float()).all()
+    err = gu.rel_err(gu.to_f64(Y[sel]), Yref)
+    print(f"{op} T={T}: {len(rows)} sampled rows, rel err {err:.3e}")
+    assert err <= gu.TOL["bf16"]
