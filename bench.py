@@ -316,7 +316,7 @@ def run_sweep(steps, warmup, only=None):
     return rows
 
 
-def run_table3(steps, warmup):
+def run_table3(steps, warmup, scale=1):
     """Every layer shape of the paper's Table 3 (Appendix, Layer Details) with every method, against the
     same-shape dense GEMM; rows go to gpurun_out/table3.json and to stderr."""
     import torch
@@ -324,12 +324,14 @@ def run_table3(steps, warmup):
     rows = []
     for t3 in bi.TABLE3:
         model, lname, n_in, n_out, n, methods = t3
+        n *= scale                                           # `scale` sequences (or images) per call
         W = to_dev(bi.dense_weight(n_in, n_out, "bf16"))
         X = torch.randn((n, n_in), device="cuda", dtype=torch.float32).to(torch.bfloat16)
         Yd = torch.empty((n, n_out), device="cuda", dtype=torch.bfloat16)
         ms_dense = time_graph(lambda: B.prepared(B.dense_reference_forward, X, W, Yd), steps, warmup)
         for method in methods:
             cfg = bi.table3_cfg(t3, method)
+            cfg["T"] = (n,)
             layer = GpuLayer(cfg, n, random_x=False)
             layer.set_x(X)
             ms = time_graph(layer.prepared, steps, warmup)
@@ -346,7 +348,7 @@ def run_table3(steps, warmup):
         del W, X, Yd
         torch.cuda.empty_cache()
     os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "table3.json"), "w") as f:
+    with open(os.path.join(ROOT, "gpurun_out", "table3.json" if scale == 1 else f"table3_x{scale}.json"), "w") as f:
         json.dump(rows, f, indent=1)
     return rows
 
@@ -469,6 +471,7 @@ def main():
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--table3", action="store_true", help="also time every layer shape of the paper's Table 3")
+    ap.add_argument("--table3-scale", type=int, default=1, help="sequences per call for --table3 (token count x this)")
     ap.add_argument("--sweep-configs", default="", help="comma-separated subset of the configurations for --sweep")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -540,7 +543,7 @@ def main():
         T_cpu = min(T, {"C1": 6304, "C0": 8}.get(args.workload, 512))
         out["cpu_baseline"] = cpu_baseline(cfg, T_cpu)
     if args.table3:
-        out["table3"] = run_table3(max(args.steps // 4, 20), max(args.warmup // 2, 5))
+        out["table3"] = run_table3(max(args.steps // 4, 20), max(args.warmup // 2, 5), max(args.table3_scale, 1))
     if args.sweep:
         out["sweep"] = run_sweep(max(args.steps // 4, 20), max(args.warmup // 2, 5), set(filter(None, args.sweep_configs.split(","))))
     print(json.dumps(out), flush=True)
