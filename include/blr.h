@@ -2,8 +2,9 @@
  * blr.h - C ABI of the block low-rank (BLR) linear forward library for AMD MI355X (gfx950).
  *
  * The library evaluates Y = X W^T for a weight W[n_out][n_in] that is never formed, but given
- * by Monarch or BLAST factors (paper Section 2.1, "Weight Structures"), plus a plain dense
- * product that serves as the speed-up denominator.
+ * by Monarch, BLAST or plain low-rank factors (paper Section 2.1, "Weight Structures"), plus a plain
+ * dense product that serves as the speed-up denominator, and the row-wise / elementwise steps that
+ * sit between the linears of a decoder-layer chain.
  *
  * Conventions shared by every entry point
  *   - All pointers are DEVICE pointers (HIP global memory), 16-byte aligned, to dense row-major
