@@ -18,6 +18,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // (arrays of HIP's uint4 struct stay in scratch memory)
 
 constexpr int TN = 64, TR = 64;              // the coupling works on 64 tokens x 64 rank indices at a time
 constexpr int ZSTR = TN * 32 + 8;            // bytes of one rho row of Zs: TN tokens x 16 j x 2 B, + 8 B pad
@@ -104,23 +105,40 @@ __device__ __forceinline__ void couple_group(unsigned char* grp, const s16x4 (&s
 }
 
 // A[t][i][rho0 .. rho0+63] from the in-place groups: 8 lanes write the 128 contiguous bytes of one
-// (token, block). tok(t) is the token (relative to t0) that row t of the tile stands for.
+// (token, block). tok(t) is the token (relative to t0) that row t of the tile stands for. A thread's
+// items go in batches of four: the LDS reads of a batch are issued together, then its stores, so that
+// the LDS latency is paid once per batch.
 // Must be entered after a barrier that follows couple_group.
 template <int NW, class TokMap, int TNT = TN>          // NW wavefronts in the workgroup, TNT tokens in the tile
 __device__ __forceinline__ void store_a_tile(const unsigned char* Zs, bf16_t* __restrict__ A,
                                              int64_t T, int64_t t0, int rho0, int b, int r, TokMap tok) {
     const int tid = threadIdx.x, c8 = tid & 7;
     constexpr int PER = NW * 8;                         // (token, block) items per sweep of the workgroup
+    constexpr int UB = 4;
     const int di = PER % b, dt = PER / b;
     int v = tid >> 3, i = v % b, t = v / b;
-    const bool rho_ok = rho0 + c8 * 8 < r;
+    if (rho0 + c8 * 8 >= r) return;
     const unsigned char* src = Zs + c8 * (8 * (TNT * 32 + 8));
-    for (; v < TNT * b; v += PER) {
-        const int64_t tg = t0 + tok(t);
-        if (tg < T && rho_ok)
-            *(uint4*)(A + (tg * b + i) * r + rho0 + c8 * 8) = *(const uint4*)(src + (i * TNT + (t ^ (i & 15))) * 16);
-        i += di; t += dt;
-        if (i >= b) { i -= b; ++t; }
+    bf16_t* dst = A + t0 * b * r + rho0 + c8 * 8;
+    const int tokens_left = T - t0 < TNT * 2 ? (int)(T - t0) : TNT * 2;   // tok() stays below 2 TNT
+    for (; v < TNT * b; v += PER * UB) {
+        u32x4 val[UB];
+        int off[UB];                                    // elements from dst; (tile tokens) * b * r fits 32 bits (host-checked)
+        bool ok[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int tk = tok(t);
+            ok[u] = v + u * PER < TNT * b && tk < tokens_left;
+            const int tt = ok[u] ? t : 0;               // keep the LDS address inside the tile
+            val[u] = *(const u32x4*)(src + (i * TNT + (tt ^ (i & 15))) * 16);
+            off[u] = (tk * b + i) * r;
+            i += di; t += dt;
+            if (i >= b) { i -= b; ++t; }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+            if (ok[u]) *(u32x4*)(dst + off[u]) = val[u];
     }
 }
 
@@ -433,7 +451,6 @@ static_assert(16 * FT * 16 <= FCHUNK, "in-place A must fit in the chunk it repla
 // 16-byte global load the compiler can neither move nor count: the caller waits on vmcnt itself
 // (the count being the number of vector-memory operations issued after this one) and ties the
 // result to that wait before using it. The "memory" clobber keeps other loads from crossing it.
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ u32x4 global_load_b128_pinned(const void* uniform_base, unsigned lane_offset) {
     u32x4 v;
     asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(lane_offset), "s"(uniform_base) : "memory");

@@ -27,6 +27,12 @@ bool blast_shape_ok(int64_t T, int n_in, int n_out, int b, int r) {
     return T >= 0 && n_in > 0 && n_out > 0 && b > 0 && r > 0 && n_in % b == 0 && n_out % b == 0;
 }
 
+// Shapes the MFMA BLAST kernels take (the others run on the portable kernels): at most 16 blocks,
+// 16-byte rows of V and of the rank index, and a rank whose tile offsets (tokens of a tile * b * r) fit 32 bits.
+bool blast_mfma_shape_ok(int n_in, int b, int r) {
+    return b <= 16 && (n_in / b) % 8 == 0 && r % 8 == 0 && r < (1 << 20);
+}
+
 // Where the re-laid-out BLAST factors live inside the packed buffer.
 struct PackLayout {
     bool full;                       // served by the single-kernel path: fragment-ordered V and U
@@ -74,7 +80,7 @@ BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt,
     BlastPlan pl{};
     const int q = n_in / b;
     const bool packed = flags & BLR_BLAST_PACKED;
-    const bool mfma = dt == BLR_BF16 && !(flags & BLR_FORCE_GENERIC) && b <= 16 && q % 8 == 0 && r % 8 == 0;
+    const bool mfma = dt == BLR_BF16 && !(flags & BLR_FORCE_GENERIC) && blast_mfma_shape_ok(n_in, b, r);
     const size_t per_token = (size_t)b * r * elem_size(dt);
     size_t off = 0;
     pl.chunk = T;
@@ -261,7 +267,7 @@ size_t blr_blast_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, b
 }
 
 size_t blr_blast_packed_bytes(int n_in, int n_out, int b, int r, blr_dtype dt) {
-    if (dt != BLR_BF16 || !blast_shape_ok(0, n_in, n_out, b, r) || b > 16 || (n_in / b) % 8 || r % 8) return 0;
+    if (dt != BLR_BF16 || !blast_shape_ok(0, n_in, n_out, b, r) || !blast_mfma_shape_ok(n_in, b, r)) return 0;
     return pack_layout(n_in, n_out, b, r).total;
 }
 
@@ -269,7 +275,7 @@ blr_status blr_blast_pack(const void* U, const void* S, const void* V, void* pac
                           int n_in, int n_out, int b, int r, blr_dtype dt, blr_stream stream) {
     if (!U || !S || !V || !packed) return BLR_ERR_INVALID_ARG;
     if (!blast_shape_ok(0, n_in, n_out, b, r) || dt != BLR_BF16 || b > 16) return BLR_ERR_INVALID_ARG;
-    if ((n_in / b) % 8 || r % 8) return BLR_ERR_UNSUPPORTED;          // such layers run on the portable kernels, unpacked
+    if (!blast_mfma_shape_ok(n_in, b, r)) return BLR_ERR_UNSUPPORTED;   // such layers run on the portable kernels, unpacked
     if (!aligned16(U) || !aligned16(S) || !aligned16(V) || !aligned16(packed)) return BLR_ERR_INVALID_ARG;
     return run_pack(U, S, V, packed, n_in, n_out, b, r, (hipStream_t)stream);
 }

@@ -18,6 +18,7 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 
 __device__ inline int xcd_contiguous(int bid, int nblk) {
     const int q8 = nblk >> 3, rem = nblk & 7;
@@ -74,29 +75,53 @@ __device__ __forceinline__ void store_c_tile(const GemmDesc& d, const f32x16 (&a
     __syncthreads();
     // A thread's column (group of 8 columns) is the same in every sweep of the workgroup over the
     // rows, so the column map (two integer divisions) is evaluated once per thread, not per element.
+    // The sweeps go in batches: all LDS reads of a batch are issued, then its stores, so that the LDS
+    // latency is paid once per batch and not once per store.
     bf16_t* Cp = (bf16_t*)d.C;
     if (cvec) {
         // groups of 8 consecutive columns map to 8 consecutive, 16-byte aligned elements of C
         constexpr int CPRC = BN / 8;
         static_assert(THREADS % CPRC == 0, "a thread keeps its column group");
-        const int cc = tid % CPRC;
+        constexpr int RPS = THREADS / CPRC, SWEEPS = BM / RPS, UB = SWEEPS < 8 ? SWEEPS : 8;
+        static_assert(BM % RPS == 0 && SWEEPS % UB == 0, "whole sweeps, whole batches");
+        const int cc = tid % CPRC, row0 = tid / CPRC;
         const int n = n0 + cc * 8;
         if (n < d.N) {
             const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
-            for (int row = tid / CPRC; row < BM; row += THREADS / CPRC) {
-                const int64_t m = m0 + row;
-                if (m < d.M) *(uint4*)(Cp + m * d.c_rs + col) = *(const uint4*)(Cs + row * CSTR + cc * 16);
+            const unsigned char* src = Cs + row0 * CSTR + cc * 16;
+            bf16_t* dst = Cp + (m0 + row0) * d.c_rs + col;
+            const int64_t rows_left = d.M - m0 - row0;   // rows of this thread's first sweep and below that exist
+#pragma unroll
+            for (int s0 = 0; s0 < SWEEPS; s0 += UB) {
+                u32x4 v[UB];                            // (a native vector type: arrays of HIP's uint4 struct stay in scratch memory)
+#pragma unroll
+                for (int u = 0; u < UB; ++u) v[u] = *(const u32x4*)(src + (s0 + u) * (RPS * CSTR));
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < UB; ++u)
+                    if ((int64_t)(s0 + u) * RPS < rows_left) *(u32x4*)(dst + (int64_t)(s0 + u) * RPS * d.c_rs) = v[u];
             }
         }
     } else {
         static_assert(THREADS % BN == 0, "a thread keeps its column");
-        const int nn = tid % BN;
+        constexpr int RPS = THREADS / BN, SWEEPS = BM / RPS, UB = SWEEPS < 16 ? SWEEPS : 16;
+        static_assert(BM % RPS == 0 && SWEEPS % UB == 0, "whole sweeps, whole batches");
+        const int nn = tid % BN, row0 = tid / BN;
         const int n = n0 + nn;
         if (n < d.N) {
             const int64_t col = (int64_t)g * d.c_gs + (int64_t)(n / d.c_div) * d.c_hi + (int64_t)(n % d.c_div) * d.c_lo;
-            for (int row = tid / BN; row < BM; row += THREADS / BN) {
-                const int64_t m = m0 + row;
-                if (m < d.M) Cp[m * d.c_rs + col] = *(const bf16_t*)(Cs + row * CSTR + nn * 2);
+            const unsigned char* src = Cs + row0 * CSTR + nn * 2;
+            bf16_t* dst = Cp + (m0 + row0) * d.c_rs + col;
+            const int64_t rows_left = d.M - m0 - row0;
+#pragma unroll
+            for (int s0 = 0; s0 < SWEEPS; s0 += UB) {
+                bf16_t v[UB];
+#pragma unroll
+                for (int u = 0; u < UB; ++u) v[u] = *(const bf16_t*)(src + (s0 + u) * (RPS * CSTR));
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < UB; ++u)
+                    if ((int64_t)(s0 + u) * RPS < rows_left) dst[(int64_t)(s0 + u) * RPS * d.c_rs] = v[u];
             }
         }
     }
