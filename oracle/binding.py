@@ -31,8 +31,12 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        # BLR_ORACLE_LIB: a library built from a deliberately altered copy of the source; only the test
+        # that checks that the pins notice such alterations sets it (in a child process)
+        override = os.environ.get("BLR_ORACLE_LIB")
+        if not override:
+            build()
+        _lib = ctypes.CDLL(override or _LIB)
         for name in ("blr_oracle_dense_forward", "blr_oracle_monarch_forward", "blr_oracle_blast_forward",
                      "blr_oracle_materialize_monarch", "blr_oracle_materialize_blast",
                      "blr_oracle_monarch_middle_perm", "blr_oracle_lowrank_forward",
