@@ -77,6 +77,16 @@ typedef void* blr_stream;      /* a hipStream_t */
  * force one of them (mutually exclusive) so that tests and the benchmark can run both. */
 #define BLR_BLAST_FUSED_STAGE12     0x800u
 #define BLR_BLAST_THREE_KERNELS     0x1000u
+/* flags of the Monarch and low-rank forwards (bf16). Two executions exist: (a) two GEMM kernels with
+ * the intermediate in the workspace, and (b) ONE kernel that keeps the intermediate on chip (the
+ * full fusion of the paper's appendix on low-rank layers, applied to every Monarch form), for narrow
+ * layers: it needs 16 | r/nblocks (resp. r_block, r), 32 | n_in/b_in, 32 | b_in r_block and a
+ * 32-token tile of X plus its intermediate within LDS. By default the library picks (b) for narrow
+ * layers at small and medium token counts, where two launches cost more than their work; these flags
+ * force one of them (mutually exclusive; FUSED returns BLR_ERR_UNSUPPORTED where (b) does not apply,
+ * and cannot be combined with the stage flags or BLR_MONARCH_IN_BLOCKED). */
+#define BLR_MONARCH_FUSED           0x2000u
+#define BLR_MONARCH_TWO_KERNELS     0x4000u
 
 /*
  * Monarch forward (paper Section 2.1 "Monarch"; Section 4 "Monarch", optimisations 1-3).

@@ -116,12 +116,36 @@ blr_status run_pack(const void* U, const void* S, const void* V, void* packed, i
                                       n_in, n_out, b, r, s));
 }
 
+// Is this call (Monarch with b1 x b2 blocks of rank rp; low-rank is 1 x 1) served by the single kernel
+// that keeps the intermediate on chip? It can be when the shape fits and the call asks for neither
+// the portable kernels, nor a single stage, nor a blocked input. It is by default where it was
+// measured faster than the two GEMMs (narrow layers of the ViT-B / GPT2-S kind, 1.1-1.35x): two
+// workgroups fit a compute unit (half of LDS each), not more tokens than one to two rounds of
+// 32-token tiles, and, when the output order interleaves the blocks (2-byte stores at a stride), no more
+// than 1024 tokens.
+constexpr int64_t kFusedMonarchMaxTokens = 4096;
+constexpr int64_t kFusedMonarchMaxTokensInterleaved = 1024;
+constexpr int kFusedMonarchMaxLds = 80 * 1024;
+bool monarch_fused_possible(int64_t T, int n_in, int n_out, int b1, int b2, int rp, blr_dtype dt, unsigned flags) {
+    if (dt != BLR_BF16 || (flags & (BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_MONARCH_IN_BLOCKED | BLR_MONARCH_TWO_KERNELS))) return false;
+    return monarch_fused_supported(T, n_in, n_out, b1, b2, rp);
+}
+bool monarch_takes_fused(int64_t T, int n_in, int n_out, int b1, int b2, int rp, blr_dtype dt, unsigned flags) {
+    if (!monarch_fused_possible(T, n_in, n_out, b1, b2, rp, dt, flags)) return false;
+    if (flags & BLR_MONARCH_FUSED) return true;
+    const bool contiguous = (flags & BLR_MONARCH_OUT_BLOCKED) || b2 == 1;
+    return T > 32 && T <= (contiguous ? kFusedMonarchMaxTokens : kFusedMonarchMaxTokensInterleaved) &&
+           monarch_fused_lds_bytes(T, n_in, n_out, b1, b2, rp) <= kFusedMonarchMaxLds;
+}
+
 // Both Monarch entry points: b1 input blocks, b2 output blocks, per-block rank rp.
 blr_status monarch_run(const void* X, const void* R, const void* L, void* Y, int64_t T, int n_in, int n_out,
                        int b1, int b2, int rp, blr_dtype dt, unsigned flags, void* workspace, hipStream_t s) {
     const int p = n_in / b1, q = n_out / b2;
     const int w1 = rp * b2, w2 = b1 * rp;               // widths of one middle block before / after the permutation
     const bool allow_mfma = !(flags & BLR_FORCE_GENERIC);
+    if (monarch_takes_fused(T, n_in, n_out, b1, b2, rp, dt, flags))
+        return from_hip(launch_monarch_fused(X, R, L, Y, T, n_in, n_out, b1, b2, rp, flags & BLR_MONARCH_OUT_BLOCKED, s));
 
     // stage 1: block-diagonal R; tile column n' = k*r' + rho reads row rho*b2 + k of R[l] (the
     // re-layout of the first factor done in the load index) and lands at Z'[t][k][l*r' + rho]
@@ -179,13 +203,15 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
                                blr_dtype dt, unsigned flags,
                                void* workspace, size_t workspace_bytes, blr_stream stream) {
     if (!monarch_shape_ok(T, n_in, n_out, nblocks, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
-    if (flags & ~(BLR_MONARCH_OUT_BLOCKED | BLR_MONARCH_IN_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_MONARCH_OUT_BLOCKED | BLR_MONARCH_IN_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_MONARCH_FUSED | BLR_MONARCH_TWO_KERNELS)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_MONARCH_FUSED) && (flags & (BLR_MONARCH_TWO_KERNELS | BLR_MONARCH_IN_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE))) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_MONARCH_IN_BLOCKED) && (n_in / nblocks) % nblocks) return BLR_ERR_INVALID_ARG;
     if (!R || !L) return BLR_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(R) || !aligned16(L) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
     if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null
     if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_MONARCH_FUSED) && !monarch_fused_possible(T, n_in, n_out, nblocks, nblocks, r / nblocks, dt, flags)) return BLR_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < blr_monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt)) return BLR_ERR_WORKSPACE;
     return monarch_run(X, R, L, Y, T, n_in, n_out, nblocks, nblocks, r / nblocks, dt, flags, workspace, (hipStream_t)stream);
 }
@@ -200,12 +226,14 @@ blr_status blr_monarch_rect_forward(const void* X, const void* R, const void* L,
                                     blr_dtype dt, unsigned flags,
                                     void* workspace, size_t workspace_bytes, blr_stream stream) {
     if (!monarch_rect_shape_ok(T, n_in, n_out, b_in, b_out, r_block) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
-    if (flags & ~(BLR_MONARCH_OUT_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_MONARCH_OUT_BLOCKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_MONARCH_FUSED | BLR_MONARCH_TWO_KERNELS)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_MONARCH_FUSED) && (flags & (BLR_MONARCH_TWO_KERNELS | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE))) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
     if (!R || !L) return BLR_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(R) || !aligned16(L) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
     if (T == 0) return BLR_OK;
     if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_MONARCH_FUSED) && !monarch_fused_possible(T, n_in, n_out, b_in, b_out, r_block, dt, flags)) return BLR_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < blr_monarch_rect_workspace_bytes(T, n_in, n_out, b_in, b_out, r_block, dt)) return BLR_ERR_WORKSPACE;
     return monarch_run(X, R, L, Y, T, n_in, n_out, b_in, b_out, r_block, dt, flags, workspace, (hipStream_t)stream);
 }
@@ -221,14 +249,19 @@ blr_status blr_lowrank_forward(const void* X, const void* V, const void* U, void
                                int64_t T, int n_in, int n_out, int r, blr_dtype dt, unsigned flags,
                                void* workspace, size_t workspace_bytes, blr_stream stream) {
     if (T < 0 || T >= (1ll << 31) || n_in <= 0 || n_out <= 0 || r <= 0 || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
-    if (flags & ~(BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_MONARCH_FUSED | BLR_MONARCH_TWO_KERNELS)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_MONARCH_FUSED) && (flags & (BLR_MONARCH_TWO_KERNELS | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE))) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
     if (!V || !U) return BLR_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(V) || !aligned16(U) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
     if (T == 0) return BLR_OK;
     if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_MONARCH_FUSED) && !monarch_fused_possible(T, n_in, n_out, 1, 1, r, dt, flags)) return BLR_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < blr_lowrank_workspace_bytes(T, n_in, n_out, r, dt)) return BLR_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
+    // a single block of a Monarch layer: V and U are its two factors in the same storage orders
+    if (monarch_takes_fused(T, n_in, n_out, 1, 1, r, dt, flags))
+        return from_hip(launch_monarch_fused(X, V, U, Y, T, n_in, n_out, 1, 1, r, true, s));
     const bool allow_mfma = !(flags & BLR_FORCE_GENERIC);
     // Z[T][r] = X V^T, then Y = Z U^T: two plain NT products, the narrow intermediate in the workspace.
     // With few tokens and a narrow rank the first product has few tiles and a long contraction index:

@@ -92,6 +92,14 @@ size_t gemm_split_scratch_bytes(int64_t M, int N, int K, int G);
 bool skinny_gemm_supported(const GemmDesc& d);
 hipError_t launch_gemm_skinny(const GemmDesc& d, bool cvec, hipStream_t s);
 
+// Monarch (b1 input blocks, b2 output blocks, per-block rank rp; low-rank is b1 = b2 = 1) in one kernel
+// for narrow layers: the intermediate stays on chip. Needs 16 | rp, 32 | n_in/b1, 32 | b1 rp and a token
+// tile plus intermediate that fit LDS.
+bool monarch_fused_supported(int64_t T, int n_in, int n_out, int b1, int b2, int rp);
+int monarch_fused_lds_bytes(int64_t T, int n_in, int n_out, int b1, int b2, int rp);   // of a supported call
+hipError_t launch_monarch_fused(const void* X, const void* R, const void* L, void* Y, int64_t T, int n_in, int n_out,
+                                int b1, int b2, int rp, bool out_blocked, hipStream_t s);
+
 // BLAST: fused stage 1 + coupling on MFMA. X[T][n_in], Vt[b][r][q], Sp[r][16][16] -> A[T][b][r] (bf16)
 bool blast_fused_supported(int64_t T, int n_in, int b, int r);
 int64_t blast_fused_tiles(int64_t T, int r);                 // workgroups the fused stage 1 + coupling kernel would launch

@@ -89,6 +89,14 @@ def test_monarch_argument_checks():
     assert _monarch(flags=B.ONLY_FIRST_STAGE | B.ONLY_LAST_STAGE) == B.ERR_INVALID_ARG
     assert _blast(flags=B.BLAST_FUSED_STAGE12 | B.BLAST_THREE_KERNELS) == B.ERR_INVALID_ARG
     assert _monarch(flags=B.BLAST_THREE_KERNELS) == B.ERR_INVALID_ARG
+    # single-kernel execution: exclusive with the two-kernel flag, the stage flags, the portable kernels, a blocked input
+    for other in (B.MONARCH_TWO_KERNELS, B.ONLY_FIRST_STAGE, B.ONLY_LAST_STAGE, B.FORCE_GENERIC, B.MONARCH_IN_BLOCKED):
+        assert _monarch(n_in=512, n_out=512, nb=4, r=64, flags=B.MONARCH_FUSED | other) == B.ERR_INVALID_ARG
+    # ... and unsupported where its shape rules do not hold: 16 | r/nblocks, 32 | n_in/nblocks, bf16
+    assert _monarch(n_in=512, n_out=512, nb=4, r=32, flags=B.MONARCH_FUSED) == B.ERR_UNSUPPORTED
+    assert _monarch(n_in=64, n_out=64, nb=4, r=64, flags=B.MONARCH_FUSED) == B.ERR_UNSUPPORTED
+    assert _monarch(n_in=512, n_out=512, nb=4, r=64, dt=B.F32, flags=B.MONARCH_FUSED) == B.ERR_UNSUPPORTED
+    assert _monarch(n_in=512, n_out=512, nb=4, r=64, flags=B.MONARCH_FUSED, ws=None) == B.ERR_WORKSPACE   # same workspace contract
     # blocked input needs nblocks^2 | n_in
     assert _monarch(n_in=60, n_out=60, nb=6, r=12, flags=B.MONARCH_IN_BLOCKED) == B.ERR_INVALID_ARG
     L = B.lib()

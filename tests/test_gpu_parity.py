@@ -295,3 +295,71 @@ def test_linearity_on_gpu():
     X3 = bi.store(2.0 * X1.f64 - 0.5 * X2.f64, "f32")
     f = lambda X: gu.to_f64(gu.run_blast(X, lay))
     np.testing.assert_allclose(f(X3), 2.0 * f(X1) - 0.5 * f(X2), rtol=0, atol=2e-5 * np.abs(f(X1)).max())
+
+
+# Single-kernel Monarch / low-rank (intermediate on chip): forced by flag, against the oracle and
+# against the two-kernel execution of the same call. Shapes cover several column tiles per wavefront,
+# one and several output ranges per block, a ragged last token tile, wavefronts with and without tiles
+# in either phase, b1 != b2, and outputs that do / do not allow 16-byte stores.
+FUSED_MONARCH_CASES = [
+    # T, n_in, n_out, b1, b2, r'
+    (197, 768, 2304, 4, 4, 32),
+    (1024, 768, 2304, 4, 4, 48),
+    (70, 768, 3072, 4, 4, 48),
+    (33, 256, 200, 2, 5, 16),
+    (100, 1024, 1152, 4, 4, 32),
+    (64, 2048, 512, 8, 2, 16),
+    (300, 256, 72, 1, 3, 64),
+    (31, 1024, 768, 4, 4, 48),
+    (500, 768, 768, 4, 4, 16),
+    (130, 512, 1040, 4, 13, 48),
+]
+
+
+@pytest.mark.parametrize("T,n_in,n_out,b1,b2,rp", FUSED_MONARCH_CASES)
+@pytest.mark.parametrize("order", ["interleaved", "blocked"])
+def test_monarch_single_kernel_parity(T, n_in, n_out, b1, b2, rp, order):
+    gu = _gu()
+    B = gu.B
+    p, q = n_in // b1, n_out // b2
+    R = bi.gaussian(T + n_in, 51, (b1, rp * b2, p), 1.0 / np.sqrt(p), "bf16")
+    L = bi.gaussian(T + n_in, 52, (b2, q, b1 * rp), 1.0 / np.sqrt(b1 * rp), "bf16")
+    X = bi.activations(T, n_in, "bf16", seed=rp + b2)
+    blocked = order == "blocked"
+    fl = B.MONARCH_OUT_BLOCKED if blocked else 0
+    Xd, Rd, Ld = gu.to_dev(X), gu.to_dev(R), gu.to_dev(L)
+    Y1, Y2 = gu.empty_out(T, n_out, "bf16"), gu.empty_out(T, n_out, "bf16")
+    B.monarch_rect_forward(Xd, Rd, Ld, Y1, b1, b2, rp, fl | B.MONARCH_FUSED)
+    B.monarch_rect_forward(Xd, Rd, Ld, Y2, b1, b2, rp, fl | B.MONARCH_TWO_KERNELS)
+    torch.cuda.synchronize()
+    Yref = oracle.monarch_rect_forward(X.f64, R.f64, L.f64, b1, b2, oracle.OUT_BLOCKED if blocked else oracle.OUT_INTERLEAVED)
+    assert gu.rel_err(gu.to_f64(Y1), Yref) <= gu.TOL["bf16"]
+    assert gu.rel_err(gu.to_f64(Y2), Yref) <= gu.TOL["bf16"]
+    assert gu.rel_err(gu.to_f64(Y1), gu.to_f64(Y2)) <= gu.TOL["bf16"]
+    if b1 == b2:                                            # the square entry point takes the same path
+        Y3 = gu.empty_out(T, n_out, "bf16")
+        B.monarch_forward(Xd, Rd, Ld, Y3, b1, rp * b1, fl | B.MONARCH_FUSED)
+        torch.cuda.synchronize()
+        assert torch.equal(Y3, Y1)
+
+
+@pytest.mark.parametrize("T,n_in,n_out,r", [(197, 256, 2304, 128), (1024, 224, 3072, 192), (40, 160, 1152, 64), (333, 256, 768, 256), (65, 96, 40, 32)])
+def test_lowrank_single_kernel_parity(T, n_in, n_out, r):
+    gu = _gu()
+    B = gu.B
+    lay = bi.lowrank_layer(n_in, n_out, r, "bf16", seed=T + r)
+    X = bi.activations(T, n_in, "bf16", seed=n_out)
+    Yref = oracle.lowrank_forward(X.f64, lay.V.f64, lay.U.f64)
+    Y1 = gu.to_f64(gu.run_lowrank(X, lay, B.MONARCH_FUSED))
+    Y2 = gu.to_f64(gu.run_lowrank(X, lay, B.MONARCH_TWO_KERNELS))
+    assert gu.rel_err(Y1, Yref) <= gu.TOL["bf16"]
+    assert gu.rel_err(Y2, Yref) <= gu.TOL["bf16"]
+
+
+def test_single_kernel_is_unsupported_where_its_shape_rules_fail():
+    gu = _gu()
+    B = gu.B
+    lay = bi.monarch_layer(256, 256, 4, 32, "bf16", seed=3)       # r' = 8
+    X = bi.activations(8, 256, "bf16", seed=4)
+    with pytest.raises(RuntimeError):
+        gu.run_monarch(X, lay, B.MONARCH_FUSED)
