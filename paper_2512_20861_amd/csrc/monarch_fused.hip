@@ -7,7 +7,7 @@
 // lose to the single dense GEMM they replace; one launch that never writes the intermediate wins that
 // back. The large layers keep the two GEMMs: there the weights are re-used over 256-token tiles.
 //
-// A workgroup (4 wavefronts) owns 32 tokens, one output block k and a range of that block's outputs:
+// A workgroup (4 or 8 wavefronts) owns 32 tokens, one output block k and a range of that block's outputs:
 //   phase 0  X[32][n_in] -> LDS (rows past T repeat the last row and are never stored)
 //   phase 1  Z'_k[t][l r' + rho] = sum_a X[t][l p + a] R[l][rho b2 + k][a]        -> LDS, bf16
 //            (all input blocks l, i.e. everything output block k needs; a workgroup of another output
@@ -30,7 +30,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // (arrays of HIP's uint4 struct stay in scratch memory)
 
 constexpr int MF_TT = 32;          // tokens per workgroup
-constexpr int MF_WAVES = 4;
+constexpr int MF_MAX_WAVES = 8;    // wavefronts per workgroup: 8 when the launch has at most one workgroup per compute unit, else 4
 constexpr int MF_KC = 8;           // k32 steps per group of weight fragments
 
 struct MonarchFusedArgs {
@@ -47,10 +47,11 @@ struct MonarchFusedArgs {
 // fragment of a tile is one load or LDS read with an immediate offset from one address per tile: with run-time
 // counts the index arithmetic per fragment, not the memory system, bounded the kernel (1 us per tile).
 template <int KS1, int KS2>
-__global__ __launch_bounds__(64 * MF_WAVES) void monarch_fused_kernel(MonarchFusedArgs a) {
+__global__ __launch_bounds__(64 * MF_MAX_WAVES) void monarch_fused_kernel(MonarchFusedArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nw = (int)(blockDim.x >> 6);              // 4 or 8
     const int l16 = lane & 15, kg = lane >> 4;
     const int64_t t0 = (int64_t)blockIdx.x * MF_TT;
     const int k = blockIdx.y / a.jsplit;
@@ -69,10 +70,11 @@ __global__ __launch_bounds__(64 * MF_WAVES) void monarch_fused_kernel(MonarchFus
         const int last = a.T - t0 > MF_TT ? MF_TT - 1 : (int)(a.T - t0) - 1;
 #pragma unroll 1
         for (int c0 = 0; c0 < pieces; c0 += 128) {
-            u32x4 v[MF_TT / MF_WAVES][2];
+            u32x4 v[MF_TT / 4][2];                      // rows wave, wave + nw, ...: 8 of them with 4 wavefronts, 4 with 8
 #pragma unroll
-            for (int i = 0; i < MF_TT / MF_WAVES; ++i) {
-                int row = wave + MF_WAVES * i;
+            for (int i = 0; i < MF_TT / 4; ++i) {
+                if (nw * i >= MF_TT) break;             // uniform
+                int row = wave + nw * i;
                 if (row > last) row = last;
                 const unsigned roff = (unsigned)(row * a.n_in) * 2u;
 #pragma unroll
@@ -83,11 +85,11 @@ __global__ __launch_bounds__(64 * MF_WAVES) void monarch_fused_kernel(MonarchFus
                 }
             }
 #pragma unroll
-            for (int i = 0; i < MF_TT / MF_WAVES; ++i)
+            for (int i = 0; i < MF_TT / 4; ++i)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     const int c = c0 + h * 64 + lane;
-                    if (c < pieces) *(u32x4*)(Xs + (wave + MF_WAVES * i) * a.xstr + c * 16) = v[i][h];
+                    if (c < pieces && wave + nw * i < MF_TT) *(u32x4*)(Xs + (wave + nw * i) * a.xstr + c * 16) = v[i][h];
                 }
         }
     };
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(64 * MF_WAVES) void monarch_fused_kernel(MonarchFus
     // three tiles ahead of the MFMAs, across the barrier that separates the phases (four register
     // buffers in rotation): the kernel is a stream of the factors through the CU.
     const int n1 = a.w2 >> 4, n2 = (nj + 15) >> 4;
-    const int ch1 = (n1 + MF_WAVES - 1) / MF_WAVES, ch2 = (n2 + MF_WAVES - 1) / MF_WAVES;
+    const int ch1 = (n1 + nw - 1) / nw, ch2 = (n2 + nw - 1) / nw;
     const int s1 = wave * ch1, s2 = wave * ch2;
     const int c1 = n1 - s1 < ch1 ? (n1 - s1 > 0 ? n1 - s1 : 0) : ch1;    // this wavefront's tiles of phase 1 / phase 2
     const int c2 = n2 - s2 < ch2 ? (n2 - s2 > 0 ? n2 - s2 : 0) : ch2;
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(64 * MF_WAVES) void monarch_fused_kernel(MonarchFus
     const int64_t col0 = contiguous ? (int64_t)k * a.q + j0 : (int64_t)j0 * a.b2 + k;
     if (contiguous && (nj & 7) == 0 && (col0 & 7) == 0 && (a.n_out & 7) == 0) {
         const int pieces = nj >> 3;
-        for (int row = wave; row < MF_TT; row += MF_WAVES) {
+        for (int row = wave; row < MF_TT; row += nw) {
             const int64_t t = t0 + row;
             if (t >= a.T) break;                        // uniform
             for (int c = lane; c < pieces; c += 64)
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(64 * MF_WAVES) void monarch_fused_kernel(MonarchFus
         }
     } else {
         const int cstep = contiguous ? 1 : a.b2;
-        for (int row = wave; row < MF_TT; row += MF_WAVES) {
+        for (int row = wave; row < MF_TT; row += nw) {
             const int64_t t = t0 + row;
             if (t >= a.T) break;                        // uniform
             for (int c = lane; c < nj; c += 64)
@@ -234,7 +236,9 @@ hipError_t launch_inst(const MonarchFusedArgs& a, dim3 grid, int lds, hipStream_
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((monarch_fused_kernel<KS1, KS2>), grid, dim3(64 * MF_WAVES), lds, s, a);
+    // one workgroup per compute unit at most: twice the wavefronts, i.e. twice the weight bytes in flight per compute unit
+    const unsigned waves = (uint64_t)grid.x * grid.y <= 256 ? MF_MAX_WAVES : MF_MAX_WAVES / 2;
+    hipLaunchKernelGGL((monarch_fused_kernel<KS1, KS2>), grid, dim3(64 * waves), lds, s, a);
     return hipGetLastError();
 }
 
