@@ -30,15 +30,21 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
     const int n0 = (blockIdx.x % tiles_n) * SK_BN;
     const int l16 = lane & 15, kg = lane >> 4;          // fragment row, group of 8 consecutive k (of the step's 32)
 
-    // fragment sources: weight row n0 + l16, token rows mt*16 + l16
-    int n = n0 + l16;
+    // A fragment (16 rows x 32 k) is LOADED with four neighbouring lanes on the 64 contiguous bytes of one
+    // row (lane = 4 row + piece: 16 requests of 64 bytes per instruction) and moved to the MFMA's order
+    // (lane = 16 piece + row) by a cross-lane permute when it is used: loaded in the MFMA's order every
+    // lane would be a 16-byte request of its own, which the load path serves several times slower.
+    const int ld_row = lane >> 2, ld_piece = lane & 3;
+    const int from_lane = (l16 * 4 + kg) * 4;           // byte index of the lane that loaded this lane's piece
+    // fragment sources: weight row n0 + ld_row, token rows mt*16 + ld_row
+    int n = n0 + ld_row;
     if (n > d.N - 1) n = d.N - 1;                       // rows past N repeat the last row; never stored
     const int64_t nr = d.b_div ? (int64_t)(n % d.b_div) * d.b_mul + n / d.b_div : n;
     const bf16_t* wp = (const bf16_t*)d.B + (int64_t)g * d.b_gs + nr * d.b_rs;
     const bf16_t* xp[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        int64_t m = mt * 16 + l16;
+        int64_t m = mt * 16 + ld_row;
         if (m > d.M - 1) m = d.M - 1;
         xp[mt] = (const bf16_t*)d.A + (int64_t)g * d.a_gs + m * d.a_rs;
     }
@@ -56,7 +62,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
         constexpr int slot = decltype(SLOT)::value;
         int ks = s_begin + s;
         if (ks > nk - 1) ks = nk - 1;                   // steps past the end repeat the last one; never consumed
-        int k = ks * 32 + kg * 8;
+        int k = ks * 32 + ld_piece * 8;
         if (k > d.K - 8) k = d.K - 8;                   // k groups past K re-read valid data (K is a multiple of 8)
         rw[slot] = *(const uint4*)(wp + k);
         // segmented contraction index of A: a k32 step lies inside one segment (uniform division)
@@ -64,16 +70,22 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) rx[slot][mt] = *(const uint4*)(xp[mt] + ka);
     };
+    auto to_mfma_order = [&](uint4 v) -> uint4 {
+        return make_uint4((unsigned)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.x), (unsigned)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.y),
+                          (unsigned)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.z), (unsigned)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.w));
+    };
     f32x4 acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
     auto step = [&](auto U, int s) {
         constexpr int u = decltype(U)::value;
         const bool ok = (s_begin + s) * 32 + kg * 8 < d.K;
-        const uint4 w = keep_if(ok, rw[u]);
+        const uint4 w = keep_if(ok, to_mfma_order(rw[u]));
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&w, *(const bf16x8*)&rx[u][mt], acc[mt], 0, 0, 0);
+        for (int mt = 0; mt < MT; ++mt) {
+            const uint4 x = to_mfma_order(rx[u][mt]);
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&w, *(const bf16x8*)&x, acc[mt], 0, 0, 0);
+        }
         gload(U, s + D);
     };
     static_for<D>([&](auto U) { gload(U, decltype(U)::value); });
