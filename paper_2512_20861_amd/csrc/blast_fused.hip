@@ -39,14 +39,6 @@ constexpr int ST_LPW = ST_ROWS / 64;         // direct-to-LDS loads per wavefron
 static_assert(ST_LPW * (ST_PD - 1) < 64, "vmcnt range");
 
 
-// workgroup id -> logical tile id such that each XCD (workgroups are dealt round-robin over 8 XCDs)
-// works on a contiguous range of logical ids, i.e. shares its X tiles in its own L2
-__device__ inline int xcd_contiguous(int bid, int nblk) {
-    const int q8 = nblk >> 3, rem = nblk & 7;
-    const int xcd = bid & 7, slot = bid >> 3;
-    return xcd * q8 + (xcd < rem ? xcd : rem) + slot;
-}
-
 // Coupling of one 64-token x 64-rank tile whose Z values sit in LDS as Zs[rho][t][j] (bf16):
 // A[t][i][rho] = sum_j S[i][j][rho] Z[t][j][rho] on v_mfma_f32_16x16x16_bf16, one MFMA per rank index
 // and 16 tokens, S tiles from the packed Sp[rho][i][j]. The 64 rank indices form 8 groups of 8; a

@@ -19,6 +19,14 @@ __host__ __device__ inline void static_for(F&& f) {
 
 typedef unsigned short bf16_t;  // bfloat16 bit pattern
 
+// Workgroup id -> logical work item id such that each XCD (the hardware deals workgroup ids round-robin
+// over the 8 XCDs) works on a contiguous range of logical ids: neighbours in logical order share an L2.
+__device__ inline int xcd_contiguous(int bid, int nblk) {
+    const int q8 = nblk >> 3, rem = nblk & 7;
+    const int xcd = bid & 7, slot = bid >> 3;
+    return xcd * q8 + (xcd < rem ? xcd : rem) + slot;
+}
+
 __host__ __device__ inline float bf16_to_float(bf16_t v) {
     union { uint32_t u; float f; } c;
     c.u = (uint32_t)v << 16;

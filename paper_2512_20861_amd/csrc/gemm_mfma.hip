@@ -20,12 +20,6 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 
-__device__ inline int xcd_contiguous(int bid, int nblk) {
-    const int q8 = nblk >> 3, rem = nblk & 7;
-    const int xcd = bid & 7, slot = bid >> 3;
-    return xcd * q8 + (xcd < rem ? xcd : rem) + slot;
-}
-
 // Tile and batch index of this workgroup. Workgroup ids are remapped so that each XCD owns a
 // contiguous range of tiles, walked in groups of 8 row-tiles per column-tile. With a scattering
 // column map (gfast) the batch index varies fastest, so the G workgroups that interleave their
