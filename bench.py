@@ -7,7 +7,7 @@ A step is one forward call of the workload's layer (every kernel of the call) on
 already resident in HBM. The default workload is the ViT-B-width BLAST layer (768x768, b=16,
 r=96, T=6304, bf16). Prints ONE JSON line on stdout. `--sweep` additionally measures every
 configuration at every T against the same-shape dense GEMM and writes the table to
-gpurun_out/sweep.json (and to stderr).
+sweep.json in the results folder (OUT_DIR below) and to stderr.
 
 Static factors are re-laid out once before the timed region (the paper's offline weight
 re-layout); the timed call receives the packed factors.
@@ -21,6 +21,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+OUT_DIR = "gpurun_out"          # where the tables of --sweep and --table3 are written
 sys.path.insert(0, ROOT)
 
 import numpy as np  # noqa: E402
@@ -310,15 +311,15 @@ def run_sweep(steps, warmup, only=None):
             del layer, Yd
         del W
         torch.cuda.empty_cache()
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "sweep.json"), "w") as f:
+    os.makedirs(os.path.join(ROOT, OUT_DIR), exist_ok=True)
+    with open(os.path.join(ROOT, OUT_DIR, "sweep.json"), "w") as f:
         json.dump(rows, f, indent=1)
     return rows
 
 
 def run_table3(steps, warmup, scale=1):
     """Every layer shape of the paper's Table 3 (Appendix, Layer Details) with every method, against the
-    same-shape dense GEMM; rows go to gpurun_out/table3.json and to stderr."""
+    same-shape dense GEMM; rows go to table3.json in the results folder and to stderr."""
     import torch
     from paper_2512_20861_amd import binding as B
     rows = []
@@ -347,8 +348,8 @@ def run_table3(steps, warmup, scale=1):
             del layer
         del W, X, Yd
         torch.cuda.empty_cache()
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "table3.json" if scale == 1 else f"table3_x{scale}.json"), "w") as f:
+    os.makedirs(os.path.join(ROOT, OUT_DIR), exist_ok=True)
+    with open(os.path.join(ROOT, OUT_DIR, "table3.json" if scale == 1 else f"table3_x{scale}.json"), "w") as f:
         json.dump(rows, f, indent=1)
     return rows
 
