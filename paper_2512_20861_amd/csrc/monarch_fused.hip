@@ -285,6 +285,7 @@ bool monarch_fused_supported(int64_t T, int n_in, int n_out, int b1, int b2, int
     const int64_t w2 = (int64_t)b1 * rp;
     if (rp % 16 || p % 32 || w2 % 32 || p > 32 * MF_KC || w2 > 32 * MF_KC || n_in > 8192 || n_out > (1 << 22)) return false;   // a tile's contraction index fits one register buffer
     if ((T + MF_TT - 1) / MF_TT * b2 * 8 >= (1ll << 31)) return false;     // workgroups (at most 8 output ranges per block)
+    if (w2 * b2 * p >= (1ll << 30)) return false;                           // byte offsets into the first factor are 32-bit
     int jsplit, qt;
     choose_ranges(T, b2, q, jsplit, qt);
     return lds_bytes(n_in, (int)w2, qt) <= 160 * 1024;
