@@ -85,40 +85,52 @@ __global__ __launch_bounds__(256) void copy_kernel(const bf16_t* __restrict__ sr
 }
 
 // Stand-alone coupling for FEW tokens: A[t][i][rho] = sum_j S[i][j][rho] * Z[t][j][rho] from the
-// canonical S[b][b][r] (rank index contiguous). One thread per (token, output block, 8 rank indices):
-// 2 b independent 16-byte loads (all in flight at once), one 16-byte store; consecutive lanes take
-// consecutive groups of 8 rank indices, so a wavefront reads and writes contiguous kilobytes.
+// canonical S[b][b][r] (rank index contiguous). One thread per (token, output block, PAIR of rank
+// indices): 2 b independent 4-byte loads (all in flight at once), one 4-byte store; consecutive lanes
+// take consecutive pairs, so a wavefront reads and writes contiguous runs. The fine grain is for
+// parallelism: with one token the whole of S (b b r elements) is read once, and 8 rank indices per
+// thread left it to 5 workgroups (8 us); pairs spread it over 20. B > 0: compile-time block count.
+template <int B>
 __global__ __launch_bounds__(256) void coupling_small_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restrict__ S,
-                                                             bf16_t* __restrict__ A, int64_t total, int b, int r8) {
+                                                             bf16_t* __restrict__ A, int64_t total, int b_rt, int r2) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
-    const int c = (int)(e % r8);
-    const int i = (int)((e / r8) % b);
-    const int64_t t = e / ((int64_t)r8 * b);
-    const int r = r8 * 8;
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 16
-    for (int j = 0; j < b; ++j) {
-        const uint4 zv = *(const uint4*)(Z + (t * b + j) * r + c * 8);
-        const uint4 sv = *(const uint4*)(S + ((int64_t)i * b + j) * r + c * 8);
-        const uint32_t zw[4] = {zv.x, zv.y, zv.z, zv.w}, sw[4] = {sv.x, sv.y, sv.z, sv.w};
+    const int b = B > 0 ? B : b_rt;
+    const int c = (int)(e % r2);
+    const int i = (int)((e / r2) % b);
+    const int64_t t = e / ((int64_t)r2 * b);
+    const uint32_t* z = (const uint32_t*)Z + t * b * r2 + c;          // Z[t][0][2c], stride r2 words per block
+    const uint32_t* sp = (const uint32_t*)S + (int64_t)i * b * r2 + c;   // S[i][0][2c]
+    float acc0 = 0.f, acc1 = 0.f;
+    if (B > 0) {
+        uint32_t zv[B > 0 ? B : 1], sv[B > 0 ? B : 1];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            acc[2 * k] = fmaf(__uint_as_float(sw[k] << 16), __uint_as_float(zw[k] << 16), acc[2 * k]);
-            acc[2 * k + 1] = fmaf(__uint_as_float(sw[k] & 0xFFFF0000u), __uint_as_float(zw[k] & 0xFFFF0000u), acc[2 * k + 1]);
+        for (int j = 0; j < B; ++j) { zv[j] = z[(int64_t)j * r2]; sv[j] = sp[(int64_t)j * r2]; }
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            acc0 = fmaf(__uint_as_float(sv[j] << 16), __uint_as_float(zv[j] << 16), acc0);
+            acc1 = fmaf(__uint_as_float(sv[j] & 0xFFFF0000u), __uint_as_float(zv[j] & 0xFFFF0000u), acc1);
+        }
+    } else {
+        for (int j = 0; j < b; ++j) {
+            const uint32_t zw = z[(int64_t)j * r2], sw = sp[(int64_t)j * r2];
+            acc0 = fmaf(__uint_as_float(sw << 16), __uint_as_float(zw << 16), acc0);
+            acc1 = fmaf(__uint_as_float(sw & 0xFFFF0000u), __uint_as_float(zw & 0xFFFF0000u), acc1);
         }
     }
-    *(uint4*)(A + (t * b + i) * r + c * 8) =
-        make_uint4(pack2_bf16(acc[0], acc[1]), pack2_bf16(acc[2], acc[3]), pack2_bf16(acc[4], acc[5]), pack2_bf16(acc[6], acc[7]));
+    ((uint32_t*)A)[(t * b + i) * r2 + c] = pack2_bf16(acc0, acc1);
 }
 
 }  // namespace
 
 hipError_t launch_coupling_small(const void* Z, const void* S, void* A, int64_t T, int b, int r, hipStream_t s) {
-    const int64_t total = T * b * (r / 8);              // r is a multiple of 8
+    const int64_t total = T * b * (r / 2);              // r is a multiple of 8
     if (total <= 0) return hipSuccess;
-    hipLaunchKernelGGL(coupling_small_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       (const bf16_t*)Z, (const bf16_t*)S, (bf16_t*)A, total, b, r / 8);
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (b == 16)
+        hipLaunchKernelGGL(coupling_small_kernel<16>, grid, dim3(256), 0, s, (const bf16_t*)Z, (const bf16_t*)S, (bf16_t*)A, total, b, r / 2);
+    else
+        hipLaunchKernelGGL(coupling_small_kernel<0>, grid, dim3(256), 0, s, (const bf16_t*)Z, (const bf16_t*)S, (bf16_t*)A, total, b, r / 2);
     return hipGetLastError();
 }
 
