@@ -119,12 +119,11 @@ blr_status run_pack(const void* U, const void* S, const void* V, void* packed, i
 // Is this call (Monarch with b1 x b2 blocks of rank rp; low-rank is 1 x 1) served by the single kernel
 // that keeps the intermediate on chip? It can be when the shape fits and the call asks for neither
 // the portable kernels, nor a single stage, nor a blocked input. It is by default where it was
-// measured faster than the two GEMMs (narrow layers of the ViT-B / GPT2-S kind, 1.1-1.35x): two
-// workgroups fit a compute unit (half of LDS each), not more tokens than one to two rounds of
-// 32-token tiles, and, when the output order interleaves the blocks (2-byte stores at a stride), no more
-// than 1024 tokens.
+// measured faster than the two GEMMs (narrow layers of the ViT-B / GPT2-S kind, 1.1-1.4x; within
+// +-10 % for the lowest ranks at token counts that leave a partial round of workgroups): two
+// workgroups fit a compute unit (half of LDS each) and not more tokens than one to two rounds of
+// 32-token tiles.
 constexpr int64_t kFusedMonarchMaxTokens = 4096;
-constexpr int64_t kFusedMonarchMaxTokensInterleaved = 1024;
 constexpr int kFusedMonarchMaxLds = 80 * 1024;
 bool monarch_fused_possible(int64_t T, int n_in, int n_out, int b1, int b2, int rp, blr_dtype dt, unsigned flags) {
     if (dt != BLR_BF16 || (flags & (BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_MONARCH_IN_BLOCKED | BLR_MONARCH_TWO_KERNELS))) return false;
@@ -133,9 +132,7 @@ bool monarch_fused_possible(int64_t T, int n_in, int n_out, int b1, int b2, int 
 bool monarch_takes_fused(int64_t T, int n_in, int n_out, int b1, int b2, int rp, blr_dtype dt, unsigned flags) {
     if (!monarch_fused_possible(T, n_in, n_out, b1, b2, rp, dt, flags)) return false;
     if (flags & BLR_MONARCH_FUSED) return true;
-    const bool contiguous = (flags & BLR_MONARCH_OUT_BLOCKED) || b2 == 1;
-    return T > 32 && T <= (contiguous ? kFusedMonarchMaxTokens : kFusedMonarchMaxTokensInterleaved) &&
-           monarch_fused_lds_bytes(T, n_in, n_out, b1, b2, rp) <= kFusedMonarchMaxLds;
+    return T > 32 && T <= kFusedMonarchMaxTokens && monarch_fused_lds_bytes(T, n_in, n_out, b1, b2, rp) <= kFusedMonarchMaxLds;
 }
 
 // Both Monarch entry points: b1 input blocks, b2 output blocks, per-block rank rp.
