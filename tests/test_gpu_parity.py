@@ -363,3 +363,17 @@ def test_single_kernel_is_unsupported_where_its_shape_rules_fail():
     X = bi.activations(8, 256, "bf16", seed=4)
     with pytest.raises(RuntimeError):
         gu.run_monarch(X, lay, B.MONARCH_FUSED)
+
+
+@pytest.mark.parametrize("T", [4096, 4100])
+def test_monarch_default_dispatch_around_the_token_limit_of_the_single_kernel(T):
+    """768 -> 2304, 4 blocks, r = 192 (the GPT2-S attention projection of the paper's layer table): the
+    default call (single kernel up to 4096 tokens, two GEMMs above) against the oracle on sampled rows."""
+    gu = _gu()
+    B = gu.B
+    lay = bi.monarch_layer(768, 2304, 4, 192, "bf16", seed=77)
+    X = bi.activations(T, 768, "bf16", seed=78)
+    Y = gu.to_f64(gu.run_monarch(X, lay))
+    rows = np.unique(np.concatenate([np.arange(0, 40), np.arange(T - 40, T), np.random.default_rng(5).integers(0, T, 200)]))
+    Yref = oracle.monarch_forward(X.f64[rows], lay.R.f64, lay.L.f64)
+    assert gu.rel_err(Y[rows], Yref) <= gu.TOL["bf16"]
