@@ -17,9 +17,10 @@
 //            (blocked order, or a single block), element-wise for the interleaved order.
 // Both products run on v_mfma_f32_16x16x32_bf16 with the weight rows as FIRST operand, straight from
 // global memory (a fragment is one 16-byte load per lane, four lanes per 64 contiguous bytes of a weight
-// row, permuted across lanes into the MFMA's order; every fragment serves both 16-token halves), the token operand from LDS. Accumulator
-// element e of a lane is output column 4 (lane / 16) + e of token lane % 16. Wavefronts split the
-// 16-wide column tiles of each phase and fetch the weights three tiles ahead of the MFMAs that use them.
+// row, permuted across lanes into the MFMA's order; every fragment serves both 16-token halves), the
+// token operand from LDS. Accumulator element e of a lane is output column 4 (lane / 16) + e of token
+// lane % 16. Wavefronts split the 16-wide column tiles of each phase and fetch the weights three tiles
+// ahead of the MFMAs that use them.
 #include "blr_common.h"
 
 namespace blr {
@@ -31,7 +32,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // (arrays of HIP'
 
 constexpr int MF_TT = 32;          // tokens per workgroup
 constexpr int MF_MAX_WAVES = 8;    // wavefronts per workgroup: 8 when the launch has at most one workgroup per compute unit, else 4
-constexpr int MF_KC = 8;           // k32 steps per group of weight fragments
+constexpr int MF_KC = 8;           // k32 steps of a tile at most (one register buffer holds a tile's weight fragments)
 
 struct MonarchFusedArgs {
     const bf16_t *X, *R, *L;
@@ -57,7 +58,8 @@ __global__ __launch_bounds__(64 * MF_MAX_WAVES) void monarch_fused_kernel(Monarc
     // Work items in the order (token tile, output range, block k) with k fastest, each XCD on a contiguous
     // range of them: the b2 workgroups that interleave their outputs into the same cache lines then
     // share an L2, where their partial-line writes merge (on different XCDs every partial line goes to
-    // memory on its own: measured +2 us at 25 token tiles, where the old (tile, k) grid put them apart).
+    // memory on its own: +2 us measured with a 2-D grid of token tiles x blocks at 25 token tiles, which
+    // deals the blocks of one token tile to different XCDs).
     const int lg = xcd_contiguous(blockIdx.x, a.nblk);
     const int k = lg % a.b2;
     const int j0 = ((lg / a.b2) % a.jsplit) * a.qt;
