@@ -16,16 +16,28 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every kernel translation unit and link the C-ABI shared library in-tree."""
-    cmd = [HIPCC] + FLAGS + sources() + ["-o", LIB]
+def _run(cmd):
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + err)
+    return err
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every kernel translation unit (in parallel) and link the C-ABI shared library in-tree."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    srcs = sources()
+    with tempfile.TemporaryDirectory(prefix="blr_build_") as tmp:
+        objs = [os.path.join(tmp, os.path.basename(src) + ".o") for src in srcs]
+        compile_flags = [f for f in FLAGS if f != "-shared"]
+        with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+            errs = list(pool.map(lambda so: _run([HIPCC] + compile_flags + ["-c", so[0], "-o", so[1]]), zip(srcs, objs)))
+        errs.append(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB]))
+    if verbose and any(e.strip() for e in errs):
+        print("\n".join(e for e in errs if e.strip()))
     return LIB
 
 
