@@ -417,7 +417,14 @@ def run_chain(args, op):
                                 + (" (blocked output)" if fl & OB else "") + (" (blocked input)" if fl & IB else ""),
                       "calls_per_step": n_calls, "ms": t, "stage_ms": st, "dense_ms": td,
                       "frac_mfma": fl_ops / (t * 1e-3) / rf.MFMA_BF16_PEAK})
-        blr_ms += n_calls * t
+        grp = {"q": "qkv", "gate": "gu"}.get(name) if chain.grouped else None
+        if grp:     # the chain runs these `count` linears as one call: that call, timed alone on the chain's buffers
+            g = chain.groups[0][grp]
+            tg = time_graph(lambda: B.prepared(*g.call_args(chain.n, chain.qkv if grp == "qkv" else chain.gu, chain.ws)), 50, 5)
+            parts[-1].update({"grouped_call_of": count, "grouped_call_ms": tg})
+            blr_ms += c["n_layers"] * tg
+        else:
+            blr_ms += n_calls * t
         dense_ms += n_calls * td
         flops += n_calls * fl_ops
         worst = n_calls * (max(st) if st else t)

@@ -211,6 +211,13 @@ blr_status blr_residual_add_rmsnorm(void* H, const void* Y, void* N, int64_t T, 
 blr_status blr_sum3_scaled(const void* Q, const void* K, const void* V, void* A, int64_t T, int d, float scale,
                            blr_dtype dt, blr_stream stream);
 blr_status blr_silu_mul(const void* G, const void* U, void* M, int64_t T, int d, blr_dtype dt, blr_stream stream);
+/* The same two operations on inputs whose rows are `ld >= d` elements apart (column slices of a wider
+ * tensor: the outputs of several layers that one call computed side by side, see the general Monarch
+ * form with b_out = layers * nblocks). The output has contiguous rows of d and must not alias an input. */
+blr_status blr_sum3_scaled_ld(const void* Q, const void* K, const void* V, void* A, int64_t T, int d, int64_t ld,
+                              float scale, blr_dtype dt, blr_stream stream);
+blr_status blr_silu_mul_ld(const void* G, const void* U, void* M, int64_t T, int d, int64_t ld,
+                           blr_dtype dt, blr_stream stream);
 
 const char* blr_status_string(blr_status s);
 

@@ -30,10 +30,10 @@ EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forw
            "blr_blast_pack", "blr_dense_reference_forward",
            "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul",
            "blr_monarch_permute_first_factor", "blr_lowrank_workspace_bytes", "blr_lowrank_forward",
-           "blr_monarch_rect_workspace_bytes", "blr_monarch_rect_forward")
+           "blr_monarch_rect_workspace_bytes", "blr_monarch_rect_forward", "blr_sum3_scaled_ld", "blr_silu_mul_ld")
 # entry points that enqueue work and return a status: the ones prepared() can record
 _LAUNCHERS = ("blr_monarch_forward", "blr_blast_forward", "blr_dense_reference_forward", "blr_lowrank_forward", "blr_monarch_rect_forward",
-              "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul")
+              "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul", "blr_sum3_scaled_ld", "blr_silu_mul_ld")
 
 _lib = None
 _last_workspace = None     # the workspace the latest forward call ran with (kept alive for prepared())
@@ -88,6 +88,10 @@ def lib() -> ctypes.CDLL:
         L.blr_sum3_scaled.argtypes = [vp, vp, vp, vp, i64, ci, cf, ci, vp]
         L.blr_silu_mul.restype = ci
         L.blr_silu_mul.argtypes = [vp, vp, vp, i64, ci, ci, vp]
+        L.blr_sum3_scaled_ld.restype = ci
+        L.blr_sum3_scaled_ld.argtypes = [vp, vp, vp, vp, i64, ci, i64, cf, ci, vp]
+        L.blr_silu_mul_ld.restype = ci
+        L.blr_silu_mul_ld.argtypes = [vp, vp, vp, i64, ci, i64, ci, vp]
         _lib = L
     return _lib
 
@@ -109,6 +113,13 @@ def _ptr(t):
         return None
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("tensors must be contiguous GPU tensors")
+    return t.data_ptr()
+
+
+def _ptr_rows(t):
+    """Pointer of a GPU tensor [T][d] whose rows may be further apart than d (a column slice)."""
+    if not t.is_cuda or t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("expected a 2-D GPU tensor with contiguous rows")
     return t.data_ptr()
 
 
@@ -283,14 +294,23 @@ def residual_add_rmsnorm(H, Y, N=None, eps=1e-6, stream=None):
 
 
 def sum3_scaled(Q, K, V, A, scale, stream=None):
-    """A <- (Q + K + V) * scale."""
+    """A <- (Q + K + V) * scale. Q, K, V may be column slices of one wider tensor (equal row strides)."""
     T, d = Q.shape
+    if Q.stride(0) != d:
+        assert Q.stride(0) == K.stride(0) == V.stride(0) and Q.stride(1) == 1 and A.is_contiguous()
+        _check(lib().blr_sum3_scaled_ld(_ptr_rows(Q), _ptr_rows(K), _ptr_rows(V), _ptr(A), T, d, Q.stride(0), scale, _dt(Q), _stream(stream)),
+               "blr_sum3_scaled_ld")
+        return A
     _check(lib().blr_sum3_scaled(_ptr(Q), _ptr(K), _ptr(V), _ptr(A), T, d, scale, _dt(Q), _stream(stream)), "blr_sum3_scaled")
     return A
 
 
 def silu_mul(G, U, M, stream=None):
-    """M <- silu(G) * U."""
+    """M <- silu(G) * U. G, U may be column slices of one wider tensor (equal row strides)."""
     T, d = G.shape
+    if G.stride(0) != d:
+        assert G.stride(0) == U.stride(0) and G.stride(1) == 1 and M.is_contiguous()
+        _check(lib().blr_silu_mul_ld(_ptr_rows(G), _ptr_rows(U), _ptr(M), T, d, G.stride(0), _dt(G), _stream(stream)), "blr_silu_mul_ld")
+        return M
     _check(lib().blr_silu_mul(_ptr(G), _ptr(U), _ptr(M), T, d, _dt(G), _stream(stream)), "blr_silu_mul")
     return M

@@ -10,6 +10,10 @@ The residual addition and the following normalisation are one kernel. In an all-
 linears whose output only meets elementwise steps before the next linear (q, k, v -> o; gate, up ->
 down) write the BLOCKED output order and their consumer reads it with a first factor re-ordered
 once at set-up (the paper's optimisation 3), so no interleaving permutation is ever executed there.
+There the linears that share an input (q, k, v; gate, up) also run as ONE call each: n Monarch layers of
+equal shape are one general Monarch layer with n * nblocks output blocks once the rows of their
+first factors are interleaved (done once at set-up), which turns 2 n launch-bound GEMMs into two
+larger ones; their outputs lie side by side in one tensor and the glue reads them as column slices.
 """
 from __future__ import annotations
 
@@ -67,11 +71,35 @@ class _Linear:
         return (B.blast_forward, X, self.U, self.S, self.V, Y, self.b, self.r, self.flags, ws)
 
 
+class _MonarchGroup:
+    """n Monarch linears of equal shape that read the same input, as one general Monarch layer:
+    R_g[l][rho * (n b) + layer * b + k] = R_layer[l][rho * b + k],  L_g[layer * b + k] = L_layer[k].
+    Output [T][n * n_out], layer by layer, each in the blocked order."""
+
+    def __init__(self, members):
+        m0 = members[0]
+        assert all(m.op == "monarch" and (m.n_in, m.n_out, m.r, m.nb, m.dt) == (m0.n_in, m0.n_out, m0.r, m0.nb, m0.dt) for m in members)
+        self.n, self.n_in, self.n_out, self.nb, self.dt = len(members), m0.n_in, m0.n_out, m0.nb, m0.dt
+        self.rp = m0.r // m0.nb
+        b, p = self.nb, m0.n_in // m0.nb
+        # [layer][l][rho][k][a] -> [l][rho][layer][k][a]
+        R = torch.stack([m.R.reshape(b, self.rp, b, p) for m in members], dim=0)
+        self.R = R.permute(1, 2, 0, 3, 4).contiguous().reshape(b, self.rp * self.n * b, p)
+        self.L = torch.cat([m.L for m in members], dim=0).contiguous()
+        self.flags = B.MONARCH_OUT_BLOCKED
+
+    def workspace_bytes(self, T):
+        return B.monarch_rect_workspace_bytes(T, self.n_in, self.n * self.n_out, self.nb, self.n * self.nb, self.rp, self.dt)
+
+    def call_args(self, X, Y, ws):
+        return (B.monarch_rect_forward, X, self.R, self.L, Y, self.nb, self.n * self.nb, self.rp, self.flags, ws)
+
+
 class DeviceChain:
     OUT_BLOCKED = ("q", "k", "v", "gate", "up")          # only elementwise steps between these and their consumer
     IN_BLOCKED = ("o", "down")
 
-    def __init__(self, host_layers, T, eps=1e-6, blocked_chaining=True):
+    def __init__(self, host_layers, T, eps=1e-6, blocked_chaining=True, grouped=True):
         first = host_layers[0]
         self.T, self.eps = T, eps
         self.hidden, self.mlp = first["q"].n_in, first["gate"].n_out
@@ -83,9 +111,21 @@ class DeviceChain:
         td = torch.bfloat16 if first["q"].dtype == "bf16" else torch.float32
         new = lambda d: torch.empty((T, d), dtype=td, device="cuda")
         self.h, self.n = new(self.hidden), new(self.hidden)
-        self.q, self.k, self.v, self.a, self.o, self.dn = (new(self.hidden) for _ in range(6))
-        self.g, self.u = new(self.mlp), new(self.mlp)
-        need = max(lin.workspace_bytes(T) for layer in self.layers for lin in layer.values())
+        self.a, self.o, self.dn = (new(self.hidden) for _ in range(3))
+        # grouped calls (all-Monarch chain with blocked chaining): q, k, v and gate, up are column slices
+        self.grouped = bool(grouped and self.blocked)
+        if self.grouped:
+            self.qkv, self.gu, self.m = new(3 * self.hidden), new(2 * self.mlp), new(self.mlp)
+            self.q, self.k, self.v = (self.qkv[:, i * self.hidden:(i + 1) * self.hidden] for i in range(3))
+            self.g, self.u = self.gu[:, :self.mlp], self.gu[:, self.mlp:]
+            self.groups = [{"qkv": _MonarchGroup([L[n] for n in "qkv"]), "gu": _MonarchGroup([L["gate"], L["up"]])} for L in self.layers]
+        else:
+            self.q, self.k, self.v = (new(self.hidden) for _ in range(3))
+            self.g, self.u = new(self.mlp), new(self.mlp)
+            self.m = self.g                              # the SiLU gate is applied in place
+            self.groups = []
+        need = max([lin.workspace_bytes(T) for layer in self.layers for lin in layer.values()] +
+                   [grp.workspace_bytes(T) for layer in self.groups for grp in layer.values()])
         self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
 
     def call_list(self):
@@ -93,16 +133,22 @@ class DeviceChain:
         c = [("rmsnorm", (B.rmsnorm, self.h, self.n, self.eps))]
         last = len(self.layers) - 1
         for li, L in enumerate(self.layers):
-            c.append((f"{li}.q", L["q"].call_args(self.n, self.q, self.ws)))
-            c.append((f"{li}.k", L["k"].call_args(self.n, self.k, self.ws)))
-            c.append((f"{li}.v", L["v"].call_args(self.n, self.v, self.ws)))
+            if self.grouped:
+                c.append((f"{li}.qkv", self.groups[li]["qkv"].call_args(self.n, self.qkv, self.ws)))
+            else:
+                c.append((f"{li}.q", L["q"].call_args(self.n, self.q, self.ws)))
+                c.append((f"{li}.k", L["k"].call_args(self.n, self.k, self.ws)))
+                c.append((f"{li}.v", L["v"].call_args(self.n, self.v, self.ws)))
             c.append((f"{li}.a", (B.sum3_scaled, self.q, self.k, self.v, self.a, 1.0 / math.sqrt(3.0))))
             c.append((f"{li}.o", L["o"].call_args(self.a, self.o, self.ws)))
             c.append((f"{li}.h1", (B.residual_add_rmsnorm, self.h, self.o, self.n, self.eps)))
-            c.append((f"{li}.gate", L["gate"].call_args(self.n, self.g, self.ws)))
-            c.append((f"{li}.up", L["up"].call_args(self.n, self.u, self.ws)))
-            c.append((f"{li}.m", (B.silu_mul, self.g, self.u, self.g)))
-            c.append((f"{li}.down", L["down"].call_args(self.g, self.dn, self.ws)))
+            if self.grouped:
+                c.append((f"{li}.gu", self.groups[li]["gu"].call_args(self.n, self.gu, self.ws)))
+            else:
+                c.append((f"{li}.gate", L["gate"].call_args(self.n, self.g, self.ws)))
+                c.append((f"{li}.up", L["up"].call_args(self.n, self.u, self.ws)))
+            c.append((f"{li}.m", (B.silu_mul, self.g, self.u, self.m)))
+            c.append((f"{li}.down", L["down"].call_args(self.m, self.dn, self.ws)))
             c.append((f"{li}.h2", (B.residual_add_rmsnorm, self.h, self.dn, None if li == last else self.n, self.eps)))
         return c
 
@@ -112,7 +158,8 @@ class DeviceChain:
 
     def forward(self, x0, record=False):
         """Run the chain on x0 [T][hidden] (device tensor); returns h. With record=True also returns, per
-        call label, a copy of the tensor that call wrote and of the tensor it read."""
+        call label, a copy of the tensor that call wrote and of the tensor it read (a grouped call is
+        recorded under the labels of its member linears, each with its own slice of the output)."""
         self.h.copy_(x0)
         taps = {}
         for label, args in self.call_list():
@@ -120,6 +167,12 @@ class DeviceChain:
                 src = args[1].clone()
             args[0](*args[1:])
             if record:
+                if args[0] is B.monarch_rect_forward:
+                    li, grp = label.split(".")
+                    for name, part in zip(("q", "k", "v") if grp == "qkv" else ("gate", "up"),
+                                          (self.q, self.k, self.v) if grp == "qkv" else (self.g, self.u)):
+                        taps[f"{li}.{name}"] = (src, part.clone())
+                    continue
                 out = {B.rmsnorm: lambda a: a[2], B.sum3_scaled: lambda a: a[4], B.silu_mul: lambda a: a[3],
                        B.residual_add_rmsnorm: lambda a: a[1], B.monarch_forward: lambda a: a[4],
                        B.blast_forward: lambda a: a[5]}[args[0]](args)

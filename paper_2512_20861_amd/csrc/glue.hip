@@ -112,6 +112,34 @@ __global__ __launch_bounds__(256) void elementwise_kernel(const TS* A, const TS*
     }
 }
 
+// The same operations on inputs whose rows are `ld` elements apart (column slices of a wider tensor, e.g.
+// the outputs of several layers computed by one call side by side); the output rows are contiguous.
+// One workgroup row per token row (grid-stride over rows), no index divisions.
+template <typename TS, int OP, bool VEC>
+__global__ __launch_bounds__(256) void elementwise_rows_kernel(const TS* A, const TS* B, const TS* C, TS* O, int64_t T, int d, int64_t ld, float scale) {
+    using V = Vec<TS>;
+    for (int64_t t = blockIdx.y; t < T; t += gridDim.y) {
+        const TS *a_row = A + t * ld, *b_row = B + t * ld, *c_row = OP == 0 ? C + t * ld : nullptr;
+        TS* o_row = O + t * (int64_t)d;
+        if (VEC) {
+            for (int v = blockIdx.x * 256 + threadIdx.x; v * V::N < d; v += gridDim.x * 256) {
+                float a[V::N], b[V::N], c[V::N];
+                V::load(a_row + v * V::N, a);
+                V::load(b_row + v * V::N, b);
+                if (OP == 0) V::load(c_row + v * V::N, c);
+#pragma unroll
+                for (int i = 0; i < V::N; ++i) a[i] = OP == 0 ? (a[i] + b[i] + c[i]) * scale : silu(a[i]) * b[i];
+                V::store(o_row + v * V::N, a);
+            }
+        } else {
+            for (int e = blockIdx.x * 256 + threadIdx.x; e < d; e += gridDim.x * 256) {
+                const float a = V::load1(a_row + e), b = V::load1(b_row + e);
+                V::store1(o_row + e, OP == 0 ? (a + b + V::load1(c_row + e)) * scale : silu(a) * b);
+            }
+        }
+    }
+}
+
 inline bool al16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 template <typename TS>
@@ -130,6 +158,18 @@ hipError_t run_elementwise(const void* A, const void* B, const void* C, void* O,
     if (blocks > 256 * 16) blocks = 256 * 16;           // grid-stride beyond 16 workgroups per compute unit
     if (vec) hipLaunchKernelGGL((elementwise_kernel<TS, OP, true>), dim3((unsigned)blocks), dim3(256), 0, s, (const TS*)A, (const TS*)B, (const TS*)C, (TS*)O, n, scale);
     else hipLaunchKernelGGL((elementwise_kernel<TS, OP, false>), dim3((unsigned)blocks), dim3(256), 0, s, (const TS*)A, (const TS*)B, (const TS*)C, (TS*)O, n, scale);
+    return hipGetLastError();
+}
+
+template <typename TS, int OP>
+hipError_t run_elementwise_rows(const void* A, const void* B, const void* C, void* O, int64_t T, int d, int64_t ld, float scale, hipStream_t s) {
+    const bool vec = d % Vec<TS>::N == 0 && ld % Vec<TS>::N == 0 && al16(A) && al16(B) && (OP != 0 || al16(C)) && al16(O);
+    const int items = vec ? d / Vec<TS>::N : d;
+    int bx = (items + 255) / 256;
+    if (bx > 64) bx = 64;
+    const dim3 grid((unsigned)bx, (unsigned)(T < 65535 ? T : 65535));
+    if (vec) hipLaunchKernelGGL((elementwise_rows_kernel<TS, OP, true>), grid, dim3(256), 0, s, (const TS*)A, (const TS*)B, (const TS*)C, (TS*)O, T, d, ld, scale);
+    else hipLaunchKernelGGL((elementwise_rows_kernel<TS, OP, false>), grid, dim3(256), 0, s, (const TS*)A, (const TS*)B, (const TS*)C, (TS*)O, T, d, ld, scale);
     return hipGetLastError();
 }
 
@@ -174,6 +214,23 @@ blr_status blr_silu_mul(const void* G, const void* U, void* M, int64_t T, int d,
     if (!G || !U || !M) return BLR_ERR_INVALID_ARG;
     return status_of(dt == BLR_BF16 ? run_elementwise<bf16_t, 1>(G, U, nullptr, M, T * d, 1.f, (hipStream_t)stream)
                                     : run_elementwise<float, 1>(G, U, nullptr, M, T * d, 1.f, (hipStream_t)stream));
+}
+
+blr_status blr_sum3_scaled_ld(const void* Q, const void* K, const void* V, void* A, int64_t T, int d, int64_t ld, float scale,
+                              blr_dtype dt, blr_stream stream) {
+    if (!dims_ok(T, d, dt) || ld < d) return BLR_ERR_INVALID_ARG;
+    if (T == 0) return BLR_OK;
+    if (!Q || !K || !V || !A) return BLR_ERR_INVALID_ARG;
+    return status_of(dt == BLR_BF16 ? run_elementwise_rows<bf16_t, 0>(Q, K, V, A, T, d, ld, scale, (hipStream_t)stream)
+                                    : run_elementwise_rows<float, 0>(Q, K, V, A, T, d, ld, scale, (hipStream_t)stream));
+}
+
+blr_status blr_silu_mul_ld(const void* G, const void* U, void* M, int64_t T, int d, int64_t ld, blr_dtype dt, blr_stream stream) {
+    if (!dims_ok(T, d, dt) || ld < d) return BLR_ERR_INVALID_ARG;
+    if (T == 0) return BLR_OK;
+    if (!G || !U || !M) return BLR_ERR_INVALID_ARG;
+    return status_of(dt == BLR_BF16 ? run_elementwise_rows<bf16_t, 1>(G, U, nullptr, M, T, d, ld, 1.f, (hipStream_t)stream)
+                                    : run_elementwise_rows<float, 1>(G, U, nullptr, M, T, d, ld, 1.f, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -239,6 +239,7 @@ def test_python_wrappers_marshal_every_entry_point(monkeypatch):
 
     monkeypatch.setattr(B, "_lib", Recorder())
     monkeypatch.setattr(B, "_ptr", lambda t: None if t is None else t.data_ptr())
+    monkeypatch.setattr(B, "_ptr_rows", lambda t: t.data_ptr())
     monkeypatch.setattr(B, "_stream", lambda s: None)
     bf = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16)
     ws = torch.zeros(1 << 22, dtype=torch.uint8)
@@ -255,4 +256,7 @@ def test_python_wrappers_marshal_every_entry_point(monkeypatch):
     B.residual_add_rmsnorm(bf(T, n), bf(T, n), None)
     B.sum3_scaled(bf(T, n), bf(T, n), bf(T, n), bf(T, n), 0.5)
     B.silu_mul(bf(T, n), bf(T, n), bf(T, n))
+    wide = bf(T, 3 * n)                                    # column slices of a wider tensor take the strided entry points
+    B.sum3_scaled(wide[:, :n], wide[:, n:2 * n], wide[:, 2 * n:], bf(T, n), 0.5)
+    B.silu_mul(wide[:, :n], wide[:, n:2 * n], bf(T, n))
     assert set(calls) == set(B._LAUNCHERS) | {"blr_blast_pack", "blr_monarch_permute_first_factor"}
