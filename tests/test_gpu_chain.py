@@ -72,6 +72,31 @@ def test_glue_kernels(T, d, dtype):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T,d", [(37, 2048), (3, 100), (70000, 8), (5, 8200)])
+def test_glue_kernels_on_column_slices(T, d, dtype):
+    """The scaled sum and the SiLU gate with their inputs taken as column slices of one wider tensor."""
+    gu = _gu()
+    B = gu.B
+    W = bi.gaussian(9, 111, (T, 3 * d), 1.3, dtype)
+    Wd = gu.to_dev(W)
+    q, k, v = (Wd[:, i * d:(i + 1) * d] for i in range(3))
+    A, M = gu.empty_out(T, d, dtype), gu.empty_out(T, d, dtype)
+    B.sum3_scaled(q, k, v, A, 0.5)
+    B.silu_mul(q, v, M)
+    torch.cuda.synchronize()
+    w = W.f64
+    assert gu.rel_err(gu.to_f64(A), (w[:, :d] + w[:, d:2 * d] + w[:, 2 * d:]) * 0.5) <= gu.TOL[dtype]
+    assert gu.rel_err(gu.to_f64(M), oc.silu(w[:, :d]) * w[:, 2 * d:]) <= (gu.TOL[dtype] if dtype == "bf16" else 1e-5)
+    # the strided form on contiguous inputs (ld = d) is the plain operation
+    Qc, Kc, Vc = (t.contiguous() for t in (q, k, v))
+    A2 = gu.empty_out(T, d, dtype)
+    st = B.lib().blr_sum3_scaled_ld(Qc.data_ptr(), Kc.data_ptr(), Vc.data_ptr(), A2.data_ptr(), T, d, d, 0.5, B.BF16 if dtype == "bf16" else B.F32, None)
+    torch.cuda.synchronize()
+    assert st == B.OK and torch.equal(A2, A)
+    assert B.lib().blr_silu_mul_ld(Qc.data_ptr(), Vc.data_ptr(), A2.data_ptr(), T, d, d - 1, B.BF16 if dtype == "bf16" else B.F32, None) == B.ERR_INVALID_ARG
+
+
 def test_glue_status_codes():
     gu = _gu()
     B = gu.B
