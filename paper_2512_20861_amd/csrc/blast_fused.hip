@@ -25,18 +25,23 @@ constexpr int ZSTR = TN * 32 + 8;            // bytes of one rho row of Zs: TN t
 constexpr int ZS_BYTES = TR * ZSTR;
 static_assert(ZS_BYTES % 16 == 0, "Zs is cleared with 16-byte stores");
 
-// stage 1 of the fused kernel: 128 tokens x 64 ranks per workgroup, 8 wavefronts of 32 x 32
-constexpr int ST_TT = 128;                   // tokens per workgroup
+// stage 1 of the fused kernel: TT tokens x 64 ranks per workgroup, 8 wavefronts; TT = 128: every wavefront
+// computes a 32 x 32 part of the tile; TT = 64 (calls with too few 128-token tiles to fill the chip):
+// wavefronts 0..3 compute, all 8 move the operands and take part in the coupling
 constexpr int ST_BK = 64;                    // k elements per step: operand rows of 128 bytes = 8 pieces of 16 bytes
-constexpr int ST_ROWS = ST_TT + TR;          // operand rows of one stage: X rows, then Vt rows
-constexpr int ST_STAGE = ST_ROWS * ST_BK * 2;
 constexpr int ST_NS = 6;                     // stages in LDS
 constexpr int ST_PD = ST_NS - 1;             // steps of loads in flight
-constexpr int ST_LDS = ST_NS * ST_STAGE > ZS_BYTES ? ST_NS * ST_STAGE : ZS_BYTES;
-static_assert(ST_LDS <= 160 * 1024, "LDS budget");
-static_assert(ST_ROWS % 64 == 0, "every wavefront issues the same number of loads per stage");
-constexpr int ST_LPW = ST_ROWS / 64;         // direct-to-LDS loads per wavefront and stage (8 rows each)
-static_assert(ST_LPW * (ST_PD - 1) < 64, "vmcnt range");
+template <int TT>
+struct StCfg {
+    static constexpr int ROWS = TT + TR;          // operand rows of one stage: X rows, then Vt rows
+    static constexpr int STAGE = ROWS * ST_BK * 2;
+    static constexpr int LDS = ST_NS * STAGE > ZS_BYTES ? ST_NS * STAGE : ZS_BYTES;
+    static constexpr int LPW = ROWS / 64;         // direct-to-LDS loads per wavefront and stage (8 rows each)
+    static_assert(TT == 128 || TT == 64, "token tiles of the fused kernel");
+    static_assert(LDS <= 160 * 1024, "LDS budget");
+    static_assert(ROWS % 64 == 0, "every wavefront issues the same number of loads per stage");
+    static_assert(LPW * (ST_PD - 1) < 64, "vmcnt range");
+};
 
 
 // Coupling of one 64-token x 64-rank tile whose Z values sit in LDS as Zs[rho][t][j] (bf16):
@@ -214,6 +219,7 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
 // block: block j walks chunks floor(j q / 64) .. ceil((j+1) q / 64) - 1, so every X piece is one whole
 // 128-byte line whatever q is. The columns of a boundary chunk that belong to a neighbouring block
 // meet zeros in Va (the chunk-aligned copy of Vt, rows of qp elements), so nothing has to be masked.
+template <int TT>
 __global__ __launch_bounds__(512)
 void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Va,
                           const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
@@ -221,10 +227,13 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;            // token quarter, rank half of this wavefront's 32 x 32
+    using C = StCfg<TT>;
+    constexpr int ST_STAGE = C::STAGE, ST_LPW = C::LPW;
+    const bool computes = TT == 128 || wave < 4;         // uniform: this wavefront owns a 32 x 32 part of the tile
+    const int wm = TT == 128 ? wave >> 1 : (wave >> 1) & 1, wn = wave & 1;   // token part, rank half of this wavefront's 32 x 32
     const int logical = xcd_contiguous(blockIdx.x, nblk);
     const int tile_t = logical / tiles_r, tile_r = logical % tiles_r;
-    const int64_t t0 = (int64_t)tile_t * ST_TT;
+    const int64_t t0 = (int64_t)tile_t * TT;
     const int rho0 = tile_r * TR;
     const int q = n_in / b;
     auto chunk_begin = [&](int j) { return (j * q) >> 6; };
@@ -238,12 +247,12 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
     for (int h = 0; h < ST_LPW; ++h) {
         const int row = 8 * (ST_LPW * wave + h) + (lane >> 3);
         const int piece = (lane & 7) ^ ((row >> 1) & 7);
-        if (row < ST_TT) {
+        if (row < TT) {
             int xr = row;
             if (t0 + xr > T - 1) xr = (int)(T - 1 - t0);    // rows past the end re-read the last row; never stored
             off[h] = (xr * n_in + piece * 8) * 2;           // bytes from the tile's first X row
         } else {
-            int vr = rho0 + row - ST_TT;
+            int vr = rho0 + row - TT;
             if (vr > r - 1) vr = r - 1;
             off[h] = (vr * qp + piece * 8) * 2;             // bytes from Va[j]
         }
@@ -258,7 +267,7 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
         const unsigned char* vc = vs + fj * v_block + (size_t)fk * (ST_BK * 2);
 #pragma unroll
         for (int h = 0; h < ST_LPW; ++h) {
-            const bool isx = 8 * (ST_LPW * wave + h) < ST_TT;              // uniform
+            const bool isx = 8 * (ST_LPW * wave + h) < TT;                 // uniform
             __builtin_amdgcn_global_load_lds(BLR_GPTR((isx ? xc : vc) + off[h]),
                                              BLR_LPTR(smem + stage_off + (ST_LPW * wave + h) * 1024), 16, 0, 0);
         }
@@ -276,18 +285,22 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
     for (int ks = 0; ks < ST_BK / 16; ++ks) {
         const unsigned sw = (unsigned)(((2 * ks + kg) ^ ((m >> 1) & 7)) * 16);
         fa[ks] = lds0 + (wm * 32 + m) * (ST_BK * 2) + sw;
-        fb[ks] = lds0 + (ST_TT + wn * 32 + m) * (ST_BK * 2) + sw;
+        fb[ks] = lds0 + (TT + wn * 32 + m) * (ST_BK * 2) + sw;
     }
 
     int cstage = 0, istage = ST_PD * ST_STAGE;          // byte offsets of the stage to compute on / to refill
     auto step = [&](f32x16& acc) {
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(ST_LPW * (ST_PD - 1)) : "memory");
         issue(istage);                                  // the stage every wavefront finished reading one step ago
+        const int rstage = cstage;                      // the stage of this step
+        cstage = cstage + ST_STAGE == ST_NS * ST_STAGE ? 0 : cstage + ST_STAGE;
+        istage = istage + ST_STAGE == ST_NS * ST_STAGE ? 0 : istage + ST_STAGE;
+        if (!computes) return;                          // moves operands only
         bf16x8 af[ST_BK / 16], bfr[ST_BK / 16];
 #pragma unroll
         for (int ks = 0; ks < ST_BK / 16; ++ks) {
-            asm volatile("ds_read_b128 %0, %1" : "=v"(af[ks]) : "v"(fa[ks] + cstage) : "memory");
-            asm volatile("ds_read_b128 %0, %1" : "=v"(bfr[ks]) : "v"(fb[ks] + cstage) : "memory");
+            asm volatile("ds_read_b128 %0, %1" : "=v"(af[ks]) : "v"(fa[ks] + rstage) : "memory");
+            asm volatile("ds_read_b128 %0, %1" : "=v"(bfr[ks]) : "v"(fb[ks] + rstage) : "memory");
         }
         static_assert(ST_BK / 16 == 4, "the waits below are written for four fragment pairs");
         asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(af[0]), "+v"(bfr[0]) :: "memory");
@@ -298,8 +311,6 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[2], bfr[2], acc, 0, 0, 0);
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[3]), "+v"(bfr[3]) :: "memory");
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[3], bfr[3], acc, 0, 0, 0);
-        cstage = cstage + ST_STAGE == ST_NS * ST_STAGE ? 0 : cstage + ST_STAGE;
-        istage = istage + ST_STAGE == ST_NS * ST_STAGE ? 0 : istage + ST_STAGE;
     };
 
     for (int s = 0; s < ST_PD; ++s) issue(s * ST_STAGE);
@@ -339,24 +350,43 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
     unsigned char* Zs = smem;
     s16x4 sfrag[8];
     load_s_group(Sp, rho0, wave, r, sfrag);             // in flight across the barrier and the Zs writes
-    static_for<2>([&](auto HF) {
-        constexpr int hf = decltype(HF)::value;
-        if (hf == 0 || T - t0 > 16) {                   // uniform
-            __syncthreads();                            // stages / the previous pass's A are no longer read
-            unsigned char* zrow = Zs + (wn * 32 + m) * ZSTR + (wm * 16 + 4 * kg) * 32;
+    if constexpr (TT == 128) {
+        static_for<2>([&](auto HF) {
+            constexpr int hf = decltype(HF)::value;
+            if (hf == 0 || T - t0 > 16) {               // uniform
+                __syncthreads();                        // stages / the previous pass's A are no longer read
+                unsigned char* zrow = Zs + (wn * 32 + m) * ZSTR + (wm * 16 + 4 * kg) * 32;
 #pragma unroll
-            for (int e2 = 0; e2 < 8; ++e2) {
-                unsigned char* dst = zrow + (8 * (e2 / 4) + (e2 % 4)) * 32;
+                for (int e2 = 0; e2 < 8; ++e2) {
+                    unsigned char* dst = zrow + (8 * (e2 / 4) + (e2 % 4)) * 32;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        *(uint2*)(dst + (v ^ (2 * ((e2 / 4) & 1))) * 8) = make_uint2(zq[8 * hf + e2][2 * v], zq[8 * hf + e2][2 * v + 1]);
+                }
+                __syncthreads();
+                couple_group(Zs + wave * GROUP, sfrag);
+                __syncthreads();
+                store_a_tile<8>(Zs, A, T, t0, rho0, b, r, [](int t) { return (t >> 4) * 32 + hf * 16 + (t & 15); });
+            }
+        });
+    } else {
+        // 64 tokens: one pass; the four computing wavefronts hand over all 32 tokens of their parts
+        __syncthreads();                                // the stages are no longer read
+        if (computes) {
+            unsigned char* zrow = Zs + (wn * 32 + m) * ZSTR + (wm * 32 + 4 * kg) * 32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                unsigned char* dst = zrow + (8 * (e / 4) + (e % 4)) * 32;
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    *(uint2*)(dst + (v ^ (2 * ((e2 / 4) & 1))) * 8) = make_uint2(zq[8 * hf + e2][2 * v], zq[8 * hf + e2][2 * v + 1]);
+                    *(uint2*)(dst + (v ^ (2 * ((e / 4) & 1))) * 8) = make_uint2(zq[e][2 * v], zq[e][2 * v + 1]);
             }
-            __syncthreads();
-            couple_group(Zs + wave * GROUP, sfrag);
-            __syncthreads();
-            store_a_tile<8>(Zs, A, T, t0, rho0, b, r, [](int t) { return (t >> 4) * 32 + hf * 16 + (t & 15); });
         }
-    });
+        __syncthreads();
+        couple_group(Zs + wave * GROUP, sfrag);
+        __syncthreads();
+        store_a_tile<8>(Zs, A, T, t0, rho0, b, r, [](int t) { return t; });
+    }
 }
 
 }  // namespace
@@ -367,25 +397,35 @@ bool blast_fused_supported(int64_t T, int n_in, int b, int r) {
     const int64_t nblk = blast_fused_tiles(T, r);
     // 64 | n_in: the chunk grid is aligned to 64 input columns and must end with the row
     return q % 8 == 0 && r % 8 == 0 && n_in % 64 == 0 && nblk < (1ll << 30) &&
-           ((int64_t)ST_TT * n_in + 64) * 2 < (1ll << 31) && ((int64_t)r * blast_va_row(q) + 64) * 2 < (1ll << 31);
+           ((int64_t)128 * n_in + 64) * 2 < (1ll << 31) && ((int64_t)r * blast_va_row(q) + 64) * 2 < (1ll << 31);
 }
 
-int64_t blast_fused_tiles(int64_t T, int r) { return ((T + ST_TT - 1) / ST_TT) * ((r + TR - 1) / TR); }
+int64_t blast_fused_tiles(int64_t T, int r) { return ((T + 127) / 128) * ((r + TR - 1) / TR); }
 
-hipError_t launch_blast_stage12(const void* X, const void* Va, const void* Sp, void* A,
-                                int64_t T, int n_in, int b, int r, hipStream_t s) {
+namespace {
+template <int TT>
+hipError_t launch_stage12_inst(const void* X, const void* Va, const void* Sp, void* A,
+                               int64_t T, int n_in, int b, int r, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ST_LDS);
+        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel<TT>, hipFuncAttributeMaxDynamicSharedMemorySize, StCfg<TT>::LDS);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles_t = (int)((T + ST_TT - 1) / ST_TT), tiles_r = (r + TR - 1) / TR;
+    const int tiles_t = (int)((T + TT - 1) / TT), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
-    hipLaunchKernelGGL(blast_stage12_kernel, dim3((unsigned)nblk), dim3(512), ST_LDS, s,
+    hipLaunchKernelGGL(blast_stage12_kernel<TT>, dim3((unsigned)nblk), dim3(512), StCfg<TT>::LDS, s,
                        (const bf16_t*)X, (const bf16_t*)Va, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r,
                        blast_va_row(n_in / b), tiles_r, nblk);
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_blast_stage12(const void* X, const void* Va, const void* Sp, void* A,
+                                int64_t T, int n_in, int b, int r, hipStream_t s) {
+    // one workgroup per compute unit: 64-token tiles while they still fit in one round of the 256
+    return blast_fused_tiles(T, r) <= 128 ? launch_stage12_inst<64>(X, Va, Sp, A, T, n_in, b, r, s)
+                 : launch_stage12_inst<128>(X, Va, Sp, A, T, n_in, b, r, s);
 }
 
 template <int TNT>

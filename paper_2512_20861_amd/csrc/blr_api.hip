@@ -69,9 +69,15 @@ struct BlastPlan {
 // two intermediates (Z and A, b*r bf16 per token each) together stay well inside the 256 MB
 // memory-side cache, so that they are produced and consumed without a round trip to HBM.
 constexpr size_t kChunkBytes = 48u << 20;
-// The fused stage 1 + coupling kernel runs one workgroup per compute unit; below this many tiles it
-// leaves too much of the chip idle and the three-kernel path (finer tiles) is faster.
-constexpr int64_t kFusedMinTiles = 128;
+// The fused stage 1 + coupling kernel runs one workgroup per compute unit; below a number of 128-token
+// tiles it leaves too much of the chip idle and the three-kernel path (finer tiles) is faster. What the
+// fused kernel saves, the round trip of Z, grows with b r per token; what it pays, a stage 1 on tiles
+// of half the arithmetic intensity of the GEMM's, grows with n_in r: the longer the input block
+// q = n_in / b, the more tiles it takes to come out ahead (measured at q = 64 ... 688, r = 256 ... 1024).
+inline int64_t fused_min_tiles(int n_in, int b) {
+    const int q = n_in / b;
+    return q <= 128 ? 80 : q <= 256 ? 144 : 224;
+}
 // Up to this many tokens the coupling runs as one thread per 8 outputs (the 64-token tiles of the
 // MFMA coupling kernel would leave most of the chip idle).
 constexpr int64_t kSmallCouplingTokens = 128;
@@ -91,7 +97,7 @@ BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt,
     } else {
         if (blast_full_fusion_supported(T, n_in, n_out, b, r)) pl.path = BlastPlan::MFMA_FULL;
         else if (!(flags & BLR_BLAST_THREE_KERNELS) && blast_fused_supported(T, n_in, b, r) &&
-                 ((flags & BLR_BLAST_FUSED_STAGE12) || blast_fused_tiles(T, r) >= kFusedMinTiles)) pl.path = BlastPlan::MFMA_STAGE12;
+                 ((flags & BLR_BLAST_FUSED_STAGE12) || blast_fused_tiles(T, r) >= fused_min_tiles(n_in, b))) pl.path = BlastPlan::MFMA_STAGE12;
         else pl.path = BlastPlan::MFMA_THREE;
         if (pl.path == BlastPlan::MFMA_STAGE12) { pl.off_A = off; off += align_up((size_t)T * per_token); }
         if (pl.path == BlastPlan::MFMA_THREE) {

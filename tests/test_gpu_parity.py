@@ -69,6 +69,8 @@ BLAST_CASES = [
     (200, 1152, 1152, 9, 128, "bf16"),   # b = 9 (DiT-XL/2 rows of the paper's layer table)
     (300, 2752, 1024, 16, 328, "bf16"),  # q = 172: partial last k-chunk; r = 328: partial last rank tile
     (150, 2560, 2560, 5, 200, "bf16"),   # odd number of blocks
+    (1100, 512, 256, 16, 1000, "bf16"),  # fused stage 1+2 on 128-token tiles (more than 128 of them), ragged in T and r
+    (1000, 512, 256, 16, 1024, "bf16"),  # ... and on 64-token tiles: 256 workgroups, the last token tile ragged
 ]
 
 
