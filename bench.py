@@ -397,6 +397,7 @@ def run_chain(args, op):
     # the canonical first factor, which has the same shape (values do not matter for the timing)
     OB, IB = B.MONARCH_OUT_BLOCKED, B.MONARCH_IN_BLOCKED
     plan = ([("q", 3, OB), ("o", 1, IB), ("gate", 2, OB), ("down", 1, IB)] if chain.blocked
+            else [("q", 3, 0), ("o", 1, 0), ("gate", 2, 0), ("down", 1, 0)] if chain.grouped
             else [("q", 4, 0), ("gate", 2, 0), ("down", 1, 0)])
     for name, count, fl in plan:
         cfg = chain_linear_cfg(op, name)

@@ -167,6 +167,34 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
                              void* workspace, size_t workspace_bytes, blr_stream stream);
 
 /*
+ * `members` BLAST layers of one shape (n_in, n_out, b, r) that read the same X, as one call (q, k, v
+ * or gate, up of a decoder layer; paper Section 2.1 "BLAST", Section 4 "BLAST"). Stages 1 and 2 of
+ * the operator act on every rank index by itself, so the members' rank indices concatenate into one
+ * layer of rank members*r there (one pass over X instead of `members`, larger launches); stage 3
+ * contracts each member's own range:
+ *   Z[t][j][m*r+rho]      = sum_c X[t][j*q+c] * V_m[j][c][rho]
+ *   A[t][i][m*r+rho]      = sum_j S_m[i][j][rho] * Z[t][j][m*r+rho]
+ *   Y[t][m*n_out+i*p+a]   = sum_rho A[t][i][m*r+rho] * U_m[i][a][rho]
+ * X[T][n_in]; U[members][b][p][r]: the members' canonical U stacked; `packed`: the buffer written by
+ * blr_blast_pack for (n_in, n_out, b, members*r) from S_g[b][b][members*r] and V_g[b][q][members*r],
+ * the members' S and V concatenated along the rank index (U is not read by that call for such a shape:
+ * pass the stacked U); Y[T][members*n_out], member m in columns m*n_out ... (m+1)*n_out - 1.
+ * bf16 only, 8 | r. flags: BLR_BLAST_FUSED_STAGE12 or BLR_BLAST_THREE_KERNELS (default: the library
+ * chooses as for a single layer of rank members*r). workspace: at least
+ * blr_blast_group_workspace_bytes(...) bytes with the same flags.
+ * BLR_ERR_UNSUPPORTED (workspace query: 0) where the concatenated layer has no matrix-core kernels
+ * for stages 1 and 2 or is small enough for the single-kernel path, whose packed form holds no
+ * separate stage-1 operand: run such members one by one with blr_blast_forward. Other errors as for
+ * blr_blast_forward; T == 0 returns BLR_OK without launching.
+ */
+size_t     blr_blast_group_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, int members,
+                                           blr_dtype dt, unsigned flags);
+blr_status blr_blast_group_forward(const void* X, const void* U, const void* packed, void* Y,
+                                   int64_t T, int n_in, int n_out, int b, int r, int members,
+                                   blr_dtype dt, unsigned flags,
+                                   void* workspace, size_t workspace_bytes, blr_stream stream);
+
+/*
  * One-time re-layout of the static BLAST factors (paper Section 4: weights are static, so their
  * layout is changed once before inference). bf16 only, b <= 16. `packed` is an opaque buffer of
  * blr_blast_packed_bytes(...) bytes that holds

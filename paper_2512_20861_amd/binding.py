@@ -30,10 +30,12 @@ EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forw
            "blr_blast_pack", "blr_dense_reference_forward",
            "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul",
            "blr_monarch_permute_first_factor", "blr_lowrank_workspace_bytes", "blr_lowrank_forward",
-           "blr_monarch_rect_workspace_bytes", "blr_monarch_rect_forward", "blr_sum3_scaled_ld", "blr_silu_mul_ld")
+           "blr_monarch_rect_workspace_bytes", "blr_monarch_rect_forward", "blr_sum3_scaled_ld", "blr_silu_mul_ld",
+           "blr_blast_group_workspace_bytes", "blr_blast_group_forward")
 # entry points that enqueue work and return a status: the ones prepared() can record
 _LAUNCHERS = ("blr_monarch_forward", "blr_blast_forward", "blr_dense_reference_forward", "blr_lowrank_forward", "blr_monarch_rect_forward",
-              "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul", "blr_sum3_scaled_ld", "blr_silu_mul_ld")
+              "blr_rmsnorm", "blr_residual_add_rmsnorm", "blr_sum3_scaled", "blr_silu_mul", "blr_sum3_scaled_ld", "blr_silu_mul_ld",
+              "blr_blast_group_forward")
 
 _lib = None
 _last_workspace = None     # the workspace the latest forward call ran with (kept alive for prepared())
@@ -71,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.blr_blast_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, cu]
         L.blr_blast_forward.restype = ci
         L.blr_blast_forward.argtypes = [vp, vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, cu, vp, sz, vp]
+        L.blr_blast_group_workspace_bytes.restype = sz
+        L.blr_blast_group_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci, ci, cu]
+        L.blr_blast_group_forward.restype = ci
+        L.blr_blast_group_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, cu, vp, sz, vp]
         L.blr_blast_packed_bytes.restype = sz
         L.blr_blast_packed_bytes.argtypes = [ci, ci, ci, ci, ci]
         L.blr_blast_pack.restype = ci
@@ -215,6 +221,27 @@ def blast_forward(X, U, S, V, Y, b, r, flags=0, workspace=None, stream=None):
     _last_workspace = workspace
     _check(lib().blr_blast_forward(_ptr(X), _ptr(U), _ptr(S), _ptr(V), _ptr(Y), T, n_in, n_out, b, r, dt, flags,
                                    _ptr(workspace), workspace.numel(), _stream(stream)), "blr_blast_forward")
+    return Y
+
+
+def blast_group_workspace_bytes(T, n_in, n_out, b, r, members, dt=BF16, flags=0) -> int:
+    return lib().blr_blast_group_workspace_bytes(T, n_in, n_out, b, r, members, dt, flags)
+
+
+def blast_group_forward(X, U, packed, Y, b, r, members, flags=0, workspace=None, stream=None):
+    """Y[T][members*n_out] <- `members` BLAST layers of one shape on the same X[T][n_in];
+    U[members][b][n_out/b][r] stacked, `packed` = blast_pack of the members' S and V concatenated
+    along the rank index (rank members*r)."""
+    T, n_in = X.shape
+    n_out = Y.shape[1] // members
+    dt = _dt(X)
+    if workspace is None:
+        workspace = torch.empty(max(blast_group_workspace_bytes(T, n_in, n_out, b, r, members, dt, flags), 16),
+                                dtype=torch.uint8, device=X.device)
+    global _last_workspace
+    _last_workspace = workspace
+    _check(lib().blr_blast_group_forward(_ptr(X), _ptr(U), _ptr(packed), _ptr(Y), T, n_in, n_out, b, r, members, dt, flags,
+                                         _ptr(workspace), workspace.numel(), _stream(stream)), "blr_blast_group_forward")
     return Y
 
 

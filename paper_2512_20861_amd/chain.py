@@ -14,6 +14,8 @@ There the linears that share an input (q, k, v; gate, up) also run as ONE call e
 equal shape are one general Monarch layer with n * nblocks output blocks once the rows of their
 first factors are interleaved (done once at set-up), which turns 2 n launch-bound GEMMs into two
 larger ones; their outputs lie side by side in one tensor and the glue reads them as column slices.
+In an all-BLAST chain the same linears run as one grouped BLAST call each (stages 1 and 2 on the
+members' concatenated rank indices, one stage-3 product per member).
 """
 from __future__ import annotations
 
@@ -52,6 +54,7 @@ class _Linear:
         else:
             self.op, self.b = "blast", host.b
             self.U, self.S, self.V = upload(host.U), upload(host.S), upload(host.V)
+            self.S0, self.V0 = self.S, self.V              # canonical forms for a group's own pack; dropped by DeviceChain
             self.flags = 0
             if B.blast_packed_bytes(self.n_in, self.n_out, self.b, self.r, self.dt) > 0:
                 self.packed = B.blast_pack(self.U, self.S, self.V, self.n_in, self.n_out, self.b, self.r)
@@ -95,6 +98,33 @@ class _MonarchGroup:
         return (B.monarch_rect_forward, X, self.R, self.L, Y, self.nb, self.n * self.nb, self.rp, self.flags, ws)
 
 
+class _BlastGroup:
+    """n BLAST linears of equal shape that read the same input, as one call: stages 1 and 2 act on
+    every rank index by itself, so the members' S and V concatenate along the rank index (packed once
+    here); U stays per member. Output [T][n * n_out], member by member."""
+
+    def __init__(self, members):
+        m0 = members[0]
+        assert all(m.op == "blast" and (m.n_in, m.n_out, m.r, m.b, m.dt) == (m0.n_in, m0.n_out, m0.r, m0.b, m0.dt) for m in members)
+        self.n, self.n_in, self.n_out, self.b, self.r, self.dt = len(members), m0.n_in, m0.n_out, m0.b, m0.r, m0.dt
+        self.U = torch.stack([m.U for m in members], dim=0).contiguous()
+        S = torch.cat([m.S0 for m in members], dim=2).contiguous()
+        V = torch.cat([m.V0 for m in members], dim=2).contiguous()
+        self.packed = B.blast_pack(self.U, S, V, self.n_in, self.n_out, self.b, self.n * self.r)
+
+    @staticmethod
+    def possible(members, T):
+        m0 = members[0]
+        return all(m.op == "blast" for m in members) and \
+            B.blast_group_workspace_bytes(T, m0.n_in, m0.n_out, m0.b, m0.r, len(members), m0.dt) > 0
+
+    def workspace_bytes(self, T):
+        return B.blast_group_workspace_bytes(T, self.n_in, self.n_out, self.b, self.r, self.n, self.dt)
+
+    def call_args(self, X, Y, ws):
+        return (B.blast_group_forward, X, self.U, self.packed, Y, self.b, self.r, self.n, 0, ws)
+
+
 class DeviceChain:
     OUT_BLOCKED = ("q", "k", "v", "gate", "up")          # only elementwise steps between these and their consumer
     IN_BLOCKED = ("o", "down")
@@ -112,18 +142,26 @@ class DeviceChain:
         new = lambda d: torch.empty((T, d), dtype=td, device="cuda")
         self.h, self.n = new(self.hidden), new(self.hidden)
         self.a, self.o, self.dn = (new(self.hidden) for _ in range(3))
-        # grouped calls (all-Monarch chain with blocked chaining): q, k, v and gate, up are column slices
-        self.grouped = bool(grouped and self.blocked)
+        # grouped calls (all-Monarch chain with blocked chaining; all-BLAST chain whose groups have
+        # matrix-core kernels): q, k, v and gate, up are column slices
+        L0 = self.layers[0]
+        blast_groups = all(_BlastGroup.possible(g, T) for g in ([L0[n] for n in "qkv"], [L0["gate"], L0["up"]]))
+        self.grouped = bool(grouped and (self.blocked or blast_groups))
         if self.grouped:
             self.qkv, self.gu, self.m = new(3 * self.hidden), new(2 * self.mlp), new(self.mlp)
             self.q, self.k, self.v = (self.qkv[:, i * self.hidden:(i + 1) * self.hidden] for i in range(3))
             self.g, self.u = self.gu[:, :self.mlp], self.gu[:, self.mlp:]
-            self.groups = [{"qkv": _MonarchGroup([L[n] for n in "qkv"]), "gu": _MonarchGroup([L["gate"], L["up"]])} for L in self.layers]
+            Group = _MonarchGroup if self.blocked else _BlastGroup
+            self.groups = [{"qkv": Group([L[n] for n in "qkv"]), "gu": Group([L["gate"], L["up"]])} for L in self.layers]
         else:
             self.q, self.k, self.v = (new(self.hidden) for _ in range(3))
             self.g, self.u = new(self.mlp), new(self.mlp)
             self.m = self.g                              # the SiLU gate is applied in place
             self.groups = []
+        for L in self.layers:
+            for lin in L.values():
+                if lin.op == "blast":
+                    lin.S0 = lin.V0 = None                   # the groups hold their own packed copies
         need = max([lin.workspace_bytes(T) for layer in self.layers for lin in layer.values()] +
                    [grp.workspace_bytes(T) for layer in self.groups for grp in layer.values()])
         self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
@@ -167,7 +205,7 @@ class DeviceChain:
                 src = args[1].clone()
             args[0](*args[1:])
             if record:
-                if args[0] is B.monarch_rect_forward:
+                if args[0] in (B.monarch_rect_forward, B.blast_group_forward):
                     li, grp = label.split(".")
                     for name, part in zip(("q", "k", "v") if grp == "qkv" else ("gate", "up"),
                                           (self.q, self.k, self.v) if grp == "qkv" else (self.g, self.u)):

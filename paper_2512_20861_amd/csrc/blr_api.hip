@@ -183,6 +183,114 @@ bool monarch_rect_shape_ok(int64_t T, int n_in, int n_out, int b1, int b2, int r
 
 }  // namespace
 
+// A group runs on the bf16 MFMA kernels of stages 1 and 2 with the concatenated rank, or not at all.
+static bool blast_group_ok(int64_t T, int n_in, int n_out, int b, int r, int members, blr_dtype dt, unsigned flags) {
+    if (members <= 0 || r <= 0 || r % 8 || (int64_t)r * members > (1 << 24) || dt != BLR_BF16 || b > 16) return false;   // 8 | r: every member's range of A starts on a 16-byte boundary
+    if (!blast_shape_ok(T, n_in, n_out, b, r * members) || !blast_mfma_shape_ok(n_in, b, r * members)) return false;
+    if (pack_layout(n_in, n_out, b, r * members).full) return false;     // such a pack holds no stage-1 operand
+    const BlastPlan::Path path = blast_plan(T > 0 ? T : 1, n_in, n_out, b, r * members, dt, flags | BLR_BLAST_PACKED).path;
+    return path == BlastPlan::MFMA_STAGE12 || path == BlastPlan::MFMA_THREE;
+}
+
+// The multi-kernel executions of `members` BLAST layers of one shape that share X (members = 1: the
+// plain layer; rm: rank of one member). Stages 1 and 2 act on every rank index by itself, so the
+// members' rank indices simply concatenate there; stage 3 contracts each member's own range.
+static blr_status blast_run(const void* X, const void* U, const void* S, const void* V, void* Y,
+                            int64_t T, int n_in, int n_out, int b, int rm, int members,
+                            blr_dtype dt, unsigned flags,
+                            void* workspace, size_t workspace_bytes, hipStream_t s) {
+    const int r = rm * members;                     // stages 1 and 2 see one layer of rank r
+    const BlastPlan pl = blast_plan(T, n_in, n_out, b, r, dt, flags);
+    if ((flags & BLR_BLAST_PACKED) && pl.path == BlastPlan::GENERIC) return BLR_ERR_UNSUPPORTED;
+    if (pl.total > 0 && (!workspace || workspace_bytes < pl.total)) return BLR_ERR_WORKSPACE;
+    const int q = n_in / b, p = n_out / b;
+    unsigned char* ws = (unsigned char*)workspace;
+    void* Aws = ws + pl.off_A;
+    void* Zws = ws + pl.off_Z;
+
+    // stage 3 (all multi-kernel paths), member m: Y[t][m*n_out + i*p + a] = sum_rho A[t][i][m*rm + rho] U_m[i][a][rho]
+    const size_t es = elem_size(dt);
+    const int64_t ldy = (int64_t)members * n_out;
+    GemmDesc s3{};
+    s3.a_gs = r; s3.a_rs = (int64_t)b * r;
+    s3.b_gs = (int64_t)p * rm; s3.b_rs = rm; s3.b_ks = 1; s3.b_div = 0;
+    s3.c_rs = ldy; s3.c_gs = p; s3.c_div = 1; s3.c_hi = 1; s3.c_lo = 0;
+    s3.M = T; s3.N = p; s3.K = rm; s3.G = b;
+    auto run_stage3 = [&](int64_t c0, int64_t tc, bool mfma) {   // tokens c0 .. c0 + tc - 1; A holds them from its start
+        for (int m = 0; m < members; ++m) {
+            s3.A = (const unsigned char*)Aws + (size_t)m * rm * es;
+            s3.B = (const unsigned char*)U + (size_t)m * n_out * rm * es;
+            s3.C = (unsigned char*)Y + ((size_t)c0 * ldy + (size_t)m * n_out) * es;
+            s3.M = tc;
+            blr_status st = run_gemm(s3, dt, mfma, s);
+            if (st != BLR_OK) return st;
+        }
+        return BLR_OK;
+    };
+
+    // stage 1 as a stand-alone product: Z[t][j][rho]
+    GemmDesc s1{};
+    s1.A = X; s1.a_gs = q; s1.a_rs = n_in;
+    s1.C = Zws; s1.c_rs = (int64_t)b * r; s1.c_gs = r; s1.c_div = 1; s1.c_hi = 1; s1.c_lo = 0;
+    s1.M = T; s1.N = r; s1.K = q; s1.G = b;
+
+    const bool first = !(flags & BLR_ONLY_LAST_STAGE), last = !(flags & BLR_ONLY_FIRST_STAGE);
+    if (pl.path == BlastPlan::GENERIC) {
+        if (members != 1) return BLR_ERR_UNSUPPORTED;
+        if (first) {
+            s1.B = V; s1.b_gs = (int64_t)q * r; s1.b_rs = 1; s1.b_ks = r; s1.b_div = 0;   // V[j][c][rho]: rho contiguous
+            blr_status st = run_gemm(s1, dt, false, s);
+            if (st != BLR_OK) return st;
+            st = from_hip(launch_coupling_valu(Zws, S, Aws, T, b, r, dt == BLR_BF16 ? DType::BF16 : DType::F32, s));
+            if (st != BLR_OK) return st;
+        }
+        return last ? run_stage3(0, T, false) : BLR_OK;
+    }
+
+    const unsigned char* pack = (const unsigned char*)V;
+    if (!(flags & BLR_BLAST_PACKED)) {
+        pack = ws + pl.off_pack;
+        if (first) {
+            blr_status st = run_pack(U, S, V, ws + pl.off_pack, n_in, n_out, b, r, s);
+            if (st != BLR_OK) return st;
+        }
+    }
+    const PackLayout pk = pack_layout(n_in, n_out, b, r);
+    const void* Sp = pack + pk.off_Sp;
+    const void* Vt = pack + pk.off_Vt;
+    if (pl.path == BlastPlan::MFMA_FULL) {
+        if (!first || !last || members != 1) return BLR_ERR_UNSUPPORTED;   // one kernel: there are no stages to select
+        return from_hip(launch_blast_full(X, Sp, pack + pk.off_Vf, pack + pk.off_Uf, Y, T, n_in, n_out, b, r, s));
+    }
+    if (pl.path == BlastPlan::MFMA_STAGE12) {
+        if (first) {
+            blr_status st = from_hip(launch_blast_stage12(X, pack + pk.off_Va, Sp, Aws, T, n_in, b, r, s));
+            if (st != BLR_OK) return st;
+        }
+        return last ? run_stage3(0, T, true) : BLR_OK;
+    }
+    // three kernels per chunk of tokens: stage-1 GEMM -> Z, MFMA coupling Z -> A, stage-3 GEMM
+    s1.B = Vt; s1.b_gs = (int64_t)q * r; s1.b_rs = q; s1.b_ks = 1; s1.b_div = 0;
+    for (int64_t c0 = 0; c0 < T; c0 += pl.chunk) {
+        const int64_t tc = T - c0 < pl.chunk ? T - c0 : pl.chunk;
+        if (first) {
+            s1.A = (const unsigned char*)X + (size_t)c0 * n_in * 2;
+            s1.M = tc;
+            blr_status st = run_gemm(s1, dt, true, s);
+            if (st != BLR_OK) return st;
+            // few tokens: the 64-token tiles of the MFMA coupling would be mostly padding; one thread per output element then
+            st = from_hip(tc <= kSmallCouplingTokens ? launch_coupling_small(Zws, pack + pk.off_Sc, Aws, tc, b, r, s) : launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
+            if (st != BLR_OK) return st;
+        }
+        if (last) {
+            blr_status st = run_stage3(c0, tc, true);
+            if (st != BLR_OK) return st;
+        }
+    }
+    return BLR_OK;
+}
+
+
 extern "C" {
 
 const char* blr_status_string(blr_status s) {
@@ -329,83 +437,29 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
     if (!aligned16(X) || !aligned16(U) || !aligned16(S) || !aligned16(V) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
     if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null
     if (!X || !Y) return BLR_ERR_INVALID_ARG;
-    const BlastPlan pl = blast_plan(T, n_in, n_out, b, r, dt, flags);
-    if ((flags & BLR_BLAST_PACKED) && pl.path == BlastPlan::GENERIC) return BLR_ERR_UNSUPPORTED;
-    if (pl.total > 0 && (!workspace || workspace_bytes < pl.total)) return BLR_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
-    const int q = n_in / b, p = n_out / b;
-    unsigned char* ws = (unsigned char*)workspace;
-    void* Aws = ws + pl.off_A;
-    void* Zws = ws + pl.off_Z;
+    return blast_run(X, U, S, V, Y, T, n_in, n_out, b, r, 1, dt, flags, workspace, workspace_bytes, (hipStream_t)stream);
+}
 
-    // stage 3 (all multi-kernel paths): Y[t][i*p + a] = sum_rho A[t][i][rho] U[i][a][rho]
-    GemmDesc s3{};
-    s3.A = Aws; s3.a_gs = r; s3.a_rs = (int64_t)b * r;
-    s3.B = U; s3.b_gs = (int64_t)p * r; s3.b_rs = r; s3.b_ks = 1; s3.b_div = 0;
-    s3.C = Y; s3.c_rs = n_out; s3.c_gs = p; s3.c_div = 1; s3.c_hi = 1; s3.c_lo = 0;
-    s3.M = T; s3.N = p; s3.K = r; s3.G = b;
+size_t blr_blast_group_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, int members, blr_dtype dt, unsigned flags) {
+    if (!blast_group_ok(T, n_in, n_out, b, r, members, dt, flags)) return 0;
+    return blast_plan(T, n_in, n_out, b, r * members, dt, flags | BLR_BLAST_PACKED).total;
+}
 
-    // stage 1 as a stand-alone product: Z[t][j][rho]
-    GemmDesc s1{};
-    s1.A = X; s1.a_gs = q; s1.a_rs = n_in;
-    s1.C = Zws; s1.c_rs = (int64_t)b * r; s1.c_gs = r; s1.c_div = 1; s1.c_hi = 1; s1.c_lo = 0;
-    s1.M = T; s1.N = r; s1.K = q; s1.G = b;
-
-    const bool first = !(flags & BLR_ONLY_LAST_STAGE), last = !(flags & BLR_ONLY_FIRST_STAGE);
-    if (pl.path == BlastPlan::GENERIC) {
-        if (first) {
-            s1.B = V; s1.b_gs = (int64_t)q * r; s1.b_rs = 1; s1.b_ks = r; s1.b_div = 0;   // V[j][c][rho]: rho contiguous
-            blr_status st = run_gemm(s1, dt, false, s);
-            if (st != BLR_OK) return st;
-            st = from_hip(launch_coupling_valu(Zws, S, Aws, T, b, r, dt == BLR_BF16 ? DType::BF16 : DType::F32, s));
-            if (st != BLR_OK) return st;
-        }
-        return last ? run_gemm(s3, dt, false, s) : BLR_OK;
-    }
-
-    const unsigned char* pack = (const unsigned char*)V;
-    if (!(flags & BLR_BLAST_PACKED)) {
-        pack = ws + pl.off_pack;
-        if (first) {
-            blr_status st = run_pack(U, S, V, ws + pl.off_pack, n_in, n_out, b, r, s);
-            if (st != BLR_OK) return st;
-        }
-    }
-    const PackLayout pk = pack_layout(n_in, n_out, b, r);
-    const void* Sp = pack + pk.off_Sp;
-    const void* Vt = pack + pk.off_Vt;
-    if (pl.path == BlastPlan::MFMA_FULL) {
-        if (!first || !last) return BLR_ERR_UNSUPPORTED;   // one kernel: there are no stages to select
-        return from_hip(launch_blast_full(X, Sp, pack + pk.off_Vf, pack + pk.off_Uf, Y, T, n_in, n_out, b, r, s));
-    }
-    if (pl.path == BlastPlan::MFMA_STAGE12) {
-        if (first) {
-            blr_status st = from_hip(launch_blast_stage12(X, pack + pk.off_Va, Sp, Aws, T, n_in, b, r, s));
-            if (st != BLR_OK) return st;
-        }
-        return last ? run_gemm(s3, dt, true, s) : BLR_OK;
-    }
-    // three kernels per chunk of tokens: stage-1 GEMM -> Z, MFMA coupling Z -> A, stage-3 GEMM
-    s1.B = Vt; s1.b_gs = (int64_t)q * r; s1.b_rs = q; s1.b_ks = 1; s1.b_div = 0;
-    for (int64_t c0 = 0; c0 < T; c0 += pl.chunk) {
-        const int64_t tc = T - c0 < pl.chunk ? T - c0 : pl.chunk;
-        if (first) {
-            s1.A = (const unsigned char*)X + (size_t)c0 * n_in * 2;
-            s1.M = tc;
-            blr_status st = run_gemm(s1, dt, true, s);
-            if (st != BLR_OK) return st;
-            // few tokens: the 64-token tiles of the MFMA coupling would be mostly padding; one thread per output element then
-            st = from_hip(tc <= kSmallCouplingTokens ? launch_coupling_small(Zws, pack + pk.off_Sc, Aws, tc, b, r, s) : launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
-            if (st != BLR_OK) return st;
-        }
-        if (last) {
-            s3.C = (unsigned char*)Y + (size_t)c0 * n_out * 2;
-            s3.M = tc;
-            blr_status st = run_gemm(s3, dt, true, s);
-            if (st != BLR_OK) return st;
-        }
-    }
-    return BLR_OK;
+blr_status blr_blast_group_forward(const void* X, const void* U, const void* packed, void* Y,
+                                   int64_t T, int n_in, int n_out, int b, int r, int members,
+                                   blr_dtype dt, unsigned flags,
+                                   void* workspace, size_t workspace_bytes, blr_stream stream) {
+    if (!U || !packed || members <= 0 || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    if (r <= 0 || (int64_t)r * members > (1 << 24)) return BLR_ERR_INVALID_ARG;
+    if (!blast_shape_ok(T, n_in, n_out, b, r * members)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_BLAST_FUSED_STAGE12 | BLR_BLAST_THREE_KERNELS)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_BLAST_FUSED_STAGE12) && (flags & BLR_BLAST_THREE_KERNELS)) return BLR_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(U) || !aligned16(packed) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
+    if (!blast_group_ok(T, n_in, n_out, b, r, members, dt, flags)) return BLR_ERR_UNSUPPORTED;
+    if (T == 0) return BLR_OK;
+    if (!X || !Y) return BLR_ERR_INVALID_ARG;
+    return blast_run(X, U, nullptr, packed, Y, T, n_in, n_out, b, r, members, dt, flags | BLR_BLAST_PACKED,
+                     workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 blr_status blr_dense_reference_forward(const void* X, const void* W, void* Y,

@@ -49,6 +49,20 @@ def run_lowrank(X, lay, flags=0):
     return Y
 
 
+def run_blast_group(X, lays, flags=0):
+    """The layers of `lays` (one shape, same input) as one grouped call; returns Y[T][len(lays)*n_out]."""
+    l0 = lays[0]
+    Xd = to_dev(X)
+    Ud = torch.stack([to_dev(l.U) for l in lays], dim=0).contiguous()
+    Sd = torch.cat([to_dev(l.S) for l in lays], dim=2).contiguous()
+    Vd = torch.cat([to_dev(l.V) for l in lays], dim=2).contiguous()
+    packed = B.blast_pack(Ud, Sd, Vd, l0.n_in, l0.n_out, l0.b, len(lays) * l0.r)
+    Y = empty_out(X.shape[0], len(lays) * l0.n_out, l0.dtype)
+    B.blast_group_forward(Xd, Ud, packed, Y, l0.b, l0.r, len(lays), flags)
+    torch.cuda.synchronize()
+    return Y
+
+
 def run_blast(X, lay, flags=0, packed=False):
     Xd, Ud, Sd, Vd = to_dev(X), to_dev(lay.U), to_dev(lay.S), to_dev(lay.V)
     Y = empty_out(X.shape[0], lay.n_out, lay.dtype)

@@ -185,6 +185,33 @@ def test_dense_and_pack_argument_checks():
     assert lib.blr_blast_pack(FAKE, FAKE, FAKE, FAKE, 36, 30, 3, 10, B.BF16, None) == B.ERR_UNSUPPORTED
 
 
+def test_blast_group_argument_checks():
+    lib = B.lib()
+    def grp(X=FAKE, U=FAKE, P=FAKE, Y=FAKE, T=256, n_in=2048, n_out=2048, b=16, r=256, members=3, dt=B.BF16, flags=0, ws=FAKE, wsb=1 << 40):
+        return lib.blr_blast_group_forward(X, U, P, Y, T, n_in, n_out, b, r, members, dt, flags, ws, wsb, None)
+    need = lib.blr_blast_group_workspace_bytes(256, 2048, 2048, 16, 256, 3, B.BF16, 0)
+    # the group's workspace is that of one layer with the concatenated rank
+    assert need == lib.blr_blast_workspace_bytes(256, 2048, 2048, 16, 768, B.BF16, B.BLAST_PACKED) > 0
+    assert grp(T=0, X=None, Y=None) == B.OK
+    assert grp(U=None) == B.ERR_INVALID_ARG
+    assert grp(P=None) == B.ERR_INVALID_ARG
+    assert grp(X=None) == B.ERR_INVALID_ARG
+    assert grp(members=0) == B.ERR_INVALID_ARG
+    assert grp(r=0) == B.ERR_INVALID_ARG
+    assert grp(n_in=2050) == B.ERR_INVALID_ARG                       # b does not divide n_in
+    assert grp(flags=B.BLAST_PACKED) == B.ERR_INVALID_ARG            # implied, not a flag of this entry point
+    assert grp(flags=B.FORCE_GENERIC) == B.ERR_INVALID_ARG
+    assert grp(flags=B.BLAST_FUSED_STAGE12 | B.BLAST_THREE_KERNELS) == B.ERR_INVALID_ARG
+    assert grp(X=FAKE + 2) == B.ERR_INVALID_ARG                      # not 16-byte aligned
+    assert grp(wsb=need - 1) == B.ERR_WORKSPACE
+    assert grp(ws=None) == B.ERR_WORKSPACE
+    # no matrix-core kernels for the concatenated layer, or a layer of the single-kernel size: members run one by one
+    for kw in (dict(dt=B.F32), dict(r=12), dict(n_in=36, n_out=30, b=3, r=8), dict(n_in=768, n_out=768, b=16, r=32, members=2)):
+        args = dict(T=256, n_in=2048, n_out=2048, b=16, r=256, members=3, dt=B.BF16); args.update(kw)
+        assert lib.blr_blast_group_workspace_bytes(args["T"], args["n_in"], args["n_out"], args["b"], args["r"], args["members"], args["dt"], 0) == 0, kw
+        assert grp(**kw) == B.ERR_UNSUPPORTED, kw
+
+
 def test_glue_argument_checks():
     L = B.lib()
     A, C, D = FAKE, FAKE + 0x1000, FAKE + 0x2000
@@ -250,6 +277,7 @@ def test_python_wrappers_marshal_every_entry_point(monkeypatch):
     B.lowrank_forward(bf(T, n), bf(r, n), bf(48, r), bf(T, 48), 0, ws)
     B.blast_forward(bf(T, n), bf(b, n // b, r), bf(b, b, r), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
     B.blast_pack(bf(16, 48, 96), bf(16, 16, 96), bf(16, 48, 96), 768, 768, 16, 96)
+    B.blast_group_forward(bf(T, 2048), bf(3, 16, 128, 256), bf(64), bf(T, 3 * 2048), 16, 256, 3, 0, ws)
     B.dense_reference_forward(bf(T, n), bf(n, n), bf(T, n))
     B.rmsnorm(bf(T, n), bf(T, n))
     B.residual_add_rmsnorm(bf(T, n), bf(T, n), bf(T, n))

@@ -90,6 +90,48 @@ def test_blast_parity(T, n_in, n_out, b, r, dtype, mode):
     assert err <= gu.TOL[dtype]
 
 
+BLAST_GROUP_CASES = [
+    # T, n_in, n_out, b, r, members
+    (333, 1024, 512, 16, 72, 3),      # concatenated rank 216: partial last rank tile; ragged T
+    (130, 2816, 1024, 16, 168, 2),    # q = 176: input chunks that straddle blocks
+    (1100, 512, 256, 16, 504, 2),     # more than 128 of the 128-token fused tiles
+    (70, 512, 2048, 8, 256, 4),       # b = 8, four members
+    (1, 2048, 2048, 16, 256, 3),      # one token
+]
+
+
+@pytest.mark.parametrize("T,n_in,n_out,b,r,members", BLAST_GROUP_CASES)
+@pytest.mark.parametrize("mode", ["default", "fused12", "three"])
+def test_blast_group_parity(T, n_in, n_out, b, r, members, mode):
+    """Layers that share their input, run as one grouped call: every member's columns equal the
+    oracle's layer on that member's own factors."""
+    gu = _gu()
+    lays = [bi.blast_layer(n_in, n_out, b, r, "bf16", layer_id=m) for m in range(members)]
+    X = bi.activations(T, n_in, "bf16")
+    flags = {"fused12": gu.B.BLAST_FUSED_STAGE12, "three": gu.B.BLAST_THREE_KERNELS}.get(mode, 0)
+    Y = gu.to_f64(gu.run_blast_group(X, lays, flags))
+    assert Y.shape == (T, members * n_out)
+    for m, lay in enumerate(lays):
+        Yref = oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64)
+        err = gu.rel_err(Y[:, m * n_out:(m + 1) * n_out], Yref)
+        print(f"blast group {T}x{n_in}->{members}x{n_out} b={b} r={r} {mode} member {m}: rel err {err:.3e}")
+        assert err <= gu.TOL["bf16"]
+
+
+def test_blast_group_equals_members_bit_for_bit():
+    """Grouping changes launches, not arithmetic: each member's columns are the bits of its own call
+    when both take the same execution of stages 1 and 2."""
+    gu = _gu()
+    T, n_in, n_out, b, r = 400, 2048, 1024, 16, 256
+    lays = [bi.blast_layer(n_in, n_out, b, r, "bf16", layer_id=m) for m in range(3)]
+    X = bi.activations(T, n_in, "bf16")
+    for flag in (gu.B.BLAST_FUSED_STAGE12, gu.B.BLAST_THREE_KERNELS):
+        Yg = gu.run_blast_group(X, lays, flag)
+        for m, lay in enumerate(lays):
+            Ym = gu.run_blast(X, lay, flag, packed=True)
+            assert torch.equal(Yg[:, m * n_out:(m + 1) * n_out], Ym), (flag, m)
+
+
 def _to_blocked(X64, b):
     """Feature j*b + k -> position k*(n/b) + j (the BLOCKED output order of a Monarch layer with b blocks)."""
     T, n = X64.shape
