@@ -409,7 +409,14 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s, bool allow_split = false
     const int tiles_m = (int)((d.M + BM - 1) / BM);
     const int tiles_n = (d.N + BN - 1) / BN;
     const bool vec = c_map_vectorizes(d);
-    const bool gfast = !vec && d.G > 1 && (int64_t)tiles_m * tiles_n * d.G < (1ll << 31);
+    // Column maps that scatter runs shorter than a 128-byte line: the batches whose runs share lines run
+    // side by side (batch index fastest). Element-wise stores always; vector stores only when the
+    // output is larger than the 256 MB memory-side cache, where the parts of a line would otherwise
+    // reach HBM one by one (stage 1 of Monarch with 16 to 48 ranks per block at 16 k and more tokens:
+    // 17-24 % faster; with a cache-resident output the batch-major order is up to 20 % faster).
+    const bool runs_share_lines = vec && d.c_div > 1 && d.c_div < 64 && d.c_hi != d.c_div &&
+                                  (int64_t)d.M * d.c_rs * 2 >= (256ll << 20);
+    const bool gfast = (!vec || runs_share_lines) && d.G > 1 && (int64_t)tiles_m * tiles_n * d.G < (1ll << 31);
     const int64_t ntiles = (int64_t)tiles_m * tiles_n * d.G;
     SplitPlan sp = split_plan(ntiles, d.K);
     if (!allow_split || !d.split_scratch || (size_t)sp.nsplit * ntiles * BM * BN * sizeof(float) > d.split_scratch_bytes)

@@ -63,6 +63,23 @@ def test_monarch_llama_shapes_sampled(name, T):
         assert err <= gu.TOL["bf16"]
 
 
+def test_monarch_short_rank_runs_into_an_intermediate_beyond_the_cache_sampled():
+    """16 blocks of 16 ranks at 32768 tokens: stage 1 writes 32-byte runs into a 268 MB intermediate,
+    the case in which the blocks that share a cache line are launched side by side."""
+    gu = _gu()
+    T, n, nb, r = 32768, 2048, 16, 256
+    lay = bi.monarch_layer(n, n, nb, r, "bf16")
+    X = bi.activations(T, n, "bf16")
+    rows = _sample_rows(T, 40)
+    Y = gu.run_monarch(X, lay, gu.B.MONARCH_TWO_KERNELS)
+    assert torch.isfinite(Y.float()).all()
+    Ys = gu.to_f64(Y[torch.from_numpy(rows).cuda()])
+    Yref = oracle.monarch_forward(X.f64[rows], lay.R.f64, lay.L.f64, oracle.OUT_INTERLEAVED)
+    err = gu.rel_err(Ys, Yref)
+    print(f"monarch {n}x{n} b={nb} r={r} T={T}: {len(rows)} sampled rows, rel err {err:.3e}")
+    assert err <= gu.TOL["bf16"]
+
+
 @pytest.mark.parametrize("name,T", [("C3a", 8192), ("C3a", 512), ("C3a", 16), ("C3a", 1),
                                     ("C3b", 2048), ("C3b", 128), ("C3b", 1)])
 def test_blast_llama_shapes_sampled(name, T):
