@@ -141,6 +141,30 @@ bool monarch_takes_fused(int64_t T, int n_in, int n_out, int b1, int b2, int rp,
     return T > 32 && T <= kFusedMonarchMaxTokens && monarch_fused_lds_bytes(T, n_in, n_out, b1, b2, rp) <= kFusedMonarchMaxLds;
 }
 
+// The interleaved output order through 2-byte stores at stride b2 costs stage 2 up to twice its time
+// on large outputs (2048 -> 8192, b = 16, T = 8192: 222 us against 83 us in the blocked order). From
+// 4 M output elements on, stage 2 therefore writes the blocked order into the workspace, in chunks
+// of tokens that stay in the memory-side cache, and a permutation pass (both sides 16-byte
+// coalesced, about the time of a copy of the chunk) produces the interleaved order. With 8 blocks the
+// two ways are level, with 4 and 2 the scattered stores are faster (8- and 4-byte gaps between a
+// lane's elements instead of 32-byte ones: 4096 -> 11008, b = 4, T = 8192: 249 us against 285 us).
+constexpr int kInterleavePassMinBlocks = 8;
+constexpr int64_t kInterleavePassMinElems = 4ll << 20;
+constexpr size_t kInterleaveChunkBytes = 64u << 20;
+bool monarch_interleave_pass_shape(int64_t T, int n_out, int b2, blr_dtype dt) {
+    return dt == BLR_BF16 && b2 >= kInterleavePassMinBlocks && T * n_out >= kInterleavePassMinElems && monarch_interleave_supported(T, n_out, b2);
+}
+int64_t monarch_interleave_chunk(int64_t T, int n_out) {
+    int64_t c = (int64_t)(kInterleaveChunkBytes / ((size_t)n_out * 2)) / 256 * 256;
+    if (c < 1024) c = 1024;
+    return c < T ? c : T;
+}
+size_t monarch_workspace(int64_t T, int n_out, int b1, int b2, int rp, blr_dtype dt) {
+    size_t bytes = align_up((size_t)T * b1 * b2 * rp * elem_size(dt));
+    if (monarch_interleave_pass_shape(T, n_out, b2, dt)) bytes += align_up((size_t)monarch_interleave_chunk(T, n_out) * n_out * 2);
+    return bytes;
+}
+
 // Both Monarch entry points: b1 input blocks, b2 output blocks, per-block rank rp.
 blr_status monarch_run(const void* X, const void* R, const void* L, void* Y, int64_t T, int n_in, int n_out,
                        int b1, int b2, int rp, blr_dtype dt, unsigned flags, void* workspace, hipStream_t s) {
@@ -173,7 +197,22 @@ blr_status monarch_run(const void* X, const void* R, const void* L, void* Y, int
     if (flags & BLR_MONARCH_OUT_BLOCKED) { s2.c_gs = q; s2.c_hi = 1; }
     else { s2.c_gs = 1; s2.c_hi = b2; }
     s2.M = T; s2.N = q; s2.K = w2; s2.G = b2;
-    return run_gemm(s2, dt, allow_mfma, s);
+    if ((flags & BLR_MONARCH_OUT_BLOCKED) || !allow_mfma || !monarch_interleave_pass_shape(T, n_out, b2, dt))
+        return run_gemm(s2, dt, allow_mfma, s);
+    // interleaved order of a large output: blocked order into the workspace, then the permutation pass
+    unsigned char* Yb = (unsigned char*)workspace + align_up((size_t)T * b2 * w2 * 2);
+    s2.C = Yb; s2.c_gs = q; s2.c_hi = 1;
+    const int64_t chunk = monarch_interleave_chunk(T, n_out);
+    for (int64_t c0 = 0; c0 < T; c0 += chunk) {
+        const int64_t tc = T - c0 < chunk ? T - c0 : chunk;
+        s2.A = (const unsigned char*)workspace + (size_t)c0 * b2 * w2 * 2;
+        s2.M = tc;
+        blr_status st = run_gemm(s2, dt, true, s);
+        if (st != BLR_OK) return st;
+        st = from_hip(launch_monarch_interleave(Yb, (unsigned char*)Y + (size_t)c0 * n_out * 2, tc, n_out, b2, s));
+        if (st != BLR_OK) return st;
+    }
+    return BLR_OK;
 }
 
 bool monarch_rect_shape_ok(int64_t T, int n_in, int n_out, int b1, int b2, int rp) {
@@ -306,7 +345,7 @@ const char* blr_status_string(blr_status s) {
 
 size_t blr_monarch_workspace_bytes(int64_t T, int n_in, int n_out, int nblocks, int r, blr_dtype dt) {
     if (!monarch_shape_ok(T, n_in, n_out, nblocks, r) || !dtype_ok(dt)) return 0;
-    return align_up((size_t)T * nblocks * r * elem_size(dt));
+    return monarch_workspace(T, n_out, nblocks, nblocks, r / nblocks, dt);
 }
 
 blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void* Y,
@@ -329,7 +368,7 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
 
 size_t blr_monarch_rect_workspace_bytes(int64_t T, int n_in, int n_out, int b_in, int b_out, int r_block, blr_dtype dt) {
     if (!monarch_rect_shape_ok(T, n_in, n_out, b_in, b_out, r_block) || !dtype_ok(dt)) return 0;
-    return align_up((size_t)T * b_in * b_out * r_block * elem_size(dt));
+    return monarch_workspace(T, n_out, b_in, b_out, r_block, dt);
 }
 
 blr_status blr_monarch_rect_forward(const void* X, const void* R, const void* L, void* Y,

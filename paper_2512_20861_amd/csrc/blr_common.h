@@ -89,6 +89,10 @@ hipError_t launch_coupling_valu(const void* Z, const void* S, void* A, int64_t T
 
 // first Monarch factor re-ordered for an input in blocked order: Rp[l][c][k*(p/b)+jj] = R[l][c][jj*b+k]
 hipError_t launch_monarch_permute_first_factor(const void* R, void* Rp, int n_in, int nblocks, int r, DType dt, hipStream_t s);
+// blocked -> interleaved output order of a bf16 Monarch result, Y[t][j*b2 + k] = Yb[t][k*(n_out/b2) + j]
+// (b2 a power of two up to 64, 8 | n_out/b2)
+bool monarch_interleave_supported(int64_t T, int n_out, int b2);
+hipError_t launch_monarch_interleave(const void* Yb, void* Y, int64_t T, int n_out, int b2, hipStream_t s);
 
 // bf16 MFMA kernels; `mfma_gemm_supported` states the alignment contract
 bool mfma_gemm_supported(const GemmDesc& d);

@@ -42,7 +42,14 @@ def test_status_strings():
 def test_workspace_sizes():
     # Monarch: Z'[T][nblocks][r] in the storage type, rounded up to 256 bytes
     assert B.monarch_workspace_bytes(8, 256, 256, 4, 64, B.F32) == 8 * 4 * 64 * 4
-    assert B.monarch_workspace_bytes(8192, 4096, 4096, 4, 1024, B.BF16) == 8192 * 4096 * 2
+    assert B.monarch_workspace_bytes(512, 4096, 4096, 4, 1024, B.BF16) == 512 * 4096 * 2
+    # outputs of 4 M elements and more: plus the blocked-order copy of one chunk of tokens (64 MiB at most)
+    # with 8 blocks or more and outputs of 4 M elements or more: plus the blocked-order copy of one chunk of tokens (64 MiB at most)
+    assert B.monarch_workspace_bytes(8192, 4096, 4096, 16, 1024, B.BF16) == 8192 * 16 * 1024 * 2 + 8192 * 4096 * 2
+    assert B.monarch_workspace_bytes(32768, 2048, 8192, 16, 512, B.BF16) == 32768 * 16 * 512 * 2 + 4096 * 8192 * 2
+    assert B.monarch_workspace_bytes(8192, 4096, 4096, 16, 1024, B.F32) == 8192 * 16 * 1024 * 4     # bf16 only
+    assert B.monarch_workspace_bytes(8192, 4096, 4096, 4, 1024, B.BF16) == 8192 * 4096 * 2           # not for 4 blocks
+    assert B.monarch_workspace_bytes(8192, 4104, 4104, 12, 1032, B.BF16) == 8192 * 12 * 1032 * 2     # not for 12 blocks
     assert B.monarch_workspace_bytes(8, 250, 256, 4, 64, B.F32) == 0          # invalid shape -> 0
     # BLAST: the whole-layer kernel needs no intermediate; packed factors add nothing
     assert B.blast_workspace_bytes(6304, 768, 768, 16, 96, B.BF16, B.BLAST_PACKED) == 0

@@ -37,6 +37,11 @@ MONARCH_CASES = [
     (37, 36, 60, 3, 9, "f32"),
     (1, 512, 512, 4, 128, "bf16"),
     (65, 1024, 1024, 16, 256, "bf16"),   # 16 blocks as in the paper's Llama settings, r' = 16
+    (600, 512, 8192, 16, 256, "bf16"),   # 4.9 M outputs: interleaved order via the blocked order and the permutation pass
+    (1100, 1024, 4096, 8, 256, "bf16"),  # ... with 8 blocks
+    (2101, 512, 2048, 16, 256, "bf16"),  # ... short rows: three tokens per workgroup of the pass, the last group ragged
+    (270, 512, 16640, 8, 128, "bf16"),   # ... q = 2080 > 2032: two segments per row, the second short
+    (1100, 1024, 4096, 4, 256, "bf16"),  # 4 blocks: scattered stores at any size
 ]
 
 
