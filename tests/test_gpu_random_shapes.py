@@ -146,3 +146,61 @@ def test_monarch_rect_random_shape(T, n_in, n_out, b1, b2, rp, order):
     Yref = oracle.monarch_rect_forward(X.f64, R.f64, L.f64, b1, b2, oracle.OUT_BLOCKED if blocked else oracle.OUT_INTERLEAVED)
     err = gu.rel_err(gu.to_f64(Y), Yref)
     assert err <= gu.TOL["bf16"], (T, n_in, n_out, b1, b2, rp, order, err)
+
+
+def _group_shapes():
+    rng = np.random.default_rng(2512)
+    out = []
+    for _ in range(12):
+        b = int(rng.choice([2, 4, 8, 16]))
+        q, p = (int(rng.integers(1, 24)) * 8 for _ in range(2))
+        r = int(rng.integers(1, 40)) * 8
+        members = int(rng.integers(2, 5))
+        T = int(rng.choice([1, 17, 64, 129, 300, 700, 1500]))
+        mode = str(rng.choice(["default", "fused12", "three"]))
+        if mode == "fused12" and (b * q) % 64:
+            mode = "default"                      # the fused kernel walks the input in chunks of 64 columns
+        out.append((T, b * q, b * p, b, r, members, mode))
+    return out
+
+
+@pytest.mark.parametrize("T,n_in,n_out,b,r,members,mode", _group_shapes())
+def test_blast_group_random_shape(T, n_in, n_out, b, r, members, mode):
+    """Grouped BLAST layers (one call for layers that share their input): every member against the
+    oracle's layer on its own factors."""
+    gu = _gu()
+    B = gu.B
+    if B.blast_group_workspace_bytes(T, n_in, n_out, b, r, members) == 0:
+        pytest.skip("no grouped execution for this shape (single-kernel size, or no matrix-core kernels)")
+    lays = [bi.blast_layer(n_in, n_out, b, r, "bf16", seed=T + n_in, layer_id=m) for m in range(members)]
+    X = bi.activations(T, n_in, "bf16", seed=n_out)
+    flags = {"fused12": B.BLAST_FUSED_STAGE12, "three": B.BLAST_THREE_KERNELS}.get(mode, 0)
+    Y = gu.to_f64(gu.run_blast_group(X, lays, flags))
+    for m, lay in enumerate(lays):
+        err = gu.rel_err(Y[:, m * n_out:(m + 1) * n_out], oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64))
+        assert err <= gu.TOL["bf16"], (T, n_in, n_out, b, r, members, mode, m, err)
+
+
+def _large_interleaved_shapes():
+    rng = np.random.default_rng(20861 + 3)
+    out = []
+    for _ in range(8):
+        b = int(rng.choice([8, 16, 32]))
+        q = int(rng.integers(8, 130)) * 8
+        p = int(rng.integers(1, 8)) * 8
+        rp = int(rng.choice([8, 16, 24]))
+        T = (4 << 20) // (b * q) + int(rng.integers(1, 200))       # just past 4 M output elements
+        out.append((T, b * p, b * q, b, b * rp))
+    return out
+
+
+@pytest.mark.parametrize("T,n_in,n_out,nb,r", _large_interleaved_shapes())
+def test_monarch_large_interleaved_output_random_shape(T, n_in, n_out, nb, r):
+    """Interleaved outputs large enough to be written in the blocked order and permuted by a second
+    pass (8 blocks and more): whole tensor against the oracle."""
+    gu = _gu()
+    lay = bi.monarch_layer(n_in, n_out, nb, r, "bf16", seed=T)
+    X = bi.activations(T, n_in, "bf16", seed=n_out)
+    Y = gu.to_f64(gu.run_monarch(X, lay, gu.B.MONARCH_TWO_KERNELS))
+    err = gu.rel_err(Y, oracle.monarch_forward(X.f64, lay.R.f64, lay.L.f64, oracle.OUT_INTERLEAVED))
+    assert err <= gu.TOL["bf16"], (T, n_in, n_out, nb, r, err)
