@@ -103,6 +103,9 @@ size_t gemm_split_scratch_bytes(int64_t M, int N, int K, int G);
 // few tokens (M <= 32): weight-streaming kernel, split-K inside the workgroup; same alignment contract
 bool skinny_gemm_supported(const GemmDesc& d);
 hipError_t launch_gemm_skinny(const GemmDesc& d, bool cvec, hipStream_t s);
+// the same kernel over tiles of 32 tokens (the weights are streamed once per tile): for products with
+// too few 64 x 64 tiles to fill the chip and a long contraction index
+bool skinny_gemm_tiled_supported(const GemmDesc& d);
 
 // Monarch (b1 input blocks, b2 output blocks, per-block rank rp; low-rank is b1 = b2 = 1) in one kernel
 // for narrow layers: the intermediate stays on chip. Needs 16 | rp, 32 | n_in/b1, 32 | b1 rp and a token

@@ -1,4 +1,6 @@
-// bf16 MFMA batched "NT" GEMM for FEW tokens (M <= 32): the weight-streaming regime, HBM-bound.
+// bf16 MFMA batched "NT" GEMM for FEW tokens (M <= 32): the weight-streaming regime, HBM-bound. Also
+// used tile by tile (32 tokens per workgroup, grid.y) for products with small weights, few 64 x 64
+// tiles and a long contraction index, where the weights then come from L2.
 //
 // With few tokens the product is a stream of the weights through the chip, so the tiling is turned
 // around: a workgroup owns 16 weight rows (output columns) and ALL tokens, and its four wavefronts
@@ -29,6 +31,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
     const int g = blockIdx.x / tiles_n;
     const int n0 = (blockIdx.x % tiles_n) * SK_BN;
     const int l16 = lane & 15, kg = lane >> 4;          // fragment row, group of 8 consecutive k (of the step's 32)
+    const int64_t m_base = (int64_t)blockIdx.y * (MT * 16);   // more tokens than one tile: grid.y walks tiles of 16 MT tokens
 
     // A fragment (16 rows x 32 k) is LOADED with four neighbouring lanes on the 64 contiguous bytes of one
     // row (lane = 4 row + piece: 16 requests of 64 bytes per instruction) and moved to the MFMA's order
@@ -44,7 +47,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
     const bf16_t* xp[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        int64_t m = mt * 16 + ld_row;
+        int64_t m = m_base + mt * 16 + ld_row;
         if (m > d.M - 1) m = d.M - 1;
         xp[mt] = (const bf16_t*)d.A + (int64_t)g * d.a_gs + m * d.a_rs;
     }
@@ -104,7 +107,8 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
     for (int id = tid; id < MT * 16 * (SK_BN / 8); id += 64 * SK_WAVES) {
         const int row = id / (SK_BN / 8), c8 = (id % (SK_BN / 8)) * 8;
         const int nn = n0 + c8;
-        if (row >= d.M || nn >= d.N) continue;
+        const int64_t mrow = m_base + row;
+        if (mrow >= d.M || nn >= d.N) continue;
         float v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = part[0][row][c8 + i];
@@ -114,7 +118,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
             for (int i = 0; i < 8; ++i) v[i] += part[w][row][c8 + i];
         if (cvec) {                                     // 8 consecutive (8-aligned) columns are 16 contiguous bytes of C
             const int64_t col = (int64_t)g * d.c_gs + (int64_t)(nn / d.c_div) * d.c_hi + (int64_t)(nn % d.c_div) * d.c_lo;
-            *(uint4*)(Cp + (int64_t)row * d.c_rs + col) =
+            *(uint4*)(Cp + mrow * d.c_rs + col) =
                 make_uint4(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]), pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7]));
         } else {
 #pragma unroll
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
                 const int ni = nn + i;
                 if (ni < d.N) {
                     const int64_t col = (int64_t)g * d.c_gs + (int64_t)(ni / d.c_div) * d.c_hi + (int64_t)(ni % d.c_div) * d.c_lo;
-                    Cp[(int64_t)row * d.c_rs + col] = float_to_bf16(v[i]);
+                    Cp[mrow * d.c_rs + col] = float_to_bf16(v[i]);
                 }
             }
         }
@@ -132,7 +136,8 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(GemmDesc d, 
 template <int MT, int D>
 hipError_t launch_skinny(const GemmDesc& d, int cvec, hipStream_t s) {
     const int tiles_n = (d.N + SK_BN - 1) / SK_BN;
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, D>), dim3((unsigned)(tiles_n * d.G)), dim3(64 * SK_WAVES), 0, s, d, tiles_n, cvec);
+    const unsigned tiles_m = (unsigned)((d.M + MT * 16 - 1) / (MT * 16));
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, D>), dim3((unsigned)(tiles_n * d.G), tiles_m), dim3(64 * SK_WAVES), 0, s, d, tiles_n, cvec);
     return hipGetLastError();
 }
 
@@ -144,7 +149,11 @@ bool skinny_gemm_supported(const GemmDesc& d) {
 
 hipError_t launch_gemm_skinny(const GemmDesc& d, bool cvec, hipStream_t s) {
     if (d.M <= 16) return launch_skinny<1, 8>(d, cvec, s);
-    return launch_skinny<2, 8>(d, cvec, s);
+    return launch_skinny<2, 8>(d, cvec, s);             // more than 32 tokens: one workgroup per 32-token tile and 16 weight rows
+}
+
+bool skinny_gemm_tiled_supported(const GemmDesc& d) {
+    return d.M <= 65535ll * 32 && (int64_t)((d.N + SK_BN - 1) / SK_BN) * d.G < (1ll << 31);
 }
 
 }  // namespace blr
