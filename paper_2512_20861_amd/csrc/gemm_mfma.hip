@@ -465,15 +465,16 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     if (d.M > 64 && tiles(128, 64) >= kFill) return launch_dma<128, 64, 2, 2>(d, s);
     if (d.N > 64 && tiles(64, 128) >= kFill) return launch_dma<64, 128, 2, 2>(d, s);
     // few tiles and a long contraction: 64 x 64 tiles, contraction index split over several workgroups
-    // Few tiles and a long contraction index, small weights: the weight-streaming kernel over tiles of
-    // 32 tokens instead of split parts plus a second kernel that adds them. A workgroup streams
-    // 96 K bytes (16 weight rows, 32 token rows) at about 55 GB/s; worth it while all rounds of
-    // workgroups together stay under about 9 us (low-rank stage 1 of the 768- and 1152-wide layers at
-    // 48 ... 1024 tokens: 11-12 us -> 8.5 us; 4096 x 1024 weights up to 128 tokens: 12-13 -> 10-11 us).
-    if (split_plan(tiles(64, 64), d.K).nsplit > 1 && skinny_gemm_tiled_supported(d)) {
+    // Few tiles and a long contraction index that would be split (two launches: the parts, then their
+    // sum), small weights: the weight-streaming kernel over tiles of 32 tokens instead, one launch.
+    // A workgroup streams 96 K bytes (16 weight rows, 32 token rows) at about 55 GB/s; worth it while
+    // all rounds of workgroups together stay under about 6.5 us (first low-rank product of the 768-
+    // and 1152-wide layers: 2 us less per call in graph replay; with K = 4096 the split parts, which
+    // put more workgroups on the stream, are as fast or faster).
+    if (d.split_scratch && split_plan(tiles(64, 64), d.K).nsplit > 1 && skinny_gemm_tiled_supported(d)) {
         const int64_t wgs = ((d.M + 31) / 32) * ((d.N + 15) / 16) * d.G;
         const double est_us = (double)((wgs + 255) / 256) * (d.K * 96 / 55e3 + 1.0);
-        if (est_us <= 9.0) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
+        if (est_us <= 6.5) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
     }
     if (d.split_scratch && split_plan(tiles(64, 64), d.K).nsplit > 1) return launch_dma<64, 64, 2, 2>(d, s, true);
     if (tiles(64, 64) >= kFill || (d.M <= 64 && d.N <= 64)) return launch_dma<64, 64, 2, 2>(d, s);
