@@ -96,8 +96,8 @@ typedef void* blr_stream;      /* a hipStream_t */
  * X[T][n_in]; R[b][r][p] (the paper's first stored factor, middle dimension ordered b2-fastest);
  * L[b][q][r] (second stored factor, innermost dimension ordered r'-fastest then b1); Y[T][n_out].
  * r is the width of one middle block (r = r'*b); nblocks must divide n_in, n_out and r.
- * workspace: at least blr_monarch_workspace_bytes(...) bytes (holds Z'; for interleaved bf16 outputs of
- * 4 M elements and more with 8 or more blocks also a blocked-order copy of up to 64 MiB of Y).
+ * workspace: at least blr_monarch_workspace_bytes(...) bytes (holds Z'; for large interleaved bf16
+ * outputs with 8 or more blocks also a blocked-order copy of up to 64 MiB of Y).
  */
 size_t     blr_monarch_workspace_bytes(int64_t T, int n_in, int n_out, int nblocks, int r, blr_dtype dt);
 blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void* Y,

@@ -143,7 +143,7 @@ bool monarch_takes_fused(int64_t T, int n_in, int n_out, int b1, int b2, int rp,
 
 // The interleaved output order through 2-byte stores at stride b2 costs stage 2 up to twice its time
 // on large outputs (2048 -> 8192, b = 16, T = 8192: 222 us against 83 us in the blocked order). From
-// 4 M output elements on, stage 2 therefore writes the blocked order into the workspace, in chunks
+// 4 M output elements on (2 M for wide rows in 16 and more blocks; graph-replay timings), stage 2 therefore writes the blocked order into the workspace, in chunks
 // of tokens that stay in the memory-side cache, and a permutation pass (both sides 16-byte
 // coalesced, about the time of a copy of the chunk) produces the interleaved order. With 8 blocks the
 // two ways are level, with 4 and 2 the scattered stores are faster (8- and 4-byte gaps between a
@@ -152,7 +152,9 @@ constexpr int kInterleavePassMinBlocks = 8;
 constexpr int64_t kInterleavePassMinElems = 4ll << 20;
 constexpr size_t kInterleaveChunkBytes = 64u << 20;
 bool monarch_interleave_pass_shape(int64_t T, int n_out, int b2, blr_dtype dt) {
-    return dt == BLR_BF16 && b2 >= kInterleavePassMinBlocks && T * n_out >= kInterleavePassMinElems && monarch_interleave_supported(T, n_out, b2);
+    // with 16 and more blocks and rows of 2048 and more elements the pass already pays from 2 M outputs on
+    const int64_t min_elems = b2 >= 16 && n_out >= 2048 ? kInterleavePassMinElems / 2 : kInterleavePassMinElems;
+    return dt == BLR_BF16 && b2 >= kInterleavePassMinBlocks && T * n_out >= min_elems && monarch_interleave_supported(T, n_out, b2);
 }
 int64_t monarch_interleave_chunk(int64_t T, int n_out) {
     int64_t c = (int64_t)(kInterleaveChunkBytes / ((size_t)n_out * 2)) / 256 * 256;
