@@ -42,6 +42,7 @@ MONARCH_CASES = [
     (2101, 512, 2048, 16, 256, "bf16"),  # ... short rows: three tokens per workgroup of the pass, the last group ragged
     (270, 512, 16640, 8, 128, "bf16"),   # ... q = 2080 > 2032: two segments per row, the second short
     (1100, 1024, 4096, 4, 256, "bf16"),  # 4 blocks: scattered stores at any size
+    (1030, 512, 2048, 64, 512, "bf16"),  # 64 blocks of 32 outputs: the pass with its shortest rows per block
 ]
 
 
