@@ -138,7 +138,16 @@ bool monarch_fused_possible(int64_t T, int n_in, int n_out, int b1, int b2, int 
 bool monarch_takes_fused(int64_t T, int n_in, int n_out, int b1, int b2, int rp, blr_dtype dt, unsigned flags) {
     if (!monarch_fused_possible(T, n_in, n_out, b1, b2, rp, dt, flags)) return false;
     if (flags & BLR_MONARCH_FUSED) return true;
-    return T > 32 && T <= kFusedMonarchMaxTokens && monarch_fused_lds_bytes(T, n_in, n_out, b1, b2, rp) <= kFusedMonarchMaxLds;
+    if (T <= 32) return false;
+    if (T <= kFusedMonarchMaxTokens && monarch_fused_lds_bytes(T, n_in, n_out, b1, b2, rp) <= kFusedMonarchMaxLds) return true;
+    // Wider layers, whose token tile takes more than half of LDS (one workgroup per compute unit): the
+    // single kernel still wins while the call is one round of workgroups, with 16 or more output
+    // blocks (2048 x 2048, b = 16, r' = 16: 8.8 / 10.0 / 12.5 us against 12.7 / 11.2 / 14.6 us at
+    // 64 / 256 / 512 tokens; 1024 x 1024: 6.3-8.4 us against 9.6-14.1 us) and, for any number of
+    // blocks, up to 64 tokens (8.0-8.9 us against 10.4-11.3 us); at 8 blocks and 197-512 tokens the
+    // two GEMMs are level or up to 8 % faster and stay.
+    const int64_t base = ((T + 31) / 32) * b2;
+    return base <= 256 && (b2 >= 16 || T <= 64);
 }
 
 // The interleaved output order through 2-byte stores at stride b2 costs stage 2 up to twice its time

@@ -37,6 +37,8 @@ MONARCH_CASES = [
     (37, 36, 60, 3, 9, "f32"),
     (1, 512, 512, 4, 128, "bf16"),
     (65, 1024, 1024, 16, 256, "bf16"),   # 16 blocks as in the paper's Llama settings, r' = 16
+    (300, 2048, 2048, 16, 256, "bf16"),  # wide layer, one round of workgroups: the single kernel with one workgroup per compute unit
+    (50, 1536, 1536, 8, 256, "bf16"),    # ... up to 64 tokens with any number of blocks
     (600, 512, 8192, 16, 256, "bf16"),   # 4.9 M outputs: interleaved order via the blocked order and the permutation pass
     (1100, 1024, 4096, 8, 256, "bf16"),  # ... with 8 blocks
     (2101, 512, 2048, 16, 256, "bf16"),  # ... short rows: three tokens per workgroup of the pass, the last group ragged
