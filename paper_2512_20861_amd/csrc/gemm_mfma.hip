@@ -474,10 +474,23 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     if (d.split_scratch && split_plan(tiles(64, 64), d.K).nsplit > 1 && skinny_gemm_tiled_supported(d)) {
         const int64_t wgs = ((d.M + 31) / 32) * ((d.N + 15) / 16) * d.G;
         const double est_us = (double)((wgs + 255) / 256) * (d.K * 96 / 55e3 + 1.0);
-        if (est_us <= 6.5) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
+        // ... or under about 9 us when one round of workgroups covers at least half of the chip (4096 x 1024
+        // weights at 64 ... 128 tokens: 10 us against 12-13 us; with 32 workgroups the split parts win)
+        if (est_us <= 6.5 || (wgs >= 128 && wgs <= 256 && est_us <= 9.0)) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
     }
     if (d.split_scratch && split_plan(tiles(64, 64), d.K).nsplit > 1) return launch_dma<64, 64, 2, 2>(d, s, true);
     if (tiles(64, 64) >= kFill || (d.M <= 64 && d.N <= 64)) return launch_dma<64, 64, 2, 2>(d, s);
+    // Nothing fills the chip (a product of some tens of tokens with weights that are not split, e.g.
+    // the dense reference at 33 ... 96 tokens): the weight-streaming kernel over tiles of 32 tokens puts
+    // every compute unit on the stream, where the few tiles below would walk the whole contraction
+    // index at about 0.17 us per step of 32 (dense 4096 x 4096 at 48 tokens: 29.6 -> 17.3 us;
+    // 8192 -> 2048: 55.5 -> 17.4 us). Taken when its estimate (rounds of workgroups x the time to
+    // stream 96 K bytes at 55 GB/s) is below that walk by a margin (level estimates went to the tiles).
+    if (skinny_gemm_tiled_supported(d)) {
+        const int64_t wgs = ((d.M + 31) / 32) * ((d.N + 15) / 16) * d.G;
+        const double est_us = (double)((wgs + 255) / 256) * (d.K * 96 / 55e3 + 1.0);
+        if (est_us < 0.85 * ((d.K + 31) / 32 * 0.17 + 3.0)) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
+    }
     // too small to fill the chip with any tile: fewest, largest tiles that fit the shape
     if (d.M > 64 && d.N > 64) return tiles(64, 64) >= 64 ? launch_dma<64, 64, 2, 2>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
     if (d.M > 64) return launch_dma<128, 64, 2, 2>(d, s);
