@@ -459,7 +459,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     auto tiles = [&](int bm, int bn) { return (int64_t)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.G; };
     // large problems: 256 x 256 tiles on 8 wavefronts (half the LDS and L2 traffic per FLOP of 128 x 128)
     // (from 160 tiles on: the same scan as for kFill below, on Monarch, BLAST and low-rank layers at
-    // 300 ... 6144 tokens, had 160 ahead of 256 by 5-17 % at the token counts where they differ)
+    // 300 ... 6144 tokens, had 160 ahead of 256 by 5-17 % at the token counts where they differ, and ahead of 128 and 96 on balance)
     if (d.M > 128 && d.N > 128 && d.K > kSmallK && tiles(256, 256) >= 160) return launch_dma<256, 256, 2, 4>(d, s);
     // otherwise the largest tile that still gives every compute unit a workgroup
     // 160 of the 256 compute units: a scan of token counts 33 ... 4096 on eight weight shapes had 160
