@@ -4,10 +4,14 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1] [--sweep] [--no-cpu]
 
 A step is one forward call of the workload's layer (every kernel of the call) on inputs that are
-already resident in HBM. The default workload is the ViT-B-width BLAST layer (768x768, b=16,
-r=96, T=6304, bf16). Prints ONE JSON line on stdout. `--sweep` additionally measures every
-configuration at every T against the same-shape dense GEMM and writes the table to
-sweep.json in the results folder (OUT_DIR below) and to stderr.
+already resident in HBM. The default (headline) workload is the largest Llama-7B-shaped layer of the
+token sweep the metric is quoted on: Monarch 4096 -> 11008, nblocks = 4, r = 1024, T = 8192, bf16.
+Prints ONE JSON line on stdout; by default the line also carries `sweep`: the ViT-B-width BLAST
+layer and the four Llama-7B-shaped layers at T = 1 ... 8192, each with its time (median of graph
+replays), tokens/s, roofline bound and fraction, the same-shape dense GEMM, the cold-cache time for
+T <= 128 and a short run of the CPU oracle (`--no-sweep` leaves it out). `--sweep` widens that to
+the low-rank layers and to the forced executions of every call and also writes the table to
+sweep.json in the results folder (OUT_DIR below).
 
 Static factors are re-laid out once before the timed region (the paper's offline weight
 re-layout); the timed call receives the packed factors.
@@ -44,14 +48,14 @@ def to_dev(ht):
 class GpuLayer:
     """Device-resident factors of one layer plus a closure that enqueues its forward."""
 
-    def __init__(self, cfg, T, seed=bi.BASE_SEED, random_x=True):
+    def __init__(self, cfg, T, seed=bi.BASE_SEED, random_x=True, host=None):
         import torch
         from paper_2512_20861_amd import binding as B
         self.B, self.cfg, self.T = B, cfg, T
         self.op, self.n_in, self.n_out = cfg["op"], cfg["n_in"], cfg["n_out"]
         self.dtype = cfg["dtype"]
         td = torch.bfloat16 if self.dtype == "bf16" else torch.float32
-        lay = bi.make_layer(cfg, seed)
+        lay = host if host is not None else bi.make_layer(cfg, seed)
         self.host = lay
         # activations: values do not affect run time; draw them on the device for the big sweeps
         if random_x:
@@ -120,10 +124,11 @@ def time_calls(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
-def time_graph(make_call, steps, warmup, replays=3):
-    """Mean milliseconds per call with the `steps` calls captured once into a HIP graph and replayed:
-    the host enqueues one graph launch, so the figure is the GPU's own back-to-back rate rather than
-    the speed of the Python launch loop. `make_call()` is evaluated on the capture stream."""
+def time_graph(make_call, steps, warmup, replays=5):
+    """Milliseconds per call with the `steps` calls captured once into a HIP graph and replayed: the
+    host enqueues one graph launch, so the figure is the GPU's own back-to-back rate rather than the
+    speed of the Python launch loop. Every replay is exactly `steps` calls between two events on the
+    launch stream; the MEDIAN replay is reported. `make_call()` is evaluated on the capture stream."""
     import torch
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -140,15 +145,16 @@ def time_graph(make_call, steps, warmup, replays=3):
             call()
     g.replay()
     torch.cuda.synchronize()
-    best = 1e30
+    times = []
     for _ in range(replays):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         g.replay()
         e1.record()
         torch.cuda.synchronize()
-        best = min(best, e0.elapsed_time(e1) / steps)
-    return best
+        times.append(e0.elapsed_time(e1) / steps)
+    times.sort()
+    return times[len(times) // 2]
 
 
 def stage_times(layer, steps, warmup):
@@ -164,10 +170,11 @@ def stage_times(layer, steps, warmup):
         raise
 
 
-def cpu_baseline(cfg, T_cpu):
-    """The fp64 oracle as it stands, timed on this machine's host cores (baseline only)."""
+def cpu_baseline(cfg, T_cpu, seconds=10.0, lay=None):
+    """The fp64 oracle as it stands, timed on this machine's host cores (baseline only): about `seconds`
+    of repeated passes over the first T_cpu tokens of the workload."""
     import oracle
-    lay = bi.make_layer(cfg)
+    lay = lay if lay is not None else bi.make_layer(cfg)
     X = bi.activations(T_cpu, cfg["n_in"], cfg["dtype"], scale=cfg["x_scale"])
     nthreads = oracle.binding.default_threads()
     if cfg["op"] == "monarch":
@@ -178,13 +185,13 @@ def cpu_baseline(cfg, T_cpu):
         fn = lambda: oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64, nthreads=nthreads)
     fn()                                                 # warm-up
     passes, t_start = 0, time.perf_counter()
-    while True:                                          # about 10 s of CPU work, at least 3 passes
+    while True:                                          # about `seconds` of CPU work
         fn()
         passes += 1
         elapsed = time.perf_counter() - t_start
-        if (elapsed >= 10.0 and passes >= 3) or elapsed >= 30.0:
+        if (elapsed >= seconds and passes >= min(3, seconds)) or elapsed >= 3 * seconds:
             break
-    return {"value": T_cpu * passes / elapsed, "unit": "tokens/s", "cores": nthreads, "kind": "oracle",
+    return {"value": T_cpu * passes / elapsed, "unit": "tokens/s", "cores": min(nthreads, T_cpu), "kind": "oracle",
             "sample": f"{passes} passes over {T_cpu} of the workload's tokens ({elapsed:.1f} s of fp64 oracle time "
                       f"after one warm-up pass), std::thread over tokens"}
 
@@ -258,17 +265,25 @@ def time_cold(make_calls, steps, warmup):
     return time_graph(make_call, steps, warmup)
 
 
-def run_sweep(steps, warmup, only=None):
+DEFAULT_SWEEP = ("C1", "C2a", "C2b", "C3a", "C3b")      # what the default line carries
+FULL_SWEEP = DEFAULT_SWEEP + ("LRa", "LRb")
+
+
+def run_sweep(steps, warmup, names, variants=False, cpu_seconds=0.0, write=False):
+    """Every configuration of `names` at every T of its sweep: time of the call (median of graph
+    replays), its stages, the same-shape dense GEMM, roofline floor and fraction (algorithmic bytes or
+    FLOPs of the whole call / time / peak), cold-cache time for T <= 128 (factors rotated through
+    >= 512 MB of distinct copies), and the CPU oracle over a few tokens. `variants` adds the forced
+    executions (blocked Monarch output, both large-rank BLAST executions)."""
     import torch
     from paper_2512_20861_amd import binding as B
     rows = []
-    for name in ("C1", "C2a", "C2b", "C3a", "C3b", "LRa", "LRb"):
-        if only and name not in only:
-            continue
+    for name in names:
         cfg = bi.CONFIGS[name]
+        host = bi.make_layer(cfg)
         W = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
         for T in cfg["T"]:
-            layer = GpuLayer(cfg, T)
+            layer = GpuLayer(cfg, T, host=host)
             ms = time_graph(layer.prepared, steps, warmup)
             st = stage_times(layer, steps, warmup)
             Yd = torch.empty_like(layer.Y)
@@ -279,7 +294,7 @@ def run_sweep(steps, warmup, only=None):
             ms_alt = {}
             if cfg["op"] == "monarch":                      # the paper's optimisation 3: blocked output order, no final permutation
                 ms_alt["blocked_output"] = time_graph(lambda: layer.prepared(B.MONARCH_OUT_BLOCKED), steps, warmup)
-            if cfg["op"] == "blast" and st is not None:     # both executions for large ranks, forced
+            if variants and cfg["op"] == "blast" and st is not None:     # both executions for large ranks, forced
                 for key, fl in (("fused_stage12", B.BLAST_FUSED_STAGE12), ("three_kernels", B.BLAST_THREE_KERNELS)):
                     ws_alt = torch.empty(max(B.blast_workspace_bytes(T, cfg["n_in"], cfg["n_out"], cfg["b"], cfg["r"], B.BF16,
                                                                      layer.flags | fl), 16), dtype=torch.uint8, device="cuda")
@@ -297,23 +312,27 @@ def run_sweep(steps, warmup, only=None):
                 cold = {"ms": ms_cold, "dense_ms": dense_cold, "frac_of_floor": max(mem, mfma) / (ms_cold * 1e-3),
                         "dense_frac_of_floor": max(dmem, dmfma) / (dense_cold * 1e-3), "factor_copies": len(copies)}
                 del copies, Ws
-            row = {"config": name, "op": cfg["op"], "T": T, "ms": ms, "ms_variants": ms_alt, "cold": cold, "tokens_per_s": T / (ms * 1e-3),
-                   "stage_ms": st, "floor_hbm_us": mem * 1e6, "floor_mfma_us": mfma * 1e6,
-                   "bound": "hbm" if mem >= mfma else "mfma", "frac_of_floor": max(mem, mfma) / (ms * 1e-3),
-                   "dense_ms": ms_dense, "dense_frac_of_floor": max(dmem, dmfma) / (ms_dense * 1e-3),
-                   "speedup_vs_dense": ms_dense / ms}
+            row = {"config": name, "op": cfg["op"], "T": T, "ms": ms, "tokens_per_s": T / (ms * 1e-3),
+                   "bound": "hbm" if mem >= mfma else "mfma", "frac": max(mem, mfma) / (ms * 1e-3),
+                   "floor_hbm_us": mem * 1e6, "floor_mfma_us": mfma * 1e6, "stage_ms": st,
+                   "dense_ms": ms_dense, "dense_frac": max(dmem, dmfma) / (ms_dense * 1e-3),
+                   "speedup_vs_dense": ms_dense / ms, "ms_variants": ms_alt, "cold": cold}
+            if cpu_seconds > 0:
+                cb = cpu_baseline(cfg, min(T, 64), cpu_seconds, host)
+                row["cpu_baseline"] = {"tokens_per_s": cb["value"], "cores": cb["cores"], "T_cpu": min(T, 64)}
             rows.append(row)
             log(f"{name:4s} {cfg['op']:7s} T={T:5d}  {ms*1e3:9.1f} us  stages={None if st is None else [round(x*1e3,1) for x in st]}  "
-                f"floor {max(mem, mfma)*1e6:7.1f} us ({row['bound']}) frac {row['frac_of_floor']:.3f} | "
-                f"dense {ms_dense*1e3:9.1f} us frac {row['dense_frac_of_floor']:.3f} | speedup {row['speedup_vs_dense']:.2f}x"
+                f"floor {max(mem, mfma)*1e6:7.1f} us ({row['bound']}) frac {row['frac']:.3f} | "
+                f"dense {ms_dense*1e3:9.1f} us frac {row['dense_frac']:.3f} | speedup {row['speedup_vs_dense']:.2f}x"
                 + "".join(f" | {k} {v*1e3:.1f} us" for k, v in ms_alt.items())
                 + (f" | cold {cold['ms']*1e3:.1f} us (frac {cold['frac_of_floor']:.3f}), dense cold {cold['dense_ms']*1e3:.1f} us" if cold else ""))
             del layer, Yd
         del W
         torch.cuda.empty_cache()
-    os.makedirs(os.path.join(ROOT, OUT_DIR), exist_ok=True)
-    with open(os.path.join(ROOT, OUT_DIR, "sweep.json"), "w") as f:
-        json.dump(rows, f, indent=1)
+    if write:
+        os.makedirs(os.path.join(ROOT, OUT_DIR), exist_ok=True)
+        with open(os.path.join(ROOT, OUT_DIR, "sweep.json"), "w") as f:
+            json.dump(rows, f, indent=1)
     return rows
 
 
@@ -471,14 +490,18 @@ def run_chain(args, op):
     return out
 
 
+HEADLINE = "C2b"        # Monarch 4096 -> 11008 at the last T of its sweep (8192): the largest layer of the sweep
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C1", choices=sorted(bi.CONFIGS) + ["C4-monarch", "C4-blast"])
+    ap.add_argument("--workload", default=HEADLINE, choices=sorted(bi.CONFIGS) + ["C4-monarch", "C4-blast"])
     ap.add_argument("--tokens", type=int, default=0, help="override T of the workload")
-    ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="the wider sweep (low-rank layers, forced executions); also written to sweep.json")
+    ap.add_argument("--no-sweep", action="store_true", help="headline workload only")
     ap.add_argument("--table3", action="store_true", help="also time every layer shape of the paper's Table 3")
     ap.add_argument("--table3-scale", type=int, default=1, help="sequences per call for --table3 (token count x this)")
     ap.add_argument("--sweep-configs", default="", help="comma-separated subset of the configurations for --sweep")
@@ -515,12 +538,13 @@ def main():
     torch.cuda.synchronize()
     stages = stage_times(layer, args.steps, args.warmup)
     roof = dominant_roofline(layer, ms, stages)
-    try:                                                 # HBM bytes per launch from the committed counter runs
+    try:                                                 # HBM bytes per launch of that kernel from the committed counter runs
         with open(os.path.join(ROOT, "paper_2512_20861_amd", "measured_traffic.json")) as f:
             entry = json.load(f).get(f"{args.workload}:{T}")
         if entry:
             roof["traffic"] = entry["bytes"]
             roof["traffic_source"] = entry["profile"]
+            roof["traffic_kernel"] = entry["kernel"]
     except OSError:
         pass
 
@@ -550,11 +574,14 @@ def main():
         out["copy_calibration"] = {"read_bytes": src.numel() * 2, "write_bytes": dst.numel() * 2, "launches": 5}
     if not args.no_cpu:
         T_cpu = min(T, {"C1": 6304, "C0": 8}.get(args.workload, 512))
-        out["cpu_baseline"] = cpu_baseline(cfg, T_cpu)
+        out["cpu_baseline"] = cpu_baseline(cfg, T_cpu, lay=layer.host)
     if args.table3:
         out["table3"] = run_table3(max(args.steps // 4, 20), max(args.warmup // 2, 5), max(args.table3_scale, 1))
-    if args.sweep:
-        out["sweep"] = run_sweep(max(args.steps // 4, 20), max(args.warmup // 2, 5), set(filter(None, args.sweep_configs.split(","))))
+    if not args.no_sweep:
+        only = set(filter(None, args.sweep_configs.split(",")))
+        names = [n for n in (FULL_SWEEP if args.sweep else DEFAULT_SWEEP) if not only or n in only]
+        out["sweep"] = run_sweep(max(args.steps // 4, 20), max(args.warmup // 2, 5), names, variants=args.sweep,
+                                 cpu_seconds=0.0 if args.no_cpu else 0.7, write=args.sweep)
     print(json.dumps(out), flush=True)
 
 

@@ -59,16 +59,9 @@ typedef void* blr_stream;      /* a hipStream_t */
 /* flag of blr_blast_forward: the `V` argument is the buffer written by blr_blast_pack (the one-time
  * offline weight re-layout of paper Section 4, optimisations 1 and 5) and `S` is ignored. */
 #define BLR_BLAST_PACKED            2u
-/* flag of every forward: run the portable scalar-ALU kernels even where an MFMA kernel exists
- * (used by the tests to cross-check the two GPU paths). */
-#define BLR_FORCE_GENERIC           0x100u
-/* measurement aids of the two BLR forwards: enqueue only the kernels up to and including the one
- * that writes the workspace intermediate (FIRST), or only the kernel that consumes it (LAST; the
- * workspace must hold the intermediate of an earlier call with identical arguments). Mutually
- * exclusive; BLR_ERR_UNSUPPORTED where the call is a single kernel. Where BLAST walks the tokens in
- * several chunks the workspace holds one chunk only, so LAST is then good for timing, not for values. */
-#define BLR_ONLY_FIRST_STAGE        0x200u
-#define BLR_ONLY_LAST_STAGE         0x400u
+/* Flag bits 0x100, 0x200 and 0x400 of every forward are test and measurement aids (portable kernels only;
+ * only the first / only the last stage of a multi-kernel call). They are declared in blr_measure.h and
+ * are not needed by an application. */
 /* flags of blr_blast_forward for layers too large for the single-kernel path. Two executions exist:
  * (a) stage 1 and the coupling fused in one kernel (Z stays on chip; the paper's optimisation 4 with
  * the coupling on the matrix cores) followed by the stage-3 GEMM, and (b) three kernels over
@@ -114,7 +107,7 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
  *   Y[t][o(k,j)]       = sum_m Z'[t][k][m] * L[k][j][m],   o = j*b2+k (default) or k*q+j (BLR_MONARCH_OUT_BLOCKED)
  * R[b1][r'*b2][p], L[b2][q][b1*r'] (the same two storage orders as blr_monarch_forward, which is the
  * case b1 = b2 = nblocks, r' = r/nblocks). b_in must divide n_in and b_out must divide n_out.
- * flags: BLR_MONARCH_OUT_BLOCKED, BLR_FORCE_GENERIC, BLR_ONLY_FIRST_STAGE, BLR_ONLY_LAST_STAGE.
+ * flags: BLR_MONARCH_OUT_BLOCKED, BLR_MONARCH_FUSED, BLR_MONARCH_TWO_KERNELS.
  * workspace: at least blr_monarch_rect_workspace_bytes(...) bytes (holds Z', T*b1*b2*r' elements).
  */
 size_t     blr_monarch_rect_workspace_bytes(int64_t T, int n_in, int n_out, int b_in, int b_out, int r_block, blr_dtype dt);
@@ -133,13 +126,28 @@ blr_status blr_monarch_permute_first_factor(const void* R, void* Rp, int n_in, i
                                             blr_dtype dt, blr_stream stream);
 
 /*
+ * One-time re-layout that turns `members` Monarch layers of one shape (n_in, n_out, nblocks, r) which
+ * read the same X into ONE layer with b_in = nblocks, b_out = members * nblocks, r_block = r / nblocks
+ * for blr_monarch_rect_forward (paper Section 2.1 "Monarch": the general b2 x b1 block form; the q, k, v
+ * or gate, up projections of a decoder layer, Section 5). With b = nblocks, r' = r / b:
+ *   R_group[l][rho*(members*b) + m*b + k][:] = R_stack[m][l][rho*b + k][:],   m < members.
+ * R_stack[members][b][r][p] holds the members' first factors one after the other, R_group is
+ * [b][members*r][p]; they must not overlap. The second factors need no re-layout: the members' L one
+ * after the other are L_group[members*b][q][r]. Output block m*b + k of the grouped layer is output
+ * block k of member m, so with BLR_MONARCH_OUT_BLOCKED member m's result (in its own blocked order)
+ * occupies columns m*n_out ... (m+1)*n_out - 1 of Y[T][members*n_out].
+ */
+blr_status blr_monarch_group_first_factor(const void* R_stack, void* R_group, int n_in, int nblocks, int r, int members,
+                                          blr_dtype dt, blr_stream stream);
+
+/*
  * Low-rank forward (paper Section 2.1 "Low-Rank (LR)": W = V U, Y = (X V) U; Section 3 uses it as the
  * compute-bound structured baseline; Appendix "Full Fusion" discusses its single-kernel form):
  *   Z[t][c] = sum_a X[t][a] * V[c][a],   Y[t][o] = sum_c Z[t][c] * U[o][c].
  * X[T][n_in]; V[r][n_in] and U[n_out][r] are the paper's factors stored transposed, so that both
  * contraction indices are contiguous (a one-time offline transposition of static weights);
  * Y[T][n_out]. workspace: at least blr_lowrank_workspace_bytes(...) bytes (holds Z, T*r elements).
- * flags: BLR_FORCE_GENERIC, BLR_ONLY_FIRST_STAGE, BLR_ONLY_LAST_STAGE. Errors as for the other
+ * flags: BLR_MONARCH_FUSED, BLR_MONARCH_TWO_KERNELS. Errors as for the other
  * forwards (BLR_ERR_INVALID_ARG for null factors, non-positive sizes, pointers not 16-byte aligned,
  * unknown flags; BLR_ERR_WORKSPACE; T == 0 returns BLR_OK without launching).
  */

@@ -12,7 +12,7 @@ down) write the BLOCKED output order and their consumer reads it with a first fa
 once at set-up (the paper's optimisation 3), so no interleaving permutation is ever executed there.
 There the linears that share an input (q, k, v; gate, up) also run as ONE call each: n Monarch layers of
 equal shape are one general Monarch layer with n * nblocks output blocks once the rows of their
-first factors are interleaved (done once at set-up), which turns 2 n launch-bound GEMMs into two
+first factors are interleaved (done once at set-up by blr_monarch_group_first_factor), which turns 2 n launch-bound GEMMs into two
 larger ones; their outputs lie side by side in one tensor and the glue reads them as column slices.
 In an all-BLAST chain the same linears run as one grouped BLAST call each (stages 1 and 2 on the
 members' concatenated rank indices, one stage-3 product per member).
@@ -84,10 +84,9 @@ class _MonarchGroup:
         assert all(m.op == "monarch" and (m.n_in, m.n_out, m.r, m.nb, m.dt) == (m0.n_in, m0.n_out, m0.r, m0.nb, m0.dt) for m in members)
         self.n, self.n_in, self.n_out, self.nb, self.dt = len(members), m0.n_in, m0.n_out, m0.nb, m0.dt
         self.rp = m0.r // m0.nb
-        b, p = self.nb, m0.n_in // m0.nb
-        # [layer][l][rho][k][a] -> [l][rho][layer][k][a]
-        R = torch.stack([m.R.reshape(b, self.rp, b, p) for m in members], dim=0)
-        self.R = R.permute(1, 2, 0, 3, 4).contiguous().reshape(b, self.rp * self.n * b, p)
+        # the members' first factors one after the other -> the grouped layer's first factor (library call);
+        # the second factors one after the other ARE the grouped layer's second factor
+        self.R = B.monarch_group_first_factor(torch.stack([m.R for m in members], dim=0).contiguous(), m0.n_in, m0.nb, m0.r)
         self.L = torch.cat([m.L for m in members], dim=0).contiguous()
         self.flags = B.MONARCH_OUT_BLOCKED
 
@@ -194,25 +193,27 @@ class DeviceChain:
         """Zero-argument callables (arguments marshalled once) on the stream that is current now."""
         return [B.prepared(*args) for _, args in self.call_list()]
 
-    def forward(self, x0, record=False):
+    def forward(self, x0, record=False, rows=None):
         """Run the chain on x0 [T][hidden] (device tensor); returns h. With record=True also returns, per
         call label, a copy of the tensor that call wrote and of the tensor it read (a grouped call is
-        recorded under the labels of its member linears, each with its own slice of the output)."""
+        recorded under the labels of its member linears, each with its own slice of the output);
+        `rows` (an index tensor) restricts the copies to those token rows."""
         self.h.copy_(x0)
         taps = {}
+        keep = (lambda t: t.clone()) if rows is None else (lambda t: t[rows].clone())
         for label, args in self.call_list():
             if record:
-                src = args[1].clone()
+                src = keep(args[1])
             args[0](*args[1:])
             if record:
                 if args[0] in (B.monarch_rect_forward, B.blast_group_forward):
                     li, grp = label.split(".")
                     for name, part in zip(("q", "k", "v") if grp == "qkv" else ("gate", "up"),
                                           (self.q, self.k, self.v) if grp == "qkv" else (self.g, self.u)):
-                        taps[f"{li}.{name}"] = (src, part.clone())
+                        taps[f"{li}.{name}"] = (src, keep(part))
                     continue
                 out = {B.rmsnorm: lambda a: a[2], B.sum3_scaled: lambda a: a[4], B.silu_mul: lambda a: a[3],
                        B.residual_add_rmsnorm: lambda a: a[1], B.monarch_forward: lambda a: a[4],
                        B.blast_forward: lambda a: a[5]}[args[0]](args)
-                taps[label] = (src, out.clone())
+                taps[label] = (src, keep(out))
         return (self.h, taps) if record else self.h

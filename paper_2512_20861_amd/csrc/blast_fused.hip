@@ -406,12 +406,8 @@ namespace {
 template <int TT>
 hipError_t launch_stage12_inst(const void* X, const void* Va, const void* Sp, void* A,
                                int64_t T, int n_in, int b, int r, hipStream_t s) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)blast_stage12_kernel<TT>, hipFuncAttributeMaxDynamicSharedMemorySize, StCfg<TT>::LDS);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_limit;
+    if (hipError_t e = lds_limit.set({(const void*)blast_stage12_kernel<TT>}, StCfg<TT>::LDS); e != hipSuccess) return e;
     const int tiles_t = (int)((T + TT - 1) / TT), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
     hipLaunchKernelGGL(blast_stage12_kernel<TT>, dim3((unsigned)nblk), dim3(512), StCfg<TT>::LDS, s,
@@ -431,12 +427,8 @@ hipError_t launch_blast_stage12(const void* X, const void* Va, const void* Sp, v
 template <int TNT>
 static hipError_t launch_coupling_inst(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
     constexpr int lds = TR * (TNT * 32 + 8);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)blast_coupling_kernel<TNT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_limit;
+    if (hipError_t e = lds_limit.set({(const void*)blast_coupling_kernel<TNT>}, lds); e != hipSuccess) return e;
     const int tiles_t = (int)((T + TNT - 1) / TNT), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
     hipLaunchKernelGGL(blast_coupling_kernel<TNT>, dim3((unsigned)nblk), dim3(512), lds, s,
@@ -788,14 +780,10 @@ size_t blast_uf_bytes(int n_out, int b, int r) {
 template <int NT, int KG, int NPT>
 static hipError_t launch_full_inst(const void* X, const void* Sp, const void* Vf, const void* Uf, void* Y,
                                    int64_t T, int n_in, int n_out, int b, int r, hipStream_t s) {
-    static bool attr_set = false;
+    static LdsLimitOnce lds_limit;
     const int lds = full_fusion_lds_bytes(n_in, n_out, r);
     auto kern = blast_full_kernel<NT, KG, NPT>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = lds_limit.set({(const void*)kern}, 160 * 1024); e != hipSuccess) return e;
     const unsigned nblk = (unsigned)((T + FT - 1) / FT);
     hipLaunchKernelGGL(kern, dim3(nblk), dim3(FTHREADS), lds, s, (const bf16_t*)X, (const bf16_t*)Sp,
                        (const bf16_t*)Vf, (const bf16_t*)Uf, (bf16_t*)Y, T, n_in, n_out, b, r);

@@ -1,5 +1,6 @@
 // C-ABI front end: argument validation, workspace planning, kernel selection. Host code only.
 #include "../../include/blr.h"
+#include "../../include/blr_measure.h"
 #include "blr_common.h"
 #include <algorithm>
 
@@ -297,6 +298,8 @@ static blr_status blast_run(const void* X, const void* U, const void* S, const v
         return last ? run_stage3(0, T, false) : BLR_OK;
     }
 
+    // one kernel: there are no stages to select, and a group is never packed for it (checked before anything is enqueued)
+    if (pl.path == BlastPlan::MFMA_FULL && (!first || !last || members != 1)) return BLR_ERR_UNSUPPORTED;
     const unsigned char* pack = (const unsigned char*)V;
     if (!(flags & BLR_BLAST_PACKED)) {
         pack = ws + pl.off_pack;
@@ -308,10 +311,8 @@ static blr_status blast_run(const void* X, const void* U, const void* S, const v
     const PackLayout pk = pack_layout(n_in, n_out, b, r);
     const void* Sp = pack + pk.off_Sp;
     const void* Vt = pack + pk.off_Vt;
-    if (pl.path == BlastPlan::MFMA_FULL) {
-        if (!first || !last || members != 1) return BLR_ERR_UNSUPPORTED;   // one kernel: there are no stages to select
+    if (pl.path == BlastPlan::MFMA_FULL)
         return from_hip(launch_blast_full(X, Sp, pack + pk.off_Vf, pack + pk.off_Uf, Y, T, n_in, n_out, b, r, s));
-    }
     if (pl.path == BlastPlan::MFMA_STAGE12) {
         if (first) {
             blr_status st = from_hip(launch_blast_stage12(X, pack + pk.off_Va, Sp, Aws, T, n_in, b, r, s));
@@ -446,6 +447,14 @@ blr_status blr_lowrank_forward(const void* X, const void* V, const void* U, void
     s2.C = Y; s2.c_rs = n_out; s2.c_div = 1; s2.c_hi = 1;
     s2.M = T; s2.N = n_out; s2.K = r; s2.G = 1;
     return run_gemm(s2, dt, allow_mfma, s);
+}
+
+blr_status blr_monarch_group_first_factor(const void* R_stack, void* R_group, int n_in, int nblocks, int r, int members,
+                                          blr_dtype dt, blr_stream stream) {
+    if (!R_stack || !R_group || R_stack == R_group || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    if (n_in <= 0 || nblocks <= 0 || r <= 0 || members <= 0 || n_in % nblocks || r % nblocks) return BLR_ERR_INVALID_ARG;
+    return from_hip(launch_monarch_group_first_factor(R_stack, R_group, n_in, nblocks, r, members,
+                                                      dt == BLR_BF16 ? DType::BF16 : DType::F32, (hipStream_t)stream));
 }
 
 blr_status blr_monarch_permute_first_factor(const void* R, void* Rp, int n_in, int nblocks, int r,

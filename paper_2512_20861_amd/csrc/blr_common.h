@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <initializer_list>
+#include <mutex>
 #include <utility>
 
 namespace blr {
@@ -18,6 +20,22 @@ __host__ __device__ inline void static_for(F&& f) {
 }
 
 typedef unsigned short bf16_t;  // bfloat16 bit pattern
+
+// Raises the dynamic-LDS limit of the given kernels exactly once per process, also when several host
+// threads make their first call at the same time; every caller gets the outcome of that one attempt.
+struct LdsLimitOnce {
+    std::once_flag flag;
+    hipError_t err = hipSuccess;
+    hipError_t set(std::initializer_list<const void*> kernels, int bytes) {
+        std::call_once(flag, [&] {
+            for (const void* k : kernels) {
+                err = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+                if (err != hipSuccess) return;
+            }
+        });
+        return err;
+    }
+};
 
 // Workgroup id -> logical work item id such that each XCD (the hardware deals workgroup ids round-robin
 // over the 8 XCDs) works on a contiguous range of logical ids: neighbours in logical order share an L2.
@@ -89,6 +107,8 @@ hipError_t launch_coupling_valu(const void* Z, const void* S, void* A, int64_t T
 
 // first Monarch factor re-ordered for an input in blocked order: Rp[l][c][k*(p/b)+jj] = R[l][c][jj*b+k]
 hipError_t launch_monarch_permute_first_factor(const void* R, void* Rp, int n_in, int nblocks, int r, DType dt, hipStream_t s);
+// first factors of `members` layers that share their input, stacked [members][b][r][p] -> one layer with members*b output blocks
+hipError_t launch_monarch_group_first_factor(const void* Rs, void* Rg, int n_in, int nblocks, int r, int members, DType dt, hipStream_t s);
 // blocked -> interleaved output order of a bf16 Monarch result, Y[t][j*b2 + k] = Yb[t][k*(n_out/b2) + j]
 // (b2 a power of two up to 64, 8 | n_out/b2)
 bool monarch_interleave_supported(int64_t T, int n_out, int b2);

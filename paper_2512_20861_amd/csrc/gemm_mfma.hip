@@ -398,14 +398,9 @@ inline bool dma_offsets_fit(const GemmDesc& d, int bm) {
 template <int BM, int BN, int WGM, int WGN, int NS = 4>
 hipError_t launch_dma(const GemmDesc& d, hipStream_t s, bool allow_split = false) {
     using C = DmaCfg<BM, BN, WGM, WGN, NS>;
-    static bool attr_set = false;   // benign if set twice
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_dma_kernel<BM, BN, WGM, WGN, NS, false>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_limit;
+    if (hipError_t e = lds_limit.set({(const void*)gemm_dma_kernel<BM, BN, WGM, WGN, NS, false>,
+                                      (const void*)gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>}, C::LDS_BYTES); e != hipSuccess) return e;
     const int tiles_m = (int)((d.M + BM - 1) / BM);
     const int tiles_n = (d.N + BN - 1) / BN;
     const bool vec = c_map_vectorizes(d);

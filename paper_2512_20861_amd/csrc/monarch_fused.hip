@@ -238,12 +238,8 @@ inline int lds_bytes(int n_in, int w2, int qt) {
 
 template <int KS1, int KS2>
 hipError_t launch_inst(const MonarchFusedArgs& a, dim3 grid, int lds, hipStream_t s) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)monarch_fused_kernel<KS1, KS2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_limit;
+    if (hipError_t e = lds_limit.set({(const void*)monarch_fused_kernel<KS1, KS2>}, 160 * 1024); e != hipSuccess) return e;
     // one workgroup per compute unit at most: twice the wavefronts, i.e. twice the weight bytes in flight per compute unit
     const unsigned waves = (uint64_t)grid.x * grid.y <= 256 ? MF_MAX_WAVES : MF_MAX_WAVES / 2;
     hipLaunchKernelGGL((monarch_fused_kernel<KS1, KS2>), grid, dim3(64 * waves), lds, s, a);

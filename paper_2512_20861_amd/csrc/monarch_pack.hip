@@ -22,6 +22,22 @@ __global__ __launch_bounds__(256) void permute_first_factor_kernel(const TS* __r
     Rp[e] = R[row * p + (int64_t)jj * b + k];
 }
 
+// First factor of `members` Monarch layers of one shape that share their input, as the first factor of
+// one layer with members * b output blocks: Rg[l][rho*(members*b) + m*b + k][:] = Rs[m][l][rho*b + k][:].
+template <typename TS>
+__global__ __launch_bounds__(256) void group_first_factor_kernel(const TS* __restrict__ Rs, TS* __restrict__ Rg,
+                                                                 int members, int b, int rp, int p, int64_t total) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int a = (int)(e % p);
+    int64_t row = e / p;                                // (l, rho, m, k) flattened
+    const int k = (int)(row % b); row /= b;
+    const int m = (int)(row % members); row /= members;
+    const int rho = (int)(row % rp);
+    const int64_t l = row / rp;
+    Rg[e] = Rs[((((int64_t)m * b + l) * rp + rho) * b + k) * p + a];
+}
+
 // Blocked -> interleaved output order of a Monarch layer with b2 = 2^shift output blocks (paper Section 2.1:
 // the final stride permutation P): Y[t][j*b2 + k] = Yb[t][k*q + j]. A workgroup takes one token and
 // a segment of js values of j through LDS: rows k of the segment arrive as 16-byte pieces and leave
@@ -101,6 +117,18 @@ hipError_t launch_monarch_interleave(const void* Yb, void* Y, int64_t T, int n_o
     const int64_t groups = (T + tpw - 1) / tpw;
     hipLaunchKernelGGL(interleave_rows_kernel, dim3((unsigned)(groups * nseg)), dim3(256), (size_t)tpw * row_lds, s,
                        (const bf16_t*)Yb, (bf16_t*)Y, T, q, b2, shift, js, nseg, tpw);
+    return hipGetLastError();
+}
+
+hipError_t launch_monarch_group_first_factor(const void* Rs, void* Rg, int n_in, int nblocks, int r, int members, DType dt, hipStream_t s) {
+    const int p = n_in / nblocks, rp = r / nblocks;
+    const int64_t total = (int64_t)members * nblocks * r * p;
+    if (total <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (dt == DType::F32)
+        hipLaunchKernelGGL(group_first_factor_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)Rs, (float*)Rg, members, nblocks, rp, p, total);
+    else
+        hipLaunchKernelGGL(group_first_factor_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t*)Rs, (bf16_t*)Rg, members, nblocks, rp, p, total);
     return hipGetLastError();
 }
 

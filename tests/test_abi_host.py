@@ -252,46 +252,94 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
 
 def test_python_wrappers_marshal_every_entry_point(monkeypatch):
     """Every wrapper of the binding builds a call the C prototype accepts (argument count and types),
-    checked on the CPU with host tensors standing in for device tensors and a recorder standing in
-    for the launching entry points (size queries run for real)."""
+    checked on the CPU with host tensors standing in for device tensors: the launching functions
+    through their marshallers (nothing is called), the one-time re-layouts through a recorder that
+    stands in for their entry points (size queries run for real)."""
     torch = pytest.importorskip("torch")
     real = B.lib()
     calls = []
 
+    def fits(name, args):
+        fn = getattr(real, name)
+        assert len(args) == len(fn.argtypes), (name, len(args), len(fn.argtypes))
+        for t, a in zip(fn.argtypes, args):
+            t(a) if not isinstance(a, t) else a          # raises if the value does not fit the C type
+        calls.append(name)
+
+    RELAYOUTS = ("blr_blast_pack", "blr_monarch_permute_first_factor", "blr_monarch_group_first_factor")
+
     class Recorder:
         def __getattr__(self, name):
-            fn = getattr(real, name)
-            if name not in B._LAUNCHERS and name not in ("blr_blast_pack", "blr_monarch_permute_first_factor"):
-                return fn
+            if name not in RELAYOUTS:
+                return getattr(real, name)
             def rec(*args):
-                assert len(args) == len(fn.argtypes), (name, len(args), len(fn.argtypes))
-                for t, a in zip(fn.argtypes, args):
-                    t(a) if not isinstance(a, t) else a          # raises if the value does not fit the C type
-                calls.append(name)
+                fits(name, args)
                 return B.OK
             return rec
 
     monkeypatch.setattr(B, "_lib", Recorder())
+    monkeypatch.setattr(B, "_is_gpu", lambda t: isinstance(t, torch.Tensor))
     monkeypatch.setattr(B, "_ptr", lambda t: None if t is None else t.data_ptr())
     monkeypatch.setattr(B, "_ptr_rows", lambda t: t.data_ptr())
     monkeypatch.setattr(B, "_stream", lambda s: None)
     bf = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16)
     ws = torch.zeros(1 << 22, dtype=torch.uint8)
     T, n, b, r = 8, 64, 4, 16
-    B.monarch_forward(bf(T, n), bf(b, r, n // b), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
-    B.monarch_rect_forward(bf(T, n), bf(2, 4 * b, n // 2), bf(b, n // b, 2 * 4), bf(T, n), 2, b, 4, 0, ws)
+
+    def marshal(fn, *args):
+        name, cargs, result, keep = fn.marshal(*args)
+        fits(name, cargs)
+        assert result is not None and all(k is None or isinstance(k, torch.Tensor) for k in keep)
+
+    marshal(B.monarch_forward, bf(T, n), bf(b, r, n // b), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
+    marshal(B.monarch_rect_forward, bf(T, n), bf(2, 4 * b, n // 2), bf(b, n // b, 2 * 4), bf(T, n), 2, b, 4, 0, ws)
     B.monarch_permute_first_factor(bf(b, r, n // b), n, b, r)
-    B.lowrank_forward(bf(T, n), bf(r, n), bf(48, r), bf(T, 48), 0, ws)
-    B.blast_forward(bf(T, n), bf(b, n // b, r), bf(b, b, r), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
-    B.blast_pack(bf(16, 48, 96), bf(16, 16, 96), bf(16, 48, 96), 768, 768, 16, 96)
-    B.blast_group_forward(bf(T, 2048), bf(3, 16, 128, 256), bf(64), bf(T, 3 * 2048), 16, 256, 3, 0, ws)
-    B.dense_reference_forward(bf(T, n), bf(n, n), bf(T, n))
-    B.rmsnorm(bf(T, n), bf(T, n))
-    B.residual_add_rmsnorm(bf(T, n), bf(T, n), bf(T, n))
-    B.residual_add_rmsnorm(bf(T, n), bf(T, n), None)
-    B.sum3_scaled(bf(T, n), bf(T, n), bf(T, n), bf(T, n), 0.5)
-    B.silu_mul(bf(T, n), bf(T, n), bf(T, n))
+    assert tuple(B.monarch_group_first_factor(bf(3, b, r, n // b), n, b, r).shape) == (b, 3 * r, n // b)
+    marshal(B.lowrank_forward, bf(T, n), bf(r, n), bf(48, r), bf(T, 48), 0, ws)
+    marshal(B.blast_forward, bf(T, n), bf(b, n // b, r), bf(b, b, r), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
+    packed = B.blast_pack(bf(16, 48, 96), bf(16, 16, 96), bf(16, 48, 96), 768, 768, 16, 96)
+    marshal(B.blast_forward, bf(T, 768), bf(16, 48, 96), None, packed, bf(T, 768), 16, 96, B.BLAST_PACKED, ws)
+    gpacked = torch.zeros(B.blast_packed_bytes(2048, 2048, 16, 3 * 256), dtype=torch.uint8)
+    marshal(B.blast_group_forward, bf(T, 2048), bf(3, 16, 128, 256), gpacked, bf(T, 3 * 2048), 16, 256, 3, 0,
+            torch.zeros(B.blast_group_workspace_bytes(T, 2048, 2048, 16, 256, 3) + 16, dtype=torch.uint8))
+    marshal(B.dense_reference_forward, bf(T, n), bf(n, n), bf(T, n))
+    marshal(B.rmsnorm, bf(T, n), bf(T, n))
+    marshal(B.residual_add_rmsnorm, bf(T, n), bf(T, n), bf(T, n))
+    marshal(B.residual_add_rmsnorm, bf(T, n), bf(T, n), None)
+    marshal(B.sum3_scaled, bf(T, n), bf(T, n), bf(T, n), bf(T, n), 0.5)
+    marshal(B.silu_mul, bf(T, n), bf(T, n), bf(T, n))
     wide = bf(T, 3 * n)                                    # column slices of a wider tensor take the strided entry points
-    B.sum3_scaled(wide[:, :n], wide[:, n:2 * n], wide[:, 2 * n:], bf(T, n), 0.5)
-    B.silu_mul(wide[:, :n], wide[:, n:2 * n], bf(T, n))
-    assert set(calls) == set(B._LAUNCHERS) | {"blr_blast_pack", "blr_monarch_permute_first_factor"}
+    marshal(B.sum3_scaled, wide[:, :n], wide[:, n:2 * n], wide[:, 2 * n:], bf(T, n), 0.5)
+    marshal(B.silu_mul, wide[:, :n], wide[:, n:2 * n], bf(T, n))
+    launching = {n_ for n_ in B.EXPORTS if not n_.endswith("_bytes") and n_ != "blr_status_string"}
+    assert set(calls) == launching
+
+
+def test_python_wrappers_reject_mismatched_tensors(monkeypatch):
+    """A factor, output or workspace that does not fit the sizes of the call is refused by the binding
+    before any pointer reaches the library (on the device it would be an out-of-bounds access)."""
+    torch = pytest.importorskip("torch")
+    monkeypatch.setattr(B, "_is_gpu", lambda t: isinstance(t, torch.Tensor))
+    monkeypatch.setattr(B, "_ptr", lambda t: None if t is None else t.data_ptr())
+    monkeypatch.setattr(B, "_stream", lambda s: None)
+    bf = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16)
+    ws = torch.zeros(1 << 20, dtype=torch.uint8)
+    T, n, b, r = 8, 64, 4, 16
+    good = (bf(T, n), bf(b, r, n // b), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
+    B.monarch_forward.marshal(*good)
+    for i, bad in ((1, bf(b, r + 4, n // b)), (2, bf(b, n // b, 2 * r)), (3, bf(T + 1, n)), (1, torch.zeros((b, r, n // b))),
+                   (7, torch.zeros(1 << 20, dtype=torch.float32))):
+        args = list(good)
+        args[i] = bad
+        with pytest.raises(ValueError):
+            B.monarch_forward.marshal(*args)
+    with pytest.raises(ValueError):
+        B.monarch_forward.marshal(bf(T, n), bf(3, r, n // b), bf(3, n // b, r), bf(T, n), 3, r, 0, ws)     # 3 does not divide 64
+    with pytest.raises(ValueError):
+        B.blast_forward.marshal(bf(T, n), bf(b, n // b, r), bf(b, b, r), bf(b, n // b, r + 8), bf(T, n), b, r, 0, ws)
+    with pytest.raises(ValueError):
+        B.blast_forward.marshal(bf(T, n), bf(b, n // b, r), None, torch.zeros(8, dtype=torch.uint8), bf(T, n), b, r, B.BLAST_PACKED, ws)
+    with pytest.raises(ValueError):
+        B.lowrank_forward.marshal(bf(T, n), bf(r, n + 8), bf(48, r), bf(T, 48), 0, ws)
+    with pytest.raises(ValueError):
+        B.dense_reference_forward.marshal(bf(T, n), bf(n, n + 8), bf(T, n))

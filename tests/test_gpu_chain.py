@@ -13,11 +13,10 @@ from oracle import chain as oc
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
-# End to end, rounding errors of the 7 * n_layers bf16 linears and of the bf16 residual stream add up;
-# each contributes about 2^-9 of the stream's scale and they are independent, so the bound grows
-# with the square root of the number of roundings on the path (measured values are printed).
+# The stated bound, end to end as for a single linear: max|delta| / max|ref| <= 2e-2 (bf16), 1e-5 (fp32);
+# the measured values (printed) are 1.3-1.5e-2 over the 16 layers of the benchmark chain.
 def chain_tol(n_layers, dtype):
-    return (2e-2 if dtype == "bf16" else 1e-5) * max(1.0, math.sqrt(n_layers / 2.0))
+    return 2e-2 if dtype == "bf16" else 1e-5
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -186,8 +185,32 @@ def test_full_chain_sampled_rows(op):
         f()
     torch.cuda.synchronize()
     rows = np.array([0, 1, 127, 128, 1000, T - 1], dtype=np.int64)
-    href = oc.chain_forward(x0.f64[rows], layers, _oracle_linear(op))
-    got = gu.to_f64(chain.h[torch.from_numpy(rows).cuda()])
+    sel = torch.from_numpy(rows).cuda()
+    lin = _oracle_linear(op)
+    href = oc.chain_forward(x0.f64[rows], layers, lin)
+    got = gu.to_f64(chain.h[sel])
     err = gu.rel_err(got, href)
     print(f"full chain {op}: {len(rows)} sampled rows, end-to-end rel err {err:.3e}")
     assert err <= chain_tol(c["n_layers"], "bf16")
+    # Every one of the 112 full-size linears on its own, at the single-linear bound: the oracle applied
+    # to the sampled rows of the GPU's own input of that call (rows are independent).
+    h_prepared = chain.h.clone()
+    h2, taps = chain.forward(gu.to_dev(x0), record=True, rows=sel)
+    torch.cuda.synchronize()
+    assert torch.equal(h2.view(torch.int16), h_prepared.view(torch.int16))     # prepared and plain calls agree bit for bit
+    nb = getattr(layers[0]["q"], "nblocks", 0)
+    def canon(x):          # blocked -> canonical feature order
+        T_, n = x.shape
+        return x.reshape(T_, nb, n // nb).transpose(0, 2, 1).reshape(T_, n)
+    worst = 0.0
+    for li, layer in enumerate(layers):
+        for name in bi.CHAIN_LINEARS:
+            src, out = (gu.to_f64(t) for t in taps[f"{li}.{name}"])
+            if chain.blocked and name in chain.IN_BLOCKED:
+                src = canon(src)
+            if chain.blocked and name in chain.OUT_BLOCKED:
+                out = canon(out)
+            e = gu.rel_err(out, lin(src, layer[name]))
+            worst = max(worst, e)
+            assert e <= gu.TOL["bf16"], (li, name, e)
+    print(f"full chain {op}: worst single linear over {len(layers) * len(bi.CHAIN_LINEARS)} linears, rel err {worst:.3e}")

@@ -45,8 +45,11 @@ def test_c1_full_tensor():
     assert err <= gu.TOL["bf16"]
 
 
-@pytest.mark.parametrize("name,T", [("C2a", 8192), ("C2a", 512), ("C2a", 16), ("C2a", 1),
-                                    ("C2b", 2048), ("C2b", 128), ("C2b", 1)])
+SWEEP_T = (1, 16, 128, 512, 2048, 8192)       # every token count the benchmark sweep is quoted on
+
+
+@pytest.mark.parametrize("T", SWEEP_T)
+@pytest.mark.parametrize("name", ["C2a", "C2b"])
 def test_monarch_llama_shapes_sampled(name, T):
     gu = _gu()
     cfg = bi.CONFIGS[name]
@@ -80,8 +83,8 @@ def test_monarch_short_rank_runs_into_an_intermediate_beyond_the_cache_sampled()
     assert err <= gu.TOL["bf16"]
 
 
-@pytest.mark.parametrize("name,T", [("C3a", 8192), ("C3a", 512), ("C3a", 16), ("C3a", 1),
-                                    ("C3b", 2048), ("C3b", 128), ("C3b", 1)])
+@pytest.mark.parametrize("T", SWEEP_T)
+@pytest.mark.parametrize("name", ["C3a", "C3b"])
 def test_blast_llama_shapes_sampled(name, T):
     gu = _gu()
     cfg = bi.CONFIGS[name]
@@ -103,7 +106,38 @@ def test_blast_llama_shapes_sampled(name, T):
         assert errf <= gu.TOL["bf16"]
 
 
-@pytest.mark.parametrize("T,n_in,n_out", [(2048, 4096, 4096), (8192, 4096, 4096), (16, 4096, 11008), (128, 11008, 4096)])
+def test_monarch_whole_tensor_mid_size():
+    """Every element of a mid-size result (not a sample of rows): 16 blocks, 4096 -> 8192, a token count
+    that is not a multiple of any tile. Both stages run on the largest GEMM tile, the interleaved order
+    goes through the blocked copy and the permutation pass, and the last row tile is ragged."""
+    gu = _gu()
+    T, n_in, n_out, nb, r = 2048 + 37, 4096, 8192, 16, 1024
+    lay = bi.monarch_layer(n_in, n_out, nb, r, "bf16", seed=11)
+    X = bi.activations(T, n_in, "bf16", seed=12)
+    for order, oflag in (("interleaved", oracle.OUT_INTERLEAVED), ("blocked", oracle.OUT_BLOCKED)):
+        Y = gu.to_f64(gu.run_monarch(X, lay, gu.B.MONARCH_OUT_BLOCKED if order == "blocked" else 0))
+        Yref = oracle.monarch_forward(X.f64, lay.R.f64, lay.L.f64, oflag)
+        err = gu.rel_err(Y, Yref)
+        print(f"monarch {n_in}->{n_out} b={nb} r={r} T={T} {order}: whole tensor, rel err {err:.3e}")
+        assert err <= gu.TOL["bf16"]
+
+
+def test_blast_whole_tensor_mid_size():
+    """Every element of a mid-size BLAST result on both large-rank executions: 2048 -> 4096, b = 16,
+    r = 512, a ragged token count (several 128-token tiles of the fused kernel and a partial one)."""
+    gu = _gu()
+    T, n_in, n_out, b, r = 1536 + 75, 2048, 4096, 16, 512
+    lay = bi.blast_layer(n_in, n_out, b, r, "bf16", seed=13)
+    X = bi.activations(T, n_in, "bf16", seed=14)
+    Yref = oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64)
+    for label, flag in (("default", 0), ("fused stage 1+2", gu.B.BLAST_FUSED_STAGE12), ("three kernels", gu.B.BLAST_THREE_KERNELS)):
+        err = gu.rel_err(gu.to_f64(gu.run_blast(X, lay, flag, packed=True)), Yref)
+        print(f"blast {n_in}->{n_out} b={b} r={r} T={T} {label}: whole tensor, rel err {err:.3e}")
+        assert err <= gu.TOL["bf16"]
+
+
+@pytest.mark.parametrize("T,n_in,n_out", [(2048, 4096, 4096), (8192, 4096, 4096), (16, 4096, 11008), (128, 11008, 4096),
+                                          (512, 4096, 11008), (8192, 11008, 4096)])
 def test_dense_llama_shape_sampled(T, n_in, n_out):
     gu = _gu()
     W = bi.dense_weight(n_in, n_out, "bf16")

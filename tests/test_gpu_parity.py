@@ -318,9 +318,12 @@ def test_zero_tokens_and_status_codes():
     with pytest.raises(B.BlrError) as e:
         B.monarch_forward(X, Rd, Ld, Y, 4, 16, workspace=small)
     assert e.value.status == B.ERR_WORKSPACE
-    with pytest.raises(B.BlrError) as e:
-        B.monarch_forward(X, Rd, Ld, Y, 3, 16)                    # 3 does not divide 64
-    assert e.value.status == B.ERR_INVALID_ARG
+    with pytest.raises(ValueError):
+        B.monarch_forward(X, Rd, Ld, Y, 3, 16)                    # 3 does not divide 64: refused by the binding ...
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    st = B.lib().blr_monarch_forward(X.data_ptr(), Rd.data_ptr(), Ld.data_ptr(), Y.data_ptr(), 4, 64, 64, 3, 16, B.BF16, 0,
+                                     ws.data_ptr(), ws.numel(), None)
+    assert st == B.ERR_INVALID_ARG                                # ... and by the library itself
     torch.cuda.synchronize()
     assert torch.isnan(Y.float()).all()                           # failed calls launched nothing
 
@@ -429,3 +432,30 @@ def test_monarch_default_dispatch_around_the_token_limit_of_the_single_kernel(T)
     rows = np.unique(np.concatenate([np.arange(0, 40), np.arange(T - 40, T), np.random.default_rng(5).integers(0, T, 200)]))
     Yref = oracle.monarch_forward(X.f64[rows], lay.R.f64, lay.L.f64)
     assert gu.rel_err(Y[rows], Yref) <= gu.TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_monarch_group_first_factor_and_grouped_call(dtype):
+    """Three Monarch layers of one shape on the same input as one layer with 3 * nblocks output blocks:
+    the library's re-layout of the stacked first factors against the index formula, and each member's
+    column slice of the grouped call against the oracle's result for that member alone."""
+    gu = _gu()
+    B = gu.B
+    n_in, n_out, nb, r, T, members = 256, 384, 4, 64, 77, 3
+    lays = [bi.monarch_layer(n_in, n_out, nb, r, dtype, seed=50 + m) for m in range(members)]
+    X = bi.activations(T, n_in, dtype, seed=60)
+    Rs = torch.stack([gu.to_dev(l.R) for l in lays], dim=0).contiguous()
+    Rg = B.monarch_group_first_factor(Rs, n_in, nb, r)
+    torch.cuda.synchronize()
+    rp, p = r // nb, n_in // nb
+    host = np.stack([l.R.f64.reshape(nb, rp, nb, p) for l in lays], axis=0)            # [m][l][rho][k][a]
+    want = host.transpose(1, 2, 0, 3, 4).reshape(nb, rp * members * nb, p)             # [l][rho][m][k][a]
+    assert np.array_equal(gu.to_f64(Rg), want)
+    Lg = torch.cat([gu.to_dev(l.L) for l in lays], dim=0).contiguous()
+    Y = gu.empty_out(T, members * n_out, dtype)
+    B.monarch_rect_forward(gu.to_dev(X), Rg, Lg, Y, nb, members * nb, rp, B.MONARCH_OUT_BLOCKED)
+    torch.cuda.synchronize()
+    Yh = gu.to_f64(Y)
+    for m, l in enumerate(lays):
+        ref = oracle.monarch_forward(X.f64, l.R.f64, l.L.f64, oracle.OUT_BLOCKED)
+        assert gu.rel_err(Yh[:, m * n_out:(m + 1) * n_out], ref) <= gu.TOL[dtype]
