@@ -99,6 +99,26 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
                                void* workspace, size_t workspace_bytes, blr_stream stream);
 
 /*
+ * blr_monarch_forward for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments,
+ * same kernels and bit-identical results, but the intermediate Z' (and the blocked-order copy of large
+ * interleaved outputs) lives in a static device array of BLR_STATIC_SCRATCH_BYTES inside the library,
+ * one copy per GPU, held from the moment the library is loaded on that GPU until the process ends. The
+ * call allocates nothing and frees nothing. Its first call on a GPU looks the array's address up (the
+ * current device must be the one `stream` belongs to).
+ * BLR_ERR_WORKSPACE if blr_monarch_workspace_bytes(...) for these sizes exceeds BLR_STATIC_SCRATCH_BYTES
+ * (e.g. 4096 x 4096, nblocks = 4, r = 1024 fits up to T = 8192); nothing is enqueued then.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams
+ * or host threads) race on it and must be serialised by the caller; calls on one stream are ordered.
+ * Nothing in the array has to be zero: every element a call reads was written by the same call.
+ */
+#define BLR_STATIC_SCRATCH_BYTES (64u << 20)
+size_t     blr_static_scratch_bytes(void);
+blr_status blr_monarch_forward_static(const void* X, const void* R, const void* L, void* Y,
+                                      int64_t T, int n_in, int n_out, int nblocks, int r,
+                                      blr_dtype dt, unsigned flags, blr_stream stream);
+
+/*
  * Monarch forward with different block counts on the two sides (paper Section 2.1 "Monarch": the
  * weight is divided into b2 x b1 blocks W_{l,k} = V_{l,k} U_{l,k} of rank r', l < b1 input blocks of
  * p = n_in/b1 features, k < b2 output blocks of q = n_out/b2 features). With b1 = b_in, b2 = b_out,

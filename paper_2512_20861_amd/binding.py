@@ -38,7 +38,7 @@ EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forw
            "blr_monarch_permute_first_factor", "blr_lowrank_workspace_bytes", "blr_lowrank_forward",
            "blr_monarch_rect_workspace_bytes", "blr_monarch_rect_forward", "blr_sum3_scaled_ld", "blr_silu_mul_ld",
            "blr_blast_group_workspace_bytes", "blr_blast_group_forward",
-           "blr_monarch_group_first_factor")
+           "blr_monarch_group_first_factor", "blr_static_scratch_bytes", "blr_monarch_forward_static")
 
 _lib = None
 
@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.blr_monarch_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci]
         L.blr_monarch_forward.restype = ci
         L.blr_monarch_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, cu, vp, sz, vp]
+        L.blr_static_scratch_bytes.restype = sz
+        L.blr_static_scratch_bytes.argtypes = []
+        L.blr_monarch_forward_static.restype = ci
+        L.blr_monarch_forward_static.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, cu, vp]
         L.blr_monarch_group_first_factor.restype = ci
         L.blr_monarch_group_first_factor.argtypes = [vp, vp, ci, ci, ci, ci, ci, vp]
         L.blr_monarch_rect_workspace_bytes.restype = sz
@@ -224,6 +228,18 @@ def monarch_forward(X, R, L, Y, nblocks, r, flags=0, workspace=None, stream=None
     ws = _workspace(workspace, monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt), X)
     return ("blr_monarch_forward", (_ptr(X), _ptr(R), _ptr(L), _ptr(Y), T, n_in, n_out, nblocks, r, dt, flags,
                                     _ptr(ws), ws.numel(), _stream(stream)), Y, (X, R, L, Y, ws))
+
+
+def static_scratch_bytes() -> int:
+    return lib().blr_static_scratch_bytes()
+
+
+@_launcher
+def monarch_forward_static(X, R, L, Y, nblocks, r, flags=0, stream=None):
+    """monarch_forward without a workspace: the intermediate lives in the library's static device array."""
+    T, n_in, n_out = _monarch_checks(X, R, L, Y, nblocks, nblocks, _div(r, nblocks, "r / nblocks"))
+    return ("blr_monarch_forward_static", (_ptr(X), _ptr(R), _ptr(L), _ptr(Y), T, n_in, n_out, nblocks, r, _dt(X), flags,
+                                           _stream(stream)), Y, (X, R, L, Y))
 
 
 def monarch_rect_workspace_bytes(T, n_in, n_out, b_in, b_out, r_block, dt) -> int:

@@ -3,6 +3,7 @@
 #include "../../include/blr_measure.h"
 #include "blr_common.h"
 #include <algorithm>
+#include <mutex>
 
 using namespace blr;
 
@@ -376,6 +377,47 @@ blr_status blr_monarch_forward(const void* X, const void* R, const void* L, void
     if ((flags & BLR_MONARCH_FUSED) && !monarch_fused_possible(T, n_in, n_out, nblocks, nblocks, r / nblocks, dt, flags)) return BLR_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < blr_monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt)) return BLR_ERR_WORKSPACE;
     return monarch_run(X, R, L, Y, T, n_in, n_out, nblocks, nblocks, r / nblocks, dt, flags, workspace, (hipStream_t)stream);
+}
+
+// ---- Monarch forward for callers that cannot allocate: Z' lives in a static device array --------
+// One array per GPU (each device that loads the library holds its own copy until the process ends).
+// In host code the array's name is only a handle: the device address comes from hipGetSymbolAddress,
+// looked up once per device with that device current, and only that address is handed to kernels.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[BLR_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct DeviceScratch { std::once_flag once; void* ptr = nullptr; hipError_t err = hipSuccess; };
+DeviceScratch g_scratch[kMaxDevices];
+
+// device address of this GPU's copy of `scratch` (nullptr and the HIP error on failure)
+hipError_t static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    DeviceScratch& ds = g_scratch[dev];
+    std::call_once(ds.once, [&] { ds.err = hipGetSymbolAddress(&ds.ptr, HIP_SYMBOL(scratch)); });
+    *out = ds.ptr;
+    return ds.err;
+}
+}  // namespace
+
+extern "C" {
+
+size_t blr_static_scratch_bytes(void) { return BLR_STATIC_SCRATCH_BYTES; }
+
+blr_status blr_monarch_forward_static(const void* X, const void* R, const void* L, void* Y,
+                                      int64_t T, int n_in, int n_out, int nblocks, int r,
+                                      blr_dtype dt, unsigned flags, blr_stream stream) {
+    if (!monarch_shape_ok(T, n_in, n_out, nblocks, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
+    // sizes beyond the array are refused before anything else is looked at
+    if (blr_monarch_workspace_bytes(T, n_in, n_out, nblocks, r, dt) > BLR_STATIC_SCRATCH_BYTES) return BLR_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (static_scratch(&ws) != hipSuccess || !ws) return BLR_ERR_LAUNCH;
+    return blr_monarch_forward(X, R, L, Y, T, n_in, n_out, nblocks, r, dt, flags, ws, BLR_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t blr_monarch_rect_workspace_bytes(int64_t T, int n_in, int n_out, int b_in, int b_out, int r_block, blr_dtype dt) {

@@ -292,6 +292,7 @@ def test_python_wrappers_marshal_every_entry_point(monkeypatch):
         assert result is not None and all(k is None or isinstance(k, torch.Tensor) for k in keep)
 
     marshal(B.monarch_forward, bf(T, n), bf(b, r, n // b), bf(b, n // b, r), bf(T, n), b, r, 0, ws)
+    marshal(B.monarch_forward_static, bf(T, n), bf(b, r, n // b), bf(b, n // b, r), bf(T, n), b, r, 0)
     marshal(B.monarch_rect_forward, bf(T, n), bf(2, 4 * b, n // 2), bf(b, n // b, 2 * 4), bf(T, n), 2, b, 4, 0, ws)
     B.monarch_permute_first_factor(bf(b, r, n // b), n, b, r)
     assert tuple(B.monarch_group_first_factor(bf(3, b, r, n // b), n, b, r).shape) == (b, 3 * r, n // b)
