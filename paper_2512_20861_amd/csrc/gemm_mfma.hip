@@ -20,21 +20,25 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 
-// Tile and batch index of this workgroup. Workgroup ids are remapped so that each XCD owns a
-// contiguous range of tiles, walked in groups of 8 row-tiles per column-tile. With a scattering
-// column map (gfast) the batch index varies fastest, so the G workgroups that interleave their
-// columns into the same cache lines run side by side on one XCD and their partial-line writes
-// merge in its L2.
+// Tile and batch index of this workgroup. The grid is one-dimensional over all tiles of all batches;
+// workgroup ids are remapped so that each XCD owns a contiguous range of logical ids. Normally the
+// batch index is the SLOWEST logical index: an XCD then works on one batch (or a few) at a time, so
+// the operand panels that meet in its L2 are those of that batch only (with 4 batches and a few
+// hundred tokens every XCD used to fetch the whole activation matrix), and within a batch the tiles
+// are walked in groups of 8 row tiles per column tile. With a scattering column map (gfast) the batch
+// index varies FASTEST instead, so the G workgroups that interleave their columns into the same
+// cache lines run side by side on one XCD and their partial-line writes merge in its L2.
 __device__ inline void workgroup_tile(const GemmDesc& d, int tiles_m, int tiles_n, int gfast, int& g, int& tile_m, int& tile_n) {
     constexpr int GM = 8;
+    const int per_batch = tiles_m * tiles_n;
+    const int lg = xcd_contiguous(blockIdx.x, per_batch * d.G);
     int logical;
     if (gfast) {
-        const int lg = xcd_contiguous(blockIdx.x, tiles_m * tiles_n * d.G);
         g = lg % d.G;
         logical = lg / d.G;
     } else {
-        g = blockIdx.y;
-        logical = xcd_contiguous(blockIdx.x, tiles_m * tiles_n);
+        g = lg / per_batch;
+        logical = lg - g * per_batch;
     }
     const int group_size = GM * tiles_n;
     const int first_m = (logical / group_size) * GM;
@@ -323,6 +327,185 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, in
     store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same product for calls with FEW tiles (some hundreds of tokens): there every workgroup walks its
+// contraction index alone on its compute unit, and a step of 32 costs the same chain of latencies
+// (barrier, LDS read, dependent MFMAs) whatever the tile does in between: about 600 clocks for 128 to
+// 256 clocks of matrix work. This kernel takes DEEP steps instead: BK = 64 or 128 contraction indices
+// per barrier (rows of 128 or 256 bytes in LDS, 16-byte pieces XOR-swizzled by the row so that the 16
+// rows a ds_read_b128 serves per clock cover all 64 banks), the fragment reads of k16 step ks + 1 in
+// flight while the MFMAs of step ks run, the direct loads of step s + NS - 1 issued right after the
+// barrier of step s. The chain is paid once per 4 to 8 times the work.
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGES>
+struct DeepCfg {
+    static constexpr int BK = BKT, NS = NSTAGES;
+    static constexpr int RB = BK * 2;                 // bytes of an operand row in LDS
+    static constexpr int PPR = RB / 16;               // 16-byte pieces per row
+    static constexpr int RPL = 1024 / RB;             // rows one direct load (64 lanes x 16 bytes) fills
+    static constexpr int SH = BK == 128 ? 0 : BK == 64 ? 1 : 2;   // swizzle: piece ^ ((row >> SH) & (PPR - 1))
+    static constexpr int KS = BK / 16;                // k16 steps per stage
+    static constexpr int WAVES = WGM * WGN, THREADS = 64 * WAVES;
+    static constexpr int ROWS = BM + BN;
+    static constexpr int STAGE = ROWS * RB;
+    static constexpr int LPW = ROWS / RPL / WAVES;    // direct loads per wavefront and stage
+    static constexpr int CSTR = BN * 2 + 16;
+    static constexpr int C_BYTES = BM * CSTR;
+    static constexpr int LDS_BYTES = NS * STAGE > C_BYTES ? NS * STAGE : C_BYTES;
+    static constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    static constexpr int MI = WTM / 32, NI = WTN / 32;
+    static_assert(BK == 64 || BK == 128, "deep steps");
+    static_assert(ROWS % (RPL * WAVES) == 0 && BM % RPL == 0, "whole direct loads per wavefront, none straddling A and B");
+    static_assert(NS >= 2 && MI >= 1 && NI >= 1 && LPW * (NS - 1) < 64, "tile / vmcnt range");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert((MI * 32 - 32) * RB < 65536 && (NI * 32 - 32) * RB < 65536, "fragment offsets are ds_read immediates");
+};
+
+template <int BM, int BN, int WGM, int WGN, int BKT, int NS, bool TAIL>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_deep_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int gfast) {
+    using C = DeepCfg<BM, BN, WGM, WGN, BKT, NS>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    int g, tile_m, tile_n;
+    workgroup_tile(d, tiles_m, tiles_n, gfast, g, tile_m, tile_n);
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int n0 = tile_n * BN;
+    const unsigned char* Abase = (const unsigned char*)((const bf16_t*)d.A + (int64_t)g * d.a_gs + m0 * d.a_rs);
+    const unsigned char* Bbase = (const unsigned char*)((const bf16_t*)d.B + (int64_t)g * d.b_gs);
+    const int nk = (d.K + C::BK - 1) / C::BK;
+
+    // Direct load h of this wavefront fills stage rows RPL (LPW wave + h) .. + RPL - 1 (A rows first, then
+    // B rows): lane l brings the piece that belongs in slot l % PPR of row l / PPR of those. Offsets are
+    // bytes from Abase / Bbase; the launcher checks that they fit 32 bits, so the arithmetic is 32-bit.
+    unsigned off[C::LPW];
+    bool bad[C::LPW];
+    {
+        const int lrow = lane / C::PPR, slot = lane % C::PPR;
+        const int rows_m = d.M - m0 < BM ? (int)(d.M - m0) : BM;      // rows of this tile that exist
+        // B rows: n = n0 + row - BM walks upwards by RPL per load; its image under the row gather is kept as
+        // (remainder, quotient) and advanced without divisions
+        int bn = n0 + C::RPL * (C::LPW * wave) + lrow - BM;            // (negative while this wavefront is still on A rows)
+        int brem = 0, bquo = 0;
+        bool bstarted = false;
+#pragma unroll
+        for (int h = 0; h < C::LPW; ++h) {
+            const int row = C::RPL * (C::LPW * wave + h) + lrow;
+            const int piece = slot ^ ((row >> C::SH) & (C::PPR - 1));
+            if (C::RPL * (C::LPW * wave + h) < BM) {                   // uniform
+                const int mr = row < rows_m ? row : rows_m - 1;        // rows past the end re-read the last row; never stored
+                off[h] = ((unsigned)mr * (unsigned)d.a_rs + (unsigned)piece * 8u) * 2u;
+            } else {
+                int n = bn + C::RPL * h;
+                if (n > d.N - 1) n = d.N - 1;
+                unsigned nr = (unsigned)n;
+                if (d.b_div) {
+                    if (!bstarted || n == d.N - 1) { brem = n % d.b_div; bquo = n / d.b_div; bstarted = true; }
+                    nr = (unsigned)brem * (unsigned)d.b_mul + (unsigned)bquo;
+                    brem += C::RPL;
+                    while (brem >= d.b_div) { brem -= d.b_div; ++bquo; }
+                }
+                off[h] = (nr * (unsigned)d.b_rs + (unsigned)piece * 8u) * 2u;
+            }
+            bad[h] = TAIL && (nk - 1) * C::BK + piece * 8 >= d.K;       // in the last step this piece lies past K
+        }
+    }
+    int kf = 0;                                         // fetch cursor (uniform); stops at the last step
+    int a_pos = 0;                                      // position inside the current segment of a segmented contraction index
+    int64_t a_koff = 0;
+    // loads H0 .. H1-1 of the step under the cursor; `advance` = these complete the step's loads
+    auto issue = [&](int stage_off, auto H0, auto H1, bool advance) {
+        const bool lastk = TAIL && kf == nk - 1;
+#pragma unroll
+        for (int h = decltype(H0)::value; h < decltype(H1)::value; ++h) {
+            const bool isa = C::RPL * (C::LPW * wave + h) < BM;               // uniform
+            const unsigned char* p = (isa ? Abase + a_koff : Bbase + (size_t)kf * C::RB) + off[h];
+            if (TAIL) p = (lastk && bad[h]) ? zero_piece : p;
+            __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 0);
+        }
+        if (advance && kf < nk - 1) {
+            ++kf;
+            a_koff += C::RB;
+            if (d.a_seg) {
+                a_pos += C::BK;
+                if (a_pos == d.a_seg) { a_pos = 0; a_koff += (d.a_seg_stride - d.a_seg) * 2; }
+            }
+        }
+    };
+    constexpr std::integral_constant<int, 0> L0{};
+    constexpr std::integral_constant<int, C::LPW> LN{};
+
+    // fragment addresses inside a stage: row m of a 32-row MFMA operand, k group kg; k16 step ks adds to the piece
+    const int m = lane & 31, kg = lane >> 5;
+    const unsigned lds0 = (unsigned)(uintptr_t)BLR_LPTR(smem);
+    const unsigned swz = (unsigned)((m >> C::SH) & (C::PPR - 1));
+    const unsigned rowa = lds0 + (wm * C::WTM + m) * C::RB, rowb = lds0 + (BM + wn * C::WTN + m) * C::RB;
+
+    f32x16 acc[C::MI][C::NI];
+#pragma unroll
+    for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+        for (int j = 0; j < C::NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    bf16x8 af[2][C::MI], bfr[2][C::NI];                 // fragments of two k16 steps in rotation
+    auto read_frags = [&](auto KSC, int stage_off) {
+        constexpr int ks = decltype(KSC)::value;
+        const unsigned sw = (((unsigned)(2 * ks + kg)) ^ swz) * 16u;
+        const unsigned aa = rowa + stage_off + sw, ab = rowb + stage_off + sw;
+        static_for<C::MI>([&](auto I) { af[ks & 1][decltype(I)::value] = lds_read_b128<decltype(I)::value * 32 * C::RB>(aa); });
+        static_for<C::NI>([&](auto J) { bfr[ks & 1][decltype(J)::value] = lds_read_b128<decltype(J)::value * 32 * C::RB>(ab); });
+    };
+    auto mfma_step = [&](auto KSC) {
+        constexpr int b = decltype(KSC)::value & 1;
+#pragma unroll
+        for (int i = 0; i < C::MI; ++i) asm volatile("" : "+v"(af[b][i]));     // tie the fragments to the preceding wait
+#pragma unroll
+        for (int j = 0; j < C::NI; ++j) asm volatile("" : "+v"(bfr[b][j]));
+#pragma unroll
+        for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b][j], af[b][i], acc[i][j], 0, 0, 0);
+    };
+
+    for (int s = 0; s < C::NS - 1; ++s) issue(s * C::STAGE, L0, LN, true);
+    int cstage = 0, fstage = (C::NS - 1) * C::STAGE;    // stage to compute on / stage that is free to refill
+#pragma unroll 1
+    for (int kt = 0; kt < nk; ++kt) {
+        // this step's stage has landed (own loads: vmcnt; the others': barrier) and every wavefront has
+        // finished reading the stage of the step before, which the loads issued during this step overwrite
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(C::LPW * (C::NS - 2)) : "memory");
+        read_frags(std::integral_constant<int, 0>{}, cstage);
+        static_for<C::KS>([&](auto KSC) {
+            constexpr int ks = decltype(KSC)::value;
+            if constexpr (ks + 1 < C::KS) {
+                read_frags(std::integral_constant<int, ks + 1>{}, cstage);
+                asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(C::MI + C::NI) : "memory");   // in order: step ks has arrived
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);
+            mfma_step(KSC);
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+            // The refill of the freed stage goes out in KS slices, each behind a burst of MFMAs: a load
+            // instruction blocks the wavefront while the compute unit's load queue is full (a stage is
+            // 0.4 ... 1 k clocks of that queue's time), and issued in one piece after the barrier that time
+            // was spent before the first MFMA of the step instead of under the MFMAs.
+            constexpr int h0 = ks * C::LPW / C::KS, h1 = (ks + 1) * C::LPW / C::KS;
+            issue(fstage, std::integral_constant<int, h0>{}, std::integral_constant<int, h1>{}, ks + 1 == C::KS);
+        });
+        fstage = cstage;
+        cstage = cstage + C::STAGE == C::NS * C::STAGE ? 0 : cstage + C::STAGE;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the repeated loads of the last steps have landed too
+    __syncthreads();
+    store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
+}
+
 // Second kernel of a split contraction: adds the nsplit partial tiles in index order (so the result
 // does not depend on timing) and writes C through the column map. One thread per group of four
 // consecutive columns (one float4 of the partial tile, which is in accumulator order: element e of
@@ -411,12 +594,12 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s, bool allow_split = false
     // 17-24 % faster; with a cache-resident output the batch-major order is up to 20 % faster).
     const bool runs_share_lines = vec && d.c_div > 1 && d.c_div < 64 && d.c_hi != d.c_div &&
                                   (int64_t)d.M * d.c_rs * 2 >= (256ll << 20);
-    const bool gfast = (!vec || runs_share_lines) && d.G > 1 && (int64_t)tiles_m * tiles_n * d.G < (1ll << 31);
+    const bool gfast = (!vec || runs_share_lines) && d.G > 1;
     const int64_t ntiles = (int64_t)tiles_m * tiles_n * d.G;
     SplitPlan sp = split_plan(ntiles, d.K);
     if (!allow_split || !d.split_scratch || (size_t)sp.nsplit * ntiles * BM * BN * sizeof(float) > d.split_scratch_bytes)
         sp = SplitPlan{1, (d.K + C::BK - 1) / C::BK};
-    dim3 grid(gfast ? (unsigned)(tiles_m * tiles_n * d.G) : (unsigned)(tiles_m * tiles_n), gfast ? 1u : (unsigned)d.G, (unsigned)sp.nsplit);
+    dim3 grid((unsigned)ntiles, 1u, (unsigned)sp.nsplit);
     if (d.K % C::BK)
         hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0, sp.kspan);
     else
@@ -431,12 +614,33 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s, bool allow_split = false
     return e;
 }
 
+template <int BM, int BN, int WGM, int WGN, int BK, int NS>
+hipError_t launch_deep(const GemmDesc& d, hipStream_t s) {
+    using C = DeepCfg<BM, BN, WGM, WGN, BK, NS>;
+    static LdsLimitOnce lds_limit;
+    if (hipError_t e = lds_limit.set({(const void*)gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, false>,
+                                      (const void*)gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, true>}, C::LDS_BYTES); e != hipSuccess) return e;
+    const int tiles_m = (int)((d.M + BM - 1) / BM);
+    const int tiles_n = (d.N + BN - 1) / BN;
+    const bool vec = c_map_vectorizes(d);
+    const bool gfast = !vec && d.G > 1;
+    dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * d.G), 1u, 1u);
+    if (d.K % BK)
+        hipLaunchKernelGGL((gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+    else
+        hipLaunchKernelGGL((gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+    return hipGetLastError();
+}
+
+// deep steps need the segments of a segmented contraction index to be whole steps
+inline bool deep_ok(const GemmDesc& d, int bk) { return d.a_seg == 0 || d.a_seg % bk == 0; }
+
 }  // namespace
 
 bool mfma_gemm_supported(const GemmDesc& d) {
     return d.b_ks == 1 && d.K % 8 == 0 && d.a_rs % 8 == 0 && d.a_gs % 8 == 0 && d.b_rs % 8 == 0 &&
            d.b_gs % 8 == 0 && aligned16(d.A) && aligned16(d.B) && d.M > 0 && d.N > 0 && d.K > 0 &&
-           (int64_t)((d.M + 63) / 64) * ((d.N + 63) / 64) < (1ll << 30) && d.G <= 65535 && dma_offsets_fit(d, 256) &&
+           (int64_t)((d.M + 63) / 64) * ((d.N + 63) / 64) * d.G < (1ll << 30) && dma_offsets_fit(d, 256) &&
            (d.a_seg == 0 || (d.a_seg % 32 == 0 && d.a_seg_stride % 8 == 0));
 }
 
@@ -461,9 +665,18 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // ahead of 200 by 10-30 % wherever the two differ (e.g. 11008 -> 4096 at 640 tokens: 144 -> 98 us,
     // 160 tiles of 128 x 128 in one round instead of 320 of 128 x 64 in two) and 128 behind both
     constexpr int64_t kFill = 160;
-    if (d.M > 64 && d.N > 64 && tiles(128, 128) >= kFill) return launch_dma<128, 128, 2, 2>(d, s);
-    if (d.M > 64 && tiles(128, 64) >= kFill) return launch_dma<128, 64, 2, 2>(d, s);
-    if (d.N > 64 && tiles(64, 128) >= kFill) return launch_dma<64, 128, 2, 2>(d, s);
+    // Calls that are a single round of workgroups (at most one per compute unit) take deep steps of 128
+    // (64 for the 128 x 128 tile) contraction indices per barrier: every workgroup is alone on its compute
+    // unit, so nothing else hides the fixed cost of a step. Measured on the 4096- and 11008-wide layers at
+    // 256 ... 2048 tokens: 5-25 % faster for one round; with more workgroups than compute units the
+    // 32-deep steps, whose smaller LDS footprint lets two or three workgroups share a compute unit, stay.
+    auto one_round = [&](int bm, int bn) { return d.K >= 256 && deep_ok(d, 128) && tiles(bm, bn) <= 256; };
+    if (d.M > 64 && d.N > 64 && tiles(128, 128) >= kFill)
+        return one_round(128, 128) ? launch_deep<128, 128, 2, 2, 64, 4>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
+    if (d.M > 64 && tiles(128, 64) >= kFill)
+        return one_round(128, 64) ? launch_deep<128, 64, 2, 2, 128, 3>(d, s) : launch_dma<128, 64, 2, 2>(d, s);
+    if (d.N > 64 && tiles(64, 128) >= kFill)
+        return one_round(64, 128) ? launch_deep<64, 128, 2, 2, 128, 3>(d, s) : launch_dma<64, 128, 2, 2>(d, s);
     // few tiles and a long contraction: 64 x 64 tiles, contraction index split over several workgroups
     // Few tiles and a long contraction index that would be split (two launches: the parts, then their
     // sum), small weights: the weight-streaming kernel over tiles of 32 tokens instead, one launch.
@@ -479,7 +692,8 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
         if (est_us <= 6.5 || (wgs >= 128 && wgs <= 256 && est_us <= 9.0)) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
     }
     if (d.split_scratch && split_plan(tiles(64, 64), d.K).nsplit > 1) return launch_dma<64, 64, 2, 2>(d, s, true);
-    if (tiles(64, 64) >= kFill || (d.M <= 64 && d.N <= 64)) return launch_dma<64, 64, 2, 2>(d, s);
+    if (tiles(64, 64) >= kFill || (d.M <= 64 && d.N <= 64))
+        return one_round(64, 64) ? launch_deep<64, 64, 2, 2, 128, 4>(d, s) : launch_dma<64, 64, 2, 2>(d, s);
     // Nothing fills the chip (a product of some tens of tokens with weights that are not split, e.g.
     // the dense reference at 33 ... 96 tokens): the weight-streaming kernel over tiles of 32 tokens puts
     // every compute unit on the stream, where the few tiles below would walk the whole contraction
