@@ -21,29 +21,42 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 
 // Tile and batch index of this workgroup. The grid is one-dimensional over all tiles of all batches;
-// workgroup ids are remapped so that each XCD owns a contiguous range of logical ids. Normally the
-// batch index is the SLOWEST logical index: an XCD then works on one batch (or a few) at a time, so
-// the operand panels that meet in its L2 are those of that batch only (with 4 batches and a few
-// hundred tokens every XCD used to fetch the whole activation matrix), and within a batch the tiles
-// are walked in groups of 8 row tiles per column tile. With a scattering column map (gfast) the batch
-// index varies FASTEST instead, so the G workgroups that interleave their columns into the same
-// cache lines run side by side on one XCD and their partial-line writes merge in its L2.
-__device__ inline void workgroup_tile(const GemmDesc& d, int tiles_m, int tiles_n, int gfast, int& g, int& tile_m, int& tile_n) {
+// workgroup ids are remapped so that each XCD owns a contiguous range of logical ids. Three orders:
+// 0, batch index SLOWEST: an XCD works on one batch (or a few) at a time, so the operand panels that
+//    meet in its L2 are those of that batch only (with 4 batches and a few hundred tokens every XCD
+//    used to fetch the whole activation matrix); within a batch, groups of 8 row tiles per column tile.
+//    For operands that stay in the caches.
+// 2, groups of 8 row tiles with ALL batches of the group together: the batches of every BLR product
+//    interleave inside the rows of the A operand (X[T][b][p], Z'[T][b][r], A[T][b][r]), so this order
+//    streams whole rows of a large A from HBM, where order 0 picks one batch's slice out of every row
+//    (stage 3 of BLAST with 16 blocks at 8192 tokens: 96 us against 139 us).
+// 1, batch index FASTEST, for scattering column maps: the G workgroups that interleave their columns
+//    into the same cache lines run side by side on one XCD and their partial-line writes merge in its L2.
+__device__ inline void workgroup_tile(const GemmDesc& d, int tiles_m, int tiles_n, int order, int& g, int& tile_m, int& tile_n) {
     constexpr int GM = 8;
     const int per_batch = tiles_m * tiles_n;
     const int lg = xcd_contiguous(blockIdx.x, per_batch * d.G);
-    int logical;
-    if (gfast) {
+    const int group_size = GM * tiles_n;                // tiles of one batch in a group of GM row tiles
+    int first_m, in_group;
+    if (order == 1) {                                   // batch index fastest
         g = lg % d.G;
-        logical = lg / d.G;
-    } else {
+        const int logical = lg / d.G;
+        first_m = (logical / group_size) * GM;
+        in_group = logical % group_size;
+    } else if (order == 2) {                            // groups of row tiles, all batches of a group together
+        const int rg = lg / (group_size * d.G);         // (only the last group may have fewer than GM row tiles)
+        first_m = rg * GM;
+        const int gm_here = tiles_m - first_m < GM ? tiles_m - first_m : GM;
+        const int rest = lg - rg * group_size * d.G;
+        g = rest / (gm_here * tiles_n);
+        in_group = rest - g * gm_here * tiles_n;
+    } else {                                            // batch index slowest
         g = lg / per_batch;
-        logical = lg - g * per_batch;
+        const int logical = lg - g * per_batch;
+        first_m = (logical / group_size) * GM;
+        in_group = logical % group_size;
     }
-    const int group_size = GM * tiles_n;
-    const int first_m = (logical / group_size) * GM;
     const int gm = tiles_m - first_m < GM ? tiles_m - first_m : GM;
-    const int in_group = logical % group_size;
     tile_m = first_m + in_group % gm;
     tile_n = in_group / gm;
 }
@@ -167,14 +180,14 @@ struct DmaCfg {
 
 // TAIL: K is not a multiple of 32, the last step is partial
 template <int BM, int BN, int WGM, int WGN, int NS, bool TAIL>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int gfast, int kspan) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int order, int kspan) {
     using C = DmaCfg<BM, BN, WGM, WGN, NS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     int g, tile_m, tile_n;
-    workgroup_tile(d, tiles_m, tiles_n, gfast, g, tile_m, tile_n);
+    workgroup_tile(d, tiles_m, tiles_n, order, g, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     const int n0 = tile_n * BN;
     // Split contraction: workgroup z of a tile covers k steps [z kspan, (z+1) kspan) and leaves its fp32
@@ -361,14 +374,14 @@ struct DeepCfg {
 };
 
 template <int BM, int BN, int WGM, int WGN, int BKT, int NS, bool TAIL>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_deep_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int gfast) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_deep_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int order) {
     using C = DeepCfg<BM, BN, WGM, WGN, BKT, NS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     int g, tile_m, tile_n;
-    workgroup_tile(d, tiles_m, tiles_n, gfast, g, tile_m, tile_n);
+    workgroup_tile(d, tiles_m, tiles_n, order, g, tile_m, tile_n);
     const int64_t m0 = (int64_t)tile_m * BM;
     const int n0 = tile_n * BN;
     const unsigned char* Abase = (const unsigned char*)((const bf16_t*)d.A + (int64_t)g * d.a_gs + m0 * d.a_rs);
@@ -565,6 +578,14 @@ inline SplitPlan split_plan(int64_t ntiles, int K) {
     return sp;
 }
 
+// order of the tiles over the XCDs (see workgroup_tile): the A operand of a batched product beyond what
+// the memory-side cache holds is streamed by whole rows
+inline int tile_order(const GemmDesc& d, bool gfast) {
+    if (gfast) return 1;
+    if (d.G > 1 && d.a_gs < d.a_rs && (int64_t)d.M * d.a_rs * 2 > (128ll << 20)) return 2;
+    return 0;
+}
+
 // can 8 consecutive (8-aligned) tile columns be stored as one 16-byte vector?
 inline bool c_map_vectorizes(const GemmDesc& d) {
     if (!aligned16(d.C) || d.c_rs % 8 || d.N % 8 || d.c_gs % 8) return false;
@@ -600,10 +621,11 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s, bool allow_split = false
     if (!allow_split || !d.split_scratch || (size_t)sp.nsplit * ntiles * BM * BN * sizeof(float) > d.split_scratch_bytes)
         sp = SplitPlan{1, (d.K + C::BK - 1) / C::BK};
     dim3 grid((unsigned)ntiles, 1u, (unsigned)sp.nsplit);
+    const int order = tile_order(d, gfast);
     if (d.K % C::BK)
-        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0, sp.kspan);
+        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order, sp.kspan);
     else
-        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0, sp.kspan);
+        hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order, sp.kspan);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || sp.nsplit == 1) return e;
     if constexpr (BM == 64 && BN == 64 && WGM == 2 && WGN == 2) {   // the only tile the split plan is used with
@@ -625,10 +647,11 @@ hipError_t launch_deep(const GemmDesc& d, hipStream_t s) {
     const bool vec = c_map_vectorizes(d);
     const bool gfast = !vec && d.G > 1;
     dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * d.G), 1u, 1u);
+    const int order = tile_order(d, gfast);
     if (d.K % BK)
-        hipLaunchKernelGGL((gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+        hipLaunchKernelGGL((gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
     else
-        hipLaunchKernelGGL((gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, gfast ? 1 : 0);
+        hipLaunchKernelGGL((gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
     return hipGetLastError();
 }
 
