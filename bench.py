@@ -295,7 +295,8 @@ def run_sweep(steps, warmup, names, variants=False, cpu_seconds=0.0, write=False
             if cfg["op"] == "monarch":                      # the paper's optimisation 3: blocked output order, no final permutation
                 ms_alt["blocked_output"] = time_graph(lambda: layer.prepared(B.MONARCH_OUT_BLOCKED), steps, warmup)
             if variants and cfg["op"] == "blast" and st is not None:     # both executions for large ranks, forced
-                for key, fl in (("fused_stage12", B.BLAST_FUSED_STAGE12), ("three_kernels", B.BLAST_THREE_KERNELS)):
+                for key, fl in (("fused_stage12", B.BLAST_FUSED_STAGE12), ("three_kernels", B.BLAST_THREE_KERNELS),
+                                ("three_kernels_z_fp8", B.BLAST_Z_FP8)):
                     ws_alt = torch.empty(max(B.blast_workspace_bytes(T, cfg["n_in"], cfg["n_out"], cfg["b"], cfg["r"], B.BF16,
                                                                      layer.flags | fl), 16), dtype=torch.uint8, device="cuda")
                     mk = lambda: B.prepared(B.blast_forward, layer.X, layer.U, None, layer.packed, layer.Y, layer.b, layer.r,

@@ -70,6 +70,14 @@ typedef void* blr_stream;      /* a hipStream_t */
  * force one of them (mutually exclusive) so that tests and the benchmark can run both. */
 #define BLR_BLAST_FUSED_STAGE12     0x800u
 #define BLR_BLAST_THREE_KERNELS     0x1000u
+/* flag of blr_blast_forward: quantised intermediate (the paper's "Limitation and Future Work": quantising the
+ * intermediate activations). Runs execution (b) with Z = X_j V_j stored as 8-bit floats (OCP E4M3: 4 exponent
+ * and 3 mantissa bits, round to nearest even from the fp32 accumulator, clamped to the largest finite value
+ * 448) between the stage-1 product and the coupling, which widens them again; A and Y are as without the flag.
+ * Halves the bytes of the Z round trip at the price of one more rounding of 2^-4 relative size per element of
+ * Z. bf16 only, 16 | r, not for layers the single-kernel path serves (BLR_ERR_UNSUPPORTED, workspace query 0);
+ * cannot be combined with BLR_BLAST_FUSED_STAGE12. The workspace query takes the flag. */
+#define BLR_BLAST_Z_FP8             0x8000u
 /* flags of the Monarch and low-rank forwards (bf16). Two executions exist: (a) two GEMM kernels with
  * the intermediate in the workspace, and (b) ONE kernel that keeps the intermediate on chip (the
  * full fusion of the paper's appendix on low-rank layers, applied to every Monarch form), for narrow

@@ -30,6 +30,7 @@ ONLY_FIRST_STAGE, ONLY_LAST_STAGE = 0x200, 0x400
 BLAST_FUSED_STAGE12 = 0x800
 BLAST_THREE_KERNELS = 0x1000
 MONARCH_FUSED, MONARCH_TWO_KERNELS = 0x2000, 0x4000
+BLAST_Z_FP8 = 0x8000
 
 EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forward",
            "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_bytes",

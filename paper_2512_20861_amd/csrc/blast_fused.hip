@@ -143,7 +143,9 @@ __device__ __forceinline__ void store_a_tile(const unsigned char* Zs, bf16_t* __
 // The Z tile is read with full-line loads (8 lanes per 128-byte row segment) and transposed on its
 // way into LDS; blocks j and j+1 travel together so that every LDS write is a bf16 pair.
 // TNT tokens per workgroup: 64, or 32 when 64-token tiles would leave most of the chip idle.
-template <int TNT>
+// Z8: Z holds 8-bit floats (E4M3, written by the stage-1 product of the quantised-intermediate execution),
+// one byte per element in the same [T][b][r] order; they are widened to bf16 (exactly) on their way into LDS.
+template <int TNT, bool Z8>
 __global__ __launch_bounds__(512)
 void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
                            int64_t T, int b, int r, int tiles_r, int nblk) {
@@ -179,8 +181,21 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
             int64_t tok = t0 + t;
             if (tok > T - 1) tok = T - 1;
             const int j1 = 2 * jp + 1 < b ? 2 * jp + 1 : 2 * jp;
-            v0[u] = *(const uint4*)(Z + (tok * b + 2 * jp) * r + rho);
-            v1[u] = *(const uint4*)(Z + (tok * b + j1) * r + rho);
+            if constexpr (Z8) {
+                const unsigned char* Zb = (const unsigned char*)Z;
+                const uint2 q0 = *(const uint2*)(Zb + (tok * b + 2 * jp) * r + rho);
+                const uint2 q1 = *(const uint2*)(Zb + (tok * b + j1) * r + rho);
+                auto widen = [](uint2 q) {              // 8 x E4M3 -> 8 x bf16 (every E4M3 value is a bf16 value)
+                    const auto a = __builtin_amdgcn_cvt_pk_f32_fp8((int)q.x, false), bq = __builtin_amdgcn_cvt_pk_f32_fp8((int)q.x, true);
+                    const auto c = __builtin_amdgcn_cvt_pk_f32_fp8((int)q.y, false), dq = __builtin_amdgcn_cvt_pk_f32_fp8((int)q.y, true);
+                    return make_uint4(pack2_bf16(a[0], a[1]), pack2_bf16(bq[0], bq[1]), pack2_bf16(c[0], c[1]), pack2_bf16(dq[0], dq[1]));
+                };
+                v0[u] = widen(q0);
+                v1[u] = widen(q1);
+            } else {
+                v0[u] = *(const uint4*)(Z + (tok * b + 2 * jp) * r + rho);
+                v1[u] = *(const uint4*)(Z + (tok * b + j1) * r + rho);
+            }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -424,23 +439,24 @@ hipError_t launch_blast_stage12(const void* X, const void* Va, const void* Sp, v
                  : launch_stage12_inst<128>(X, Va, Sp, A, T, n_in, b, r, s);
 }
 
-template <int TNT>
+template <int TNT, bool Z8>
 static hipError_t launch_coupling_inst(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
     constexpr int lds = TR * (TNT * 32 + 8);
     static LdsLimitOnce lds_limit;
-    if (hipError_t e = lds_limit.set({(const void*)blast_coupling_kernel<TNT>}, lds); e != hipSuccess) return e;
+    if (hipError_t e = lds_limit.set({(const void*)blast_coupling_kernel<TNT, Z8>}, lds); e != hipSuccess) return e;
     const int tiles_t = (int)((T + TNT - 1) / TNT), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
-    hipLaunchKernelGGL(blast_coupling_kernel<TNT>, dim3((unsigned)nblk), dim3(512), lds, s,
+    hipLaunchKernelGGL((blast_coupling_kernel<TNT, Z8>), dim3((unsigned)nblk), dim3(512), lds, s,
                        (const bf16_t*)Z, (const bf16_t*)Sp, (bf16_t*)A, T, b, r, tiles_r, nblk);
     return hipGetLastError();
 }
 
-hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s) {
+hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s, bool z_fp8) {
     // 64-token tiles unless they would leave most compute units without a workgroup
     const int64_t tiles64 = ((T + 63) / 64) * ((r + TR - 1) / TR);
-    if (tiles64 < 200) return launch_coupling_inst<32>(Z, Sp, A, T, b, r, s);
-    return launch_coupling_inst<64>(Z, Sp, A, T, b, r, s);
+    if (z_fp8) return tiles64 < 200 ? launch_coupling_inst<32, true>(Z, Sp, A, T, b, r, s) : launch_coupling_inst<64, true>(Z, Sp, A, T, b, r, s);
+    if (tiles64 < 200) return launch_coupling_inst<32, false>(Z, Sp, A, T, b, r, s);
+    return launch_coupling_inst<64, false>(Z, Sp, A, T, b, r, s);
 }
 
 namespace {

@@ -35,6 +35,11 @@ bool blast_mfma_shape_ok(int n_in, int b, int r) {
     return b <= 16 && (n_in / b) % 8 == 0 && r % 8 == 0 && r < (1 << 20);
 }
 
+// The quantised-intermediate execution (Z as 8-bit floats between the stage-1 product and the coupling) exists
+// for bf16 layers on the matrix-core kernels of the three-kernel path, with packed factors whose buffer holds
+// the stage-1 operand, and 16 | r (16 consecutive rank indices are one 16-byte store).
+bool blast_z_fp8_ok(int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags);
+
 // Where the re-laid-out BLAST factors live inside the packed buffer.
 struct PackLayout {
     bool full;                       // served by the single-kernel path: fragment-ordered V and U
@@ -97,7 +102,8 @@ BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt,
         pl.off_A = off; off += align_up((size_t)T * per_token);
         pl.off_Z = off; off += align_up((size_t)T * per_token);
     } else {
-        if (blast_full_fusion_supported(T, n_in, n_out, b, r)) pl.path = BlastPlan::MFMA_FULL;
+        if (flags & BLR_BLAST_Z_FP8) pl.path = BlastPlan::MFMA_THREE;      // (the caller has checked blast_z_fp8_ok)
+        else if (blast_full_fusion_supported(T, n_in, n_out, b, r)) pl.path = BlastPlan::MFMA_FULL;
         else if (!(flags & BLR_BLAST_THREE_KERNELS) && blast_fused_supported(T, n_in, b, r) &&
                  ((flags & BLR_BLAST_FUSED_STAGE12) || blast_fused_tiles(T, r) >= fused_min_tiles(n_in, b))) pl.path = BlastPlan::MFMA_STAGE12;
         else pl.path = BlastPlan::MFMA_THREE;
@@ -107,12 +113,17 @@ BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt,
             if (c < 256) c = 256;
             if (c < T) pl.chunk = c;
             pl.off_A = off; off += align_up((size_t)pl.chunk * per_token);
-            pl.off_Z = off; off += align_up((size_t)pl.chunk * per_token);
+            pl.off_Z = off; off += align_up((size_t)pl.chunk * per_token / ((flags & BLR_BLAST_Z_FP8) ? 2 : 1));   // one byte per element of an 8-bit Z
         }
         if (!packed) { pl.off_pack = off; off += pack_layout(n_in, n_out, b, r).total; }
     }
     pl.total = off;
     return pl;
+}
+
+bool blast_z_fp8_ok(int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
+    return dt == BLR_BF16 && !(flags & (BLR_FORCE_GENERIC | BLR_BLAST_FUSED_STAGE12)) && blast_mfma_shape_ok(n_in, b, r) && r % 16 == 0 &&
+           !pack_layout(n_in, n_out, b, r).full;
 }
 
 blr_status run_pack(const void* U, const void* S, const void* V, void* packed, int n_in, int n_out, int b, int r, hipStream_t s) {
@@ -323,6 +334,8 @@ static blr_status blast_run(const void* X, const void* U, const void* S, const v
     }
     // three kernels per chunk of tokens: stage-1 GEMM -> Z, MFMA coupling Z -> A, stage-3 GEMM
     s1.B = Vt; s1.b_gs = (int64_t)q * r; s1.b_rs = q; s1.b_ks = 1; s1.b_div = 0;
+    const bool z8 = flags & BLR_BLAST_Z_FP8;
+    s1.c_fp8 = z8 ? 1 : 0;                              // Z[t][j][rho] as bytes: the same strides, counted in bytes
     for (int64_t c0 = 0; c0 < T; c0 += pl.chunk) {
         const int64_t tc = T - c0 < pl.chunk ? T - c0 : pl.chunk;
         if (first) {
@@ -331,7 +344,9 @@ static blr_status blast_run(const void* X, const void* U, const void* S, const v
             blr_status st = run_gemm(s1, dt, true, s);
             if (st != BLR_OK) return st;
             // few tokens: the 64-token tiles of the MFMA coupling would be mostly padding; one thread per output element then
-            st = from_hip(tc <= kSmallCouplingTokens ? launch_coupling_small(Zws, pack + pk.off_Sc, Aws, tc, b, r, s) : launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
+            st = from_hip(z8 ? launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s, true)
+                          : tc <= kSmallCouplingTokens ? launch_coupling_small(Zws, pack + pk.off_Sc, Aws, tc, b, r, s)
+                                                       : launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
             if (st != BLR_OK) return st;
         }
         if (last) {
@@ -508,6 +523,7 @@ blr_status blr_monarch_permute_first_factor(const void* R, void* Rp, int n_in, i
 
 size_t blr_blast_workspace_bytes(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
     if (!blast_shape_ok(T, n_in, n_out, b, r) || !dtype_ok(dt)) return 0;
+    if ((flags & BLR_BLAST_Z_FP8) && !blast_z_fp8_ok(n_in, n_out, b, r, dt, flags)) return 0;
     return blast_plan(T, n_in, n_out, b, r, dt, flags).total;
 }
 
@@ -531,11 +547,13 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
                              void* workspace, size_t workspace_bytes, blr_stream stream) {
     if (!U || !V || (!S && !(flags & BLR_BLAST_PACKED))) return BLR_ERR_INVALID_ARG;
     if (!blast_shape_ok(T, n_in, n_out, b, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
-    if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_BLAST_FUSED_STAGE12 | BLR_BLAST_THREE_KERNELS)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_BLAST_FUSED_STAGE12 | BLR_BLAST_THREE_KERNELS | BLR_BLAST_Z_FP8)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_BLAST_Z_FP8) && (flags & (BLR_BLAST_FUSED_STAGE12 | BLR_FORCE_GENERIC))) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_BLAST_FUSED_STAGE12) && (flags & BLR_BLAST_THREE_KERNELS)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_BLAST_PACKED) && (dt != BLR_BF16 || b > 16 || (flags & BLR_FORCE_GENERIC))) return BLR_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(U) || !aligned16(S) || !aligned16(V) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_BLAST_Z_FP8) && !blast_z_fp8_ok(n_in, n_out, b, r, dt, flags)) return BLR_ERR_UNSUPPORTED;
     if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null
     if (!X || !Y) return BLR_ERR_INVALID_ARG;
     return blast_run(X, U, S, V, Y, T, n_in, n_out, b, r, 1, dt, flags, workspace, workspace_bytes, (hipStream_t)stream);

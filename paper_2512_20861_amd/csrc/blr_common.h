@@ -96,6 +96,8 @@ struct GemmDesc {
     void* C; int64_t c_rs; int64_t c_gs; int c_div; int64_t c_hi; int64_t c_lo;
     int64_t M; int N; int K; int G;
     float* split_scratch; size_t split_scratch_bytes;   // optional: room for fp32 partial tiles of a split contraction
+    int c_fp8;                         // C is stored as 8-bit floats (E4M3, round to nearest even, clamped to +-448): one byte per
+                                       // element, strides and offsets of C then count bytes; tile kernels of launch_gemm_mfma only
 };
 
 enum class DType { F32 = 0, BF16 = 1 };
@@ -120,6 +122,8 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s);
 // scratch bytes with which launch_gemm_mfma may split the contraction index of an (M, N, K, G) product
 // over several workgroups per tile (0: it would not split)
 size_t gemm_split_scratch_bytes(int64_t M, int N, int K, int G);
+// can C of this product be written as 8-bit floats (16 consecutive columns = 16 contiguous, aligned bytes)?
+bool gemm_fp8_store_supported(const GemmDesc& d);
 // few tokens (M <= 32): weight-streaming kernel, split-K inside the workgroup; same alignment contract
 bool skinny_gemm_supported(const GemmDesc& d);
 hipError_t launch_gemm_skinny(const GemmDesc& d, bool cvec, hipStream_t s);
@@ -141,7 +145,7 @@ int64_t blast_fused_tiles(int64_t T, int r);                 // workgroups the f
 hipError_t launch_blast_stage12(const void* X, const void* Vt, const void* Sp, void* A,
                                 int64_t T, int n_in, int b, int r, hipStream_t s);
 // BLAST: stand-alone coupling on MFMA, Z[T][b][r] -> A[T][b][r] (bf16), S tiles from Sp[r][16][16]; needs r % 8 == 0, b <= 16
-hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s);
+hipError_t launch_blast_coupling(const void* Z, const void* Sp, void* A, int64_t T, int b, int r, hipStream_t s, bool z_fp8 = false);
 
 // BLAST: whole layer in one kernel for small ranks. Vf / Uf are V and U in MFMA-fragment order:
 //   Vf[j][nt][ks][lane][e] = V[j][ks*16 + (lane/32)*8 + e][nt*32 + lane%32]      (zero past q, r)

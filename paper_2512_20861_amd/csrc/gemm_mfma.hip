@@ -138,6 +138,46 @@ __device__ __forceinline__ void store_c_tile(const GemmDesc& d, const f32x16 (&a
     }
 }
 
+// The same epilogue with C stored as 8-bit floats (E4M3, the intermediate of a quantised-intermediate
+// execution): a lane's four consecutive columns become one 32-bit word (two v_cvt_pk_fp8_f32 after a
+// clamp to the format's largest finite value, 448), the tile goes through LDS with rows of BN + 16
+// bytes, and leaves as 16-byte stores of 16 consecutive columns. Column map: contiguous (host-checked).
+template <int BM, int BN, int WTM, int WTN, int MI, int NI, int THREADS>
+__device__ __forceinline__ void store_c_tile_fp8(const GemmDesc& d, const f32x16 (&acc)[MI][NI], unsigned char* Cs,
+                                                 int64_t m0, int n0, int g, int wm, int wn) {
+    constexpr int CSTR8 = BN + 16;
+    const int tid = threadIdx.x, lane = tid & 63;
+    auto q8 = [](float x) { return __builtin_amdgcn_fmed3f(x, -448.f, 448.f); };
+    {
+        const int mrow = wm * WTM + (lane & 31);
+        const int ncol = wn * WTN + 4 * (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    int w = __builtin_amdgcn_cvt_pk_fp8_f32(q8(acc[i][j][4 * q4]), q8(acc[i][j][4 * q4 + 1]), 0, false);
+                    w = __builtin_amdgcn_cvt_pk_fp8_f32(q8(acc[i][j][4 * q4 + 2]), q8(acc[i][j][4 * q4 + 3]), w, true);
+                    *(int*)(Cs + (mrow + i * 32) * CSTR8 + (ncol + j * 32 + 8 * q4)) = w;
+                }
+    }
+    __syncthreads();
+    constexpr int CPRC = BN / 16;                       // groups of 16 columns per row
+    static_assert(THREADS % CPRC == 0, "a thread keeps its column group");
+    constexpr int RPS = THREADS / CPRC, SWEEPS = BM / RPS;
+    static_assert(BM % RPS == 0, "whole sweeps");
+    const int cc = tid % CPRC, row0 = tid / CPRC;
+    const int n = n0 + cc * 16;
+    if (n >= d.N) return;
+    unsigned char* dst = (unsigned char*)d.C + (m0 + row0) * d.c_rs + (int64_t)g * d.c_gs + n;
+    const unsigned char* src = Cs + row0 * CSTR8 + cc * 16;
+    const int64_t rows_left = d.M - m0 - row0;
+#pragma unroll
+    for (int s0 = 0; s0 < SWEEPS; ++s0)
+        if ((int64_t)s0 * RPS < rows_left) *(u32x4*)(dst + (int64_t)s0 * RPS * d.c_rs) = *(const u32x4*)(src + s0 * (RPS * CSTR8));
+}
+
 // ---------------------------------------------------------------------------------------------
 // Operand tiles stream global -> LDS directly (global_load_lds): no staging registers and no LDS
 // store instructions, so the prefetch depth is set by LDS capacity (NS stages of BK = 32) instead of
@@ -337,7 +377,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, in
         return;
     }
     __syncthreads();
-    store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
+    if (d.c_fp8) store_c_tile_fp8<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn);
+    else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -516,7 +557,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_deep_kernel(GemmDesc d, i
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the repeated loads of the last steps have landed too
     __syncthreads();
-    store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
+    if (d.c_fp8) store_c_tile_fp8<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn);
+    else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
 }
 
 // Second kernel of a split contraction: adds the nsplit partial tiles in index order (so the result
@@ -667,6 +709,11 @@ bool mfma_gemm_supported(const GemmDesc& d) {
            (d.a_seg == 0 || (d.a_seg % 32 == 0 && d.a_seg_stride % 8 == 0));
 }
 
+bool gemm_fp8_store_supported(const GemmDesc& d) {
+    return mfma_gemm_supported(d) && aligned16(d.C) && d.N % 16 == 0 && d.c_rs % 16 == 0 && d.c_gs % 16 == 0 &&
+           d.c_div == 1 && d.c_hi == 1;
+}
+
 size_t gemm_split_scratch_bytes(int64_t M, int N, int K, int G) {
     if (M <= 32) return 0;                              // the few-token kernel splits inside its workgroups
     const int64_t ntiles = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * G;
@@ -675,6 +722,14 @@ size_t gemm_split_scratch_bytes(int64_t M, int N, int K, int G) {
 }
 
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
+    if (d.c_fp8) {                                      // 8-bit C: the tile kernels only (no weight-streaming kernel, no split contraction)
+        if (!gemm_fp8_store_supported(d)) return hipErrorInvalidValue;
+        auto tiles8 = [&](int bm, int bn) { return (int64_t)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.G; };
+        if (d.M > 128 && d.N > 128 && d.K > 128 && tiles8(256, 256) >= 160) return launch_dma<256, 256, 2, 4>(d, s);
+        if (d.M > 64 && d.N > 64 && tiles8(128, 128) >= 160) return launch_dma<128, 128, 2, 2>(d, s);
+        if (d.M > 64 && tiles8(128, 64) >= 160) return launch_dma<128, 64, 2, 2>(d, s);
+        return launch_dma<64, 64, 2, 2>(d, s);
+    }
     if (skinny_gemm_supported(d)) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
     constexpr int kSmallK = 128;     // very short contractions: 128 x 128 tiles, two workgroups per CU overlap prologue and epilogue
                                      // (measured at K = 256, M = 1024 ... 32768: 256 x 256 tiles are 16-23 % faster)

@@ -459,3 +459,44 @@ def test_monarch_group_first_factor_and_grouped_call(dtype):
     for m, l in enumerate(lays):
         ref = oracle.monarch_forward(X.f64, l.R.f64, l.L.f64, oracle.OUT_BLOCKED)
         assert gu.rel_err(Yh[:, m * n_out:(m + 1) * n_out], ref) <= gu.TOL[dtype]
+
+
+@pytest.mark.parametrize("shape", [(700, 1024, 512, 16, 256), (333, 2048, 1024, 16, 512), (2100, 768, 3072, 6, 192), (64, 1024, 1024, 8, 128)])
+def test_blast_quantised_intermediate(shape):
+    """BLAST with Z stored as E4M3 between the stage-1 product and the coupling (the paper's future work on
+    quantised intermediate activations) against the oracle that rounds Z the same way, at the stated bf16
+    bound; the distance to the UNQUANTISED oracle is printed (the price of the 8-bit intermediate)."""
+    gu = _gu()
+    B = gu.B
+    from oracle import quant
+    T, n_in, n_out, b, r = shape
+    lay = bi.blast_layer(n_in, n_out, b, r, "bf16", seed=21)
+    X = bi.activations(T, n_in, "bf16", seed=22)
+    Y = gu.to_f64(gu.run_blast(X, lay, B.BLAST_Z_FP8, packed=True))
+    Yq, Z = quant.blast_forward_qz(X.f64, lay.U.f64, lay.S.f64, lay.V.f64)
+    Yx = oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64)
+    err_q, err_x = gu.rel_err(Y, Yq), gu.rel_err(Y, Yx)
+    print(f"BLAST {n_in}->{n_out} b={b} r={r} T={T}, Z in E4M3: rel err {err_q:.3e} against the quantised oracle, "
+          f"{err_x:.3e} against the exact one (oracle's own quantisation distance {gu.rel_err(Yq, Yx):.3e}); max |Z| {np.abs(Z).max():.2f}")
+    assert err_q <= gu.TOL["bf16"]
+    # without the flag the same call is the unquantised three-kernel execution
+    Y3 = gu.to_f64(gu.run_blast(X, lay, B.BLAST_THREE_KERNELS, packed=True))
+    assert gu.rel_err(Y3, Yx) <= gu.TOL["bf16"]
+
+
+def test_blast_quantised_intermediate_status_codes():
+    gu = _gu()
+    B = gu.B
+    L = B.lib()
+    x = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    p = x.data_ptr()
+    # the single-kernel layer, r not a multiple of 16, fp32, and the fused execution cannot take the flag
+    assert L.blr_blast_workspace_bytes(100, 768, 768, 16, 96, B.BF16, B.BLAST_PACKED | B.BLAST_Z_FP8) == 0
+    assert L.blr_blast_forward(p, p, None, p, p, 100, 768, 768, 16, 96, B.BF16, B.BLAST_PACKED | B.BLAST_Z_FP8, p, 1 << 30, None) == B.ERR_UNSUPPORTED
+    assert L.blr_blast_forward(p, p, None, p, p, 100, 1024, 1024, 16, 264, B.BF16, B.BLAST_PACKED | B.BLAST_Z_FP8, p, 1 << 30, None) == B.ERR_UNSUPPORTED
+    assert L.blr_blast_forward(p, p, p, p, p, 100, 1024, 1024, 16, 256, B.F32, B.BLAST_Z_FP8, p, 1 << 30, None) == B.ERR_UNSUPPORTED
+    assert L.blr_blast_forward(p, p, None, p, p, 100, 1024, 1024, 16, 256, B.BF16, B.BLAST_PACKED | B.BLAST_Z_FP8 | B.BLAST_FUSED_STAGE12, p, 1 << 30, None) == B.ERR_INVALID_ARG
+    # Z takes half the bytes of A in the workspace
+    full = L.blr_blast_workspace_bytes(1000, 1024, 1024, 16, 256, B.BF16, B.BLAST_PACKED | B.BLAST_THREE_KERNELS)
+    half = L.blr_blast_workspace_bytes(1000, 1024, 1024, 16, 256, B.BF16, B.BLAST_PACKED | B.BLAST_Z_FP8)
+    assert full == 2 * 1000 * 16 * 256 * 2 and half == 1000 * 16 * 256 * 2 + 1000 * 16 * 256
