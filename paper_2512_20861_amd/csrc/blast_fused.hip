@@ -27,21 +27,46 @@ static_assert(ZS_BYTES % 16 == 0, "Zs is cleared with 16-byte stores");
 
 // stage 1 of the fused kernel: TT tokens x 64 ranks per workgroup, 8 wavefronts; TT = 128: every wavefront
 // computes a 32 x 32 part of the tile; TT = 64 (calls with too few 128-token tiles to fill the chip):
-// wavefronts 0..3 compute, all 8 move the operands and take part in the coupling
-constexpr int ST_BK = 64;                    // k elements per step: operand rows of 128 bytes = 8 pieces of 16 bytes
-constexpr int ST_NS = 6;                     // stages in LDS
-constexpr int ST_PD = ST_NS - 1;             // steps of loads in flight
-template <int TT>
+// wavefronts 0..3 compute, all 8 move the operands and take part in the coupling.
+// BK contraction indices per step (one barrier per step): 128 where the input blocks are whole numbers of
+// such chunks, 64 otherwise; 3 (128 tokens, 48 KB per stage) to 8 stages in LDS.
+template <int TT, int BK>
 struct StCfg {
+    static constexpr int RB = BK * 2;             // bytes of an operand row in a stage
+    static constexpr int PPR = RB / 16;           // 16-byte pieces per row
+    static constexpr int RPL = 1024 / RB;         // rows one direct load (64 lanes x 16 bytes) fills
+    static constexpr int SH = BK == 128 ? 0 : 1;  // swizzle: slot = piece ^ ((row >> SH) & (PPR - 1))
+    static constexpr int KS = BK / 16;            // k16 steps per stage
     static constexpr int ROWS = TT + TR;          // operand rows of one stage: X rows, then Vt rows
-    static constexpr int STAGE = ROWS * ST_BK * 2;
-    static constexpr int LDS = ST_NS * STAGE > ZS_BYTES ? ST_NS * STAGE : ZS_BYTES;
-    static constexpr int LPW = ROWS / 64;         // direct-to-LDS loads per wavefront and stage (8 rows each)
+    static constexpr int STAGE = ROWS * RB;
+    // stages in LDS: as many as 144 KB hold, 8 at most (a workgroup is alone on its compute unit, and with
+    // few tokens its steps are as long as a load takes to arrive divided by the steps in flight)
+    static constexpr int NS = 147456 / STAGE > 8 ? 8 : 147456 / STAGE;
+    static constexpr int PD = NS - 1;             // steps of loads in flight
+    static constexpr int CT = TT == 128 ? 64 : TT;                // tokens the coupling takes per pass
+    static constexpr int ZS = TR * (CT * 32 + 8);                 // bytes of Zs[rho][t][j] for one pass
+    static constexpr int LDS = NS * STAGE > ZS ? NS * STAGE : ZS;
+    static constexpr int LPW = ROWS / RPL / 8;    // direct-to-LDS loads per wavefront and stage
+    static constexpr int CW = TT / 16 < 8 ? TT / 16 : 8;          // wavefronts that own a 32 x 32 part of the tile
     static_assert(TT == 128 || TT == 64, "token tiles of the fused kernel");
+    static_assert(BK == 64 || BK == 128, "step depths of the fused kernel");
     static_assert(LDS <= 160 * 1024, "LDS budget");
-    static_assert(ROWS % 64 == 0, "every wavefront issues the same number of loads per stage");
-    static_assert(LPW * (ST_PD - 1) < 64, "vmcnt range");
+    static_assert(ROWS % (RPL * 8) == 0 && TT % RPL == 0, "every wavefront issues the same number of loads per stage, none straddling X and Vt");
+    static_assert(LPW * (PD - 1) < 64, "vmcnt range");
 };
+
+// asynchronous 16-byte LDS read the compiler does not see as a memory access (reads it can see make it
+// wait for ALL outstanding direct-to-LDS loads); the caller waits on lgkmcnt itself and passes the
+// value through tie_to_wait after that wait, before the first use
+__device__ __forceinline__ bf16x8 lds_read_b128_async(unsigned addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+__device__ __forceinline__ bf16x8 tie_to_wait(bf16x8 v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
 
 
 // Coupling of one 64-token x 64-rank tile whose Z values sit in LDS as Zs[rho][t][j] (bf16):
@@ -222,19 +247,24 @@ void blast_coupling_kernel(const bf16_t* __restrict__ Z, const bf16_t* __restric
     store_a_tile<8, decltype(same), TNT>(Zs, A, T, t0, rho0, b, r, same);
 }
 
-// Stage 1 + coupling. Per step (one chunk of 64 input columns of one input block j) a stage of LDS
-// holds 128 X rows and 64 Vt rows of 128 bytes; its 16-byte pieces are XOR-swizzled by (row / 2) & 7 so
-// that the 16 lanes a ds_read_b128 serves per clock (16 consecutive rows) hit 16 different 16-byte
-// columns of the 64 banks, without the row padding that a direct-to-LDS load cannot produce (lane l of
-// such a load always lands at base + 16 l). Loads for step s + ST_PD are issued while step s computes;
-// vmcnt counts them, so one wait + one barrier per step is all the synchronisation.
-// The fragment reads are inline assembly with their own lgkmcnt waits: reads that the compiler can
-// see make it wait for ALL outstanding direct-to-LDS loads first.
-// The chunks are aligned to 64 GLOBAL input columns (n_in is a multiple of 64), not to the start of the
-// block: block j walks chunks floor(j q / 64) .. ceil((j+1) q / 64) - 1, so every X piece is one whole
-// 128-byte line whatever q is. The columns of a boundary chunk that belong to a neighbouring block
+// Stage 1 + coupling. Per step (one chunk of BK input columns of one input block j) a stage of LDS holds
+// TT X rows and 64 Vt rows of 2 BK bytes; its 16-byte pieces are XOR-swizzled by the row so that the 16
+// lanes a ds_read_b128 serves per clock (16 consecutive rows) hit 16 different 16-byte columns of the 64
+// banks, without the row padding that a direct-to-LDS load cannot produce (lane l of such a load always
+// lands at base + 16 l). Loads for step s + PD are issued right after the barrier of step s, while the
+// matrix pipe is idle (a load issued while the SIMD's matrix pipe is busy takes three times as long to
+// issue); vmcnt counts them, so one wait + one barrier per step is all the synchronisation.
+// The fragment reads are inline assembly with their own lgkmcnt waits (reads that the compiler can see
+// make it wait for ALL outstanding direct-to-LDS loads first) and go out in batches of two k16 steps,
+// two batches ahead of the MFMAs that consume them.
+// A step costs a fixed 250 ... 300 clocks of barrier, waits and cursor arithmetic whatever its depth
+// (measured with the loads, the reads and the MFMAs removed in turn), which is why it is as deep as LDS
+// allows, and why the fetch cursor only does arithmetic at block boundaries.
+// The chunks are aligned to BK GLOBAL input columns (n_in is a multiple of BK), not to the start of the
+// block: block j walks chunks floor(j q / BK) .. ceil((j+1) q / BK) - 1, so every X piece is whole
+// 128-byte lines whatever q is. The columns of a boundary chunk that belong to a neighbouring block
 // meet zeros in Va (the chunk-aligned copy of Vt, rows of qp elements), so nothing has to be masked.
-template <int TT>
+template <int TT, int BK>
 __global__ __launch_bounds__(512)
 void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Va,
                           const bf16_t* __restrict__ Sp, bf16_t* __restrict__ A,
@@ -242,26 +272,27 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    using C = StCfg<TT>;
-    constexpr int ST_STAGE = C::STAGE, ST_LPW = C::LPW;
-    const bool computes = TT == 128 || wave < 4;         // uniform: this wavefront owns a 32 x 32 part of the tile
-    const int wm = TT == 128 ? wave >> 1 : (wave >> 1) & 1, wn = wave & 1;   // token part, rank half of this wavefront's 32 x 32
+    using C = StCfg<TT, BK>;
+    constexpr int ST_STAGE = C::STAGE, ST_LPW = C::LPW, ST_NS = C::NS, ST_PD = C::PD, KS = C::KS;
+    constexpr int LOG_BK = BK == 128 ? 7 : 6;
+    const bool computes = wave < C::CW;                  // uniform: this wavefront owns a 32 x 32 part of the tile
+    const int wm = (wave >> 1) % (TT / 32), wn = wave & 1;   // token part, rank half of this wavefront's 32 x 32
     const int logical = xcd_contiguous(blockIdx.x, nblk);
     const int tile_t = logical / tiles_r, tile_r = logical % tiles_r;
     const int64_t t0 = (int64_t)tile_t * TT;
     const int rho0 = tile_r * TR;
     const int q = n_in / b;
-    auto chunk_begin = [&](int j) { return (j * q) >> 6; };
-    auto chunks_of = [&](int j) { return (((j + 1) * q + 63) >> 6) - ((j * q) >> 6); };
+    auto chunk_begin = [&](int j) { return (j * q) >> LOG_BK; };
+    auto chunks_of = [&](int j) { return (((j + 1) * q + BK - 1) >> LOG_BK) - ((j * q) >> LOG_BK); };
     const int nsteps = [&] { int n = 0; for (int j = 0; j < b; ++j) n += chunks_of(j); return n; }();
 
-    // Load h of this wavefront fills operand rows 8 (ST_LPW wave + h) .. + 7 of a stage: lane l brings
-    // the piece that belongs at row l / 8 of those, slot l % 8.
+    // Load h of this wavefront fills operand rows RPL (LPW wave + h) .. + RPL - 1 of a stage: lane l brings
+    // the piece that belongs at row l / PPR of those, slot l % PPR.
     int off[ST_LPW];
 #pragma unroll
     for (int h = 0; h < ST_LPW; ++h) {
-        const int row = 8 * (ST_LPW * wave + h) + (lane >> 3);
-        const int piece = (lane & 7) ^ ((row >> 1) & 7);
+        const int row = C::RPL * (ST_LPW * wave + h) + lane / C::PPR;
+        const int piece = (lane % C::PPR) ^ ((row >> C::SH) & (C::PPR - 1));
         if (row < TT) {
             int xr = row;
             if (t0 + xr > T - 1) xr = (int)(T - 1 - t0);    // rows past the end re-read the last row; never stored
@@ -276,56 +307,73 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
     const unsigned char* vs = (const unsigned char*)Va;
     const int64_t v_block = (int64_t)r * qp * 2;        // bytes of one Va[j]
 
-    int fj = 0, fk = 0, fetched = 0;                    // fetch cursor (uniform): block, chunk within the block
+    // fetch cursor (uniform): pointers to the chunk of X and of Va[fj] it stands on; arithmetic other than
+    // an increment only when it crosses into the next block
+    int fj = 0, fk = 0, fetched = 0, fn = chunks_of(0);
+    const unsigned char* xc = xs;
+    const unsigned char* vc = vs;
     auto issue = [&](int stage_off) {
-        const unsigned char* xc = xs + (size_t)(chunk_begin(fj) + fk) * (ST_BK * 2);
-        const unsigned char* vc = vs + fj * v_block + (size_t)fk * (ST_BK * 2);
 #pragma unroll
         for (int h = 0; h < ST_LPW; ++h) {
-            const bool isx = 8 * (ST_LPW * wave + h) < TT;                 // uniform
+            const bool isx = C::RPL * (ST_LPW * wave + h) < TT;            // uniform
             __builtin_amdgcn_global_load_lds(BLR_GPTR((isx ? xc : vc) + off[h]),
                                              BLR_LPTR(smem + stage_off + (ST_LPW * wave + h) * 1024), 16, 0, 0);
         }
         if (fetched < nsteps - 1) {                     // the cursor stops at the last step; later issues repeat it
             ++fetched;
-            if (++fk == chunks_of(fj)) { fk = 0; ++fj; }
+            if (++fk == fn) {
+                fk = 0; ++fj; fn = chunks_of(fj);
+                xc = xs + (size_t)chunk_begin(fj) * C::RB;
+                vc = vs + fj * v_block;
+            } else {
+                xc += C::RB;
+                vc += C::RB;
+            }
         }
     };
 
-    // fragment addresses inside a stage: row m of this wavefront's 32 tokens (resp. ranks), k group kg
+    // fragment addresses inside a stage: row m of this wavefront's 32 tokens (resp. ranks), k group kg; the
+    // piece of k16 step ks is (2 ks + kg) ^ swizzle(row) = (kg ^ swizzle(row)) ^ 2 ks
     const int m = lane & 31, kg = lane >> 5;
     const unsigned lds0 = (unsigned)(uintptr_t)BLR_LPTR(smem);
-    unsigned fa[ST_BK / 16], fb[ST_BK / 16];
-#pragma unroll
-    for (int ks = 0; ks < ST_BK / 16; ++ks) {
-        const unsigned sw = (unsigned)(((2 * ks + kg) ^ ((m >> 1) & 7)) * 16);
-        fa[ks] = lds0 + (wm * 32 + m) * (ST_BK * 2) + sw;
-        fb[ks] = lds0 + (TT + wn * 32 + m) * (ST_BK * 2) + sw;
-    }
+    const unsigned kgx16 = (unsigned)((kg ^ ((m >> C::SH) & (C::PPR - 1))) * 16);
+    const unsigned rowa = lds0 + (wm * 32 + m) * C::RB, rowb = lds0 + (TT + wn * 32 + m) * C::RB;
 
     int cstage = 0, istage = ST_PD * ST_STAGE;          // byte offsets of the stage to compute on / to refill
+    bf16x8 fr[2][2][2];                                 // [batch parity][k16 step in the batch][X, Vt]
+    auto read_batch = [&](auto BQ, int stage_off) {     // the fragments of k16 steps 2 bq, 2 bq + 1
+        constexpr int bq = decltype(BQ)::value;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const unsigned sw = kgx16 ^ (unsigned)((2 * bq + u) * 32);
+            fr[bq & 1][u][0] = lds_read_b128_async(rowa + stage_off + sw);
+            fr[bq & 1][u][1] = lds_read_b128_async(rowb + stage_off + sw);
+        }
+    };
     auto step = [&](f32x16& acc) {
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(ST_LPW * (ST_PD - 1)) : "memory");
-        issue(istage);                                  // the stage every wavefront finished reading one step ago
         const int rstage = cstage;                      // the stage of this step
+        const int wstage = istage;                      // the stage every wavefront finished reading one step ago
         cstage = cstage + ST_STAGE == ST_NS * ST_STAGE ? 0 : cstage + ST_STAGE;
         istage = istage + ST_STAGE == ST_NS * ST_STAGE ? 0 : istage + ST_STAGE;
-        if (!computes) return;                          // moves operands only
-        bf16x8 af[ST_BK / 16], bfr[ST_BK / 16];
+        if (!computes) { issue(wstage); return; }       // moves operands only
+        read_batch(std::integral_constant<int, 0>{}, rstage);
+        read_batch(std::integral_constant<int, 1>{}, rstage);
+        // the refill goes out here: the fragment reads are on their way, and the MFMAs that the wavefronts
+        // of this SIMD issued before the barrier have drained by now
+        issue(wstage);
+        static_for<KS / 2>([&](auto BQ) {
+            constexpr int bq = decltype(BQ)::value;
+            if constexpr (bq + 1 < KS / 2) asm volatile("s_waitcnt lgkmcnt(4)" ::: "memory");   // in order: batch bq has arrived
+            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int ks = 0; ks < ST_BK / 16; ++ks) {
-            asm volatile("ds_read_b128 %0, %1" : "=v"(af[ks]) : "v"(fa[ks] + rstage) : "memory");
-            asm volatile("ds_read_b128 %0, %1" : "=v"(bfr[ks]) : "v"(fb[ks] + rstage) : "memory");
-        }
-        static_assert(ST_BK / 16 == 4, "the waits below are written for four fragment pairs");
-        asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(af[0]), "+v"(bfr[0]) :: "memory");
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0], bfr[0], acc, 0, 0, 0);
-        asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(af[1]), "+v"(bfr[1]) :: "memory");
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1], bfr[1], acc, 0, 0, 0);
-        asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(af[2]), "+v"(bfr[2]) :: "memory");
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[2], bfr[2], acc, 0, 0, 0);
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[3]), "+v"(bfr[3]) :: "memory");
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[3], bfr[3], acc, 0, 0, 0);
+            for (int u = 0; u < 2; ++u) { fr[bq & 1][u][0] = tie_to_wait(fr[bq & 1][u][0]); fr[bq & 1][u][1] = tie_to_wait(fr[bq & 1][u][1]); }
+            __builtin_amdgcn_sched_barrier(0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[bq & 1][0][0], fr[bq & 1][0][1], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[bq & 1][1][0], fr[bq & 1][1][1], acc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (bq + 2 < KS / 2) read_batch(std::integral_constant<int, bq + 2>{}, rstage);
+        });
     };
 
     for (int s = 0; s < ST_PD; ++s) issue(s * ST_STAGE);
@@ -386,9 +434,10 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
         });
     } else {
         // 64 tokens: one pass; the four computing wavefronts hand over all 32 tokens of their parts
+        constexpr int ZSTR_T = TT * 32 + 8, GROUP_T = 8 * ZSTR_T;
         __syncthreads();                                // the stages are no longer read
         if (computes) {
-            unsigned char* zrow = Zs + (wn * 32 + m) * ZSTR + (wm * 32 + 4 * kg) * 32;
+            unsigned char* zrow = Zs + (wn * 32 + m) * ZSTR_T + (wm * 32 + 4 * kg) * 32;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 unsigned char* dst = zrow + (8 * (e / 4) + (e % 4)) * 32;
@@ -398,9 +447,10 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
             }
         }
         __syncthreads();
-        couple_group(Zs + wave * GROUP, sfrag);
+        couple_group<TT>(Zs + wave * GROUP_T, sfrag);
         __syncthreads();
-        store_a_tile<8>(Zs, A, T, t0, rho0, b, r, [](int t) { return t; });
+        auto same = [](int t) { return t; };
+        store_a_tile<8, decltype(same), TT>(Zs, A, T, t0, rho0, b, r, same);
     }
 }
 
@@ -412,31 +462,38 @@ bool blast_fused_supported(int64_t T, int n_in, int b, int r) {
     const int64_t nblk = blast_fused_tiles(T, r);
     // 64 | n_in: the chunk grid is aligned to 64 input columns and must end with the row
     return q % 8 == 0 && r % 8 == 0 && n_in % 64 == 0 && nblk < (1ll << 30) &&
-           ((int64_t)128 * n_in + 64) * 2 < (1ll << 31) && ((int64_t)r * blast_va_row(q) + 64) * 2 < (1ll << 31);
+           ((int64_t)128 * n_in + 128) * 2 < (1ll << 31) && ((int64_t)r * blast_va_row(q, blast_chunk(n_in, b)) + 128) * 2 < (1ll << 31);
 }
 
 int64_t blast_fused_tiles(int64_t T, int r) { return ((T + 127) / 128) * ((r + TR - 1) / TR); }
 
 namespace {
-template <int TT>
+template <int TT, int BK>
 hipError_t launch_stage12_inst(const void* X, const void* Va, const void* Sp, void* A,
                                int64_t T, int n_in, int b, int r, hipStream_t s) {
     static LdsLimitOnce lds_limit;
-    if (hipError_t e = lds_limit.set({(const void*)blast_stage12_kernel<TT>}, StCfg<TT>::LDS); e != hipSuccess) return e;
+    constexpr int lds = StCfg<TT, BK>::LDS;
+    if (hipError_t e = lds_limit.set({(const void*)blast_stage12_kernel<TT, BK>}, lds); e != hipSuccess) return e;
     const int tiles_t = (int)((T + TT - 1) / TT), tiles_r = (r + TR - 1) / TR;
     const int nblk = tiles_t * tiles_r;
-    hipLaunchKernelGGL(blast_stage12_kernel<TT>, dim3((unsigned)nblk), dim3(512), StCfg<TT>::LDS, s,
+    hipLaunchKernelGGL((blast_stage12_kernel<TT, BK>), dim3((unsigned)nblk), dim3(512), lds, s,
                        (const bf16_t*)X, (const bf16_t*)Va, (const bf16_t*)Sp, (bf16_t*)A, T, n_in, b, r,
-                       blast_va_row(n_in / b), tiles_r, nblk);
+                       blast_va_row(n_in / b, BK), tiles_r, nblk);
     return hipGetLastError();
 }
 }  // namespace
 
 hipError_t launch_blast_stage12(const void* X, const void* Va, const void* Sp, void* A,
                                 int64_t T, int n_in, int b, int r, hipStream_t s) {
-    // one workgroup per compute unit: 64-token tiles while they still fit in one round of the 256
-    return blast_fused_tiles(T, r) <= 128 ? launch_stage12_inst<64>(X, Va, Sp, A, T, n_in, b, r, s)
-                 : launch_stage12_inst<128>(X, Va, Sp, A, T, n_in, b, r, s);
+    // one workgroup per compute unit: 64-token tiles while they still fit in one round of the 256; steps of
+    // 128 contraction indices where the input blocks are whole numbers of such chunks.
+    // (32-token tiles for still fewer tokens were built and measured: 4096 x 4096, r = 640 at 512 tokens 37.9 ->
+    // 33.6 us for the whole call against 29.8 us on three kernels, whose finer tiles keep every compute unit
+    // busy; a lone workgroup walks 4096 contraction indices in 26 us however many stages it has in flight.)
+    const bool small = blast_fused_tiles(T, r) <= 128;
+    if (blast_chunk(n_in, b) == 128)
+        return small ? launch_stage12_inst<64, 128>(X, Va, Sp, A, T, n_in, b, r, s) : launch_stage12_inst<128, 128>(X, Va, Sp, A, T, n_in, b, r, s);
+    return small ? launch_stage12_inst<64, 64>(X, Va, Sp, A, T, n_in, b, r, s) : launch_stage12_inst<128, 64>(X, Va, Sp, A, T, n_in, b, r, s);
 }
 
 template <int TNT, bool Z8>

@@ -24,17 +24,17 @@ __global__ __launch_bounds__(256) void pack_v_kernel(const bf16_t* V, bf16_t* Vt
     }
 }
 
-// Vt re-laid for the fused stage 1 + coupling kernel when q is not a multiple of 64: row (j, rho) holds
-// the k chunks of 64 GLOBAL input columns that block j touches, chunk c of the row = columns
-// 64 (cb + c) .. + 63 with cb = floor(j q / 64); positions outside [j q, (j+1) q) are zero. The
-// kernel can then walk X in 128-byte-aligned pieces, whatever q is.
-__global__ __launch_bounds__(256) void pack_va_kernel(const bf16_t* __restrict__ V, bf16_t* __restrict__ Va, int q, int r, int qp, int64_t total) {
+// Vt re-laid for the fused stage 1 + coupling kernel when q is not a multiple of the layer's chunk (64 or
+// 128 columns): row (j, rho) holds the k chunks of GLOBAL input columns that block j touches, chunk c of
+// the row = columns chunk (cb + c) .. + chunk - 1 with cb = floor(j q / chunk); positions outside
+// [j q, (j+1) q) are zero. The kernel can then walk X in whole aligned cache lines, whatever q is.
+__global__ __launch_bounds__(256) void pack_va_kernel(const bf16_t* __restrict__ V, bf16_t* __restrict__ Va, int q, int r, int qp, int chunk, int64_t total) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
     const int x = (int)(e % qp);
     const int rho = (int)((e / qp) % r);
     const int j = (int)(e / ((int64_t)qp * r));
-    const int64_t gcol = (((int64_t)j * q) >> 6) * 64 + x;           // global input column
+    const int64_t gcol = (((int64_t)j * q) / chunk) * chunk + x;     // global input column
     const int64_t c = gcol - (int64_t)j * q;
     Va[e] = (c >= 0 && c < q) ? V[((int64_t)j * q + c) * r + rho] : (bf16_t)0;
 }
@@ -152,9 +152,9 @@ hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* 
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (Va) {
-        const int qp = blast_va_row(q);
+        const int chunk = blast_chunk(n_in, b), qp = blast_va_row(q, chunk);
         const int64_t total = (int64_t)b * r * qp;
-        hipLaunchKernelGGL(pack_va_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t*)V, (bf16_t*)Va, q, r, qp, total);
+        hipLaunchKernelGGL(pack_va_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t*)V, (bf16_t*)Va, q, r, qp, chunk, total);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (Vf) {

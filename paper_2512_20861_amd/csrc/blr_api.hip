@@ -57,7 +57,8 @@ PackLayout pack_layout(int n_in, int n_out, int b, int r) {
     } else {
         pk.off_Vt = off; off += align_up((size_t)n_in * r * 2);
         const int q = n_in / b;
-        if (q % 64) { pk.off_Va = off; off += align_up((size_t)b * r * blast_va_row(q) * 2); }
+        const int chunk = blast_chunk(n_in, b);
+        if (q % chunk) { pk.off_Va = off; off += align_up((size_t)b * r * blast_va_row(q, chunk) * 2); }
         else pk.off_Va = pk.off_Vt;
         pk.off_Sc = off; off += align_up((size_t)b * b * r * 2);
     }
@@ -83,7 +84,7 @@ constexpr size_t kChunkBytes = 48u << 20;
 // q = n_in / b, the more tiles it takes to come out ahead (measured at q = 64 ... 688, r = 256 ... 1024).
 inline int64_t fused_min_tiles(int n_in, int b) {
     const int q = n_in / b;
-    return q <= 128 ? 80 : q <= 256 ? 144 : 224;
+    return q <= 128 ? 80 : q <= 256 ? 120 : 224;
 }
 // Up to this many tokens the coupling runs as one thread per 8 outputs (the 64-token tiles of the
 // MFMA coupling kernel would leave most of the chip idle).

@@ -161,8 +161,12 @@ hipError_t launch_blast_full(const void* X, const void* Sp, const void* Vf, cons
 hipError_t launch_coupling_small(const void* Z, const void* S, void* A, int64_t T, int b, int r, hipStream_t s);   // few tokens; canonical S
 
 // BLAST weight re-layout (bf16): Sp always; Vt (row-major transpose) if non-null; Vf and Uf if non-null
-// elements per (j, rho) row of the chunk-aligned copy of Vt: the 64-column chunks a block of q columns can touch
-inline int blast_va_row(int q) { return q % 64 ? ((q + 63) / 64 + 1) * 64 : q; }
+// the fused stage 1 + coupling kernel walks the contraction index in chunks aligned to this many GLOBAL input
+// columns: 128 when the input blocks are whole numbers of such chunks (no padded boundary chunks; measured
+// 4 % faster than 64 on 4096 x 4096, b = 16), else 64 (with q = 688 the deeper chunks' extra padding costs 1.5 %)
+inline int blast_chunk(int n_in, int b) { return (n_in / b) % 128 == 0 ? 128 : 64; }
+// elements per (j, rho) row of the chunk-aligned copy of Vt: the chunks of `chunk` columns a block of q columns can touch
+inline int blast_va_row(int q, int chunk) { return q % chunk ? ((q + chunk - 1) / chunk + 1) * chunk : q; }
 hipError_t launch_blast_pack(const void* U, const void* S, const void* V, void* Sp, void* Sc, void* Vt, void* Va, void* Vf, void* Uf,
                              int n_in, int n_out, int b, int r, hipStream_t s);
 

@@ -770,7 +770,9 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
         if (est_us <= 6.5 || (wgs >= 128 && wgs <= 256 && est_us <= 9.0)) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
     }
     if (d.split_scratch && split_plan(tiles(64, 64), d.K).nsplit > 1) return launch_dma<64, 64, 2, 2>(d, s, true);
-    if (tiles(64, 64) >= kFill || (d.M <= 64 && d.N <= 64))
+    // the smallest tile already from 128 workgroups on: at 128 tokens it beats the weight-streaming kernel over
+    // 32-token tiles (dense 4096 x 4096: 17.0 against 23.6 us; 11008 -> 4096: 36 against 55 us)
+    if (tiles(64, 64) >= 128 || (d.M <= 64 && d.N <= 64))
         return one_round(64, 64) ? launch_deep<64, 64, 2, 2, 128, 4>(d, s) : launch_dma<64, 64, 2, 2>(d, s);
     // Nothing fills the chip (a product of some tens of tokens with weights that are not split, e.g.
     // the dense reference at 33 ... 96 tokens): the weight-streaming kernel over tiles of 32 tokens puts
