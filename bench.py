@@ -510,6 +510,11 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run an elementwise pass over 64 MiB in / 64 MiB out (scales the HBM byte counters)")
     ap.add_argument("--eager", action="store_true", help="report the eager Python launch loop instead of the graph replay")
+    ap.add_argument("--profile-part", default="", choices=["", "call", "first", "last", "dense", "copy"],
+                    help="for runs under rocprofv3: enqueue ONLY this part of the workload (a HIP graph of --steps launches, replayed 4 times) and exit "
+                         "(call = the whole forward; first / last = the kernels up to / after the workspace intermediate; "
+                         "dense = the same-shape dense GEMM; copy = an elementwise pass over 64 MiB in / 64 MiB out that "
+                         "calibrates the HBM byte counters), so that every kernel row of the profile has one role")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (token-parallel sharding needs no exchange and is not "
@@ -528,6 +533,24 @@ def main():
     T = args.tokens or cfg["T"][-1]
     layer = GpuLayer(cfg, T)
     layer.set_x(to_dev(bi.activations(T, cfg["n_in"], cfg["dtype"], scale=cfg["x_scale"])))
+    if args.profile_part:
+        if args.profile_part == "copy":
+            src = torch.ones(32 << 20, dtype=torch.bfloat16, device="cuda")
+            dst = torch.empty_like(src)
+            fn = lambda: torch.mul(src, 2.0, out=dst)
+        elif args.profile_part == "dense":
+            Wp = to_dev(bi.dense_weight(cfg["n_in"], cfg["n_out"], cfg["dtype"]))
+            Yp = torch.empty_like(layer.Y)
+            fn = B.prepared(B.dense_reference_forward, layer.X, Wp, Yp)
+        else:
+            layer.forward()                             # the workspace holds an intermediate for a last-stage-only call
+            fn = layer.prepared({"call": 0, "first": B.ONLY_FIRST_STAGE, "last": B.ONLY_LAST_STAGE}[args.profile_part])
+        # the same launch configuration as the timed runs: the steps captured once in a HIP graph, replayed
+        torch.cuda.synchronize()
+        ms = time_graph(lambda: fn, args.steps, 2, replays=3)
+        print(json.dumps({"profile_part": args.profile_part, "workload": args.workload, "T": T,
+                          "launches": f"{args.steps} per graph replay, 4 replays + 2 warm-up calls", "ms_per_launch": ms}), flush=True)
+        return
 
     # timed region: exactly `steps` forward calls, inputs resident, synchronised on both sides.
     # eager = a Python loop of C calls (host-launch-bound for microsecond kernels);
