@@ -569,6 +569,7 @@ def main():
             roof["traffic"] = entry["bytes"]
             roof["traffic_source"] = entry["profile"]
             roof["traffic_kernel"] = entry["kernel"]
+            roof["traffic_commit"] = entry.get("commit")
     except OSError:
         pass
 
