@@ -238,11 +238,11 @@ def dominant_roofline(layer, ms_total, stages):
             "traffic": None, "kernel": kern, "kernel_ms": ms, "algorithmic_flops": flo}
 
 
-def cold_copies(layer, min_bytes=512 << 20):
-    """Shallow copies of `layer` whose factor tensors are distinct device buffers, enough of them that
-    one round over all copies streams at least `min_bytes` of factors (far beyond every cache)."""
+def cold_copies(layer, min_bytes=512 << 20, with_io=False):
+    """Shallow copies of `layer` whose factor tensors (with_io: also X and Y) are distinct device buffers,
+    enough of them that one round over all copies streams at least `min_bytes` (far beyond every cache)."""
     import copy
-    names = [n for n in ("R", "L", "U", "S", "V", "packed") if getattr(layer, n, None) is not None]
+    names = [n for n in ("R", "L", "U", "S", "V", "packed") + (("X", "Y") if with_io else ()) if getattr(layer, n, None) is not None]
     per = sum(getattr(layer, n).numel() * getattr(layer, n).element_size() for n in names)
     out = []
     for _ in range(max(2, -(-min_bytes // per))):
@@ -303,16 +303,23 @@ def run_sweep(steps, warmup, names, variants=False, cpu_seconds=0.0, write=False
                                             layer.flags | fl, ws_alt)
                     ms_alt[key] = time_graph(mk, steps, warmup)
             cold = None
-            if T <= 128 and name != "C1":                   # weight-streaming regime: also with cold caches
-                copies = cold_copies(layer)
+            if T <= 128 or name == "C1":                    # HBM-bound rows: also with cold caches
+                # few tokens: the factors are the stream, rotate them; C1: activations are the stream, rotate X, Y and factors
+                io = name == "C1"
+                copies = cold_copies(layer, with_io=io)
                 n_cold = max(steps, len(copies))
                 ms_cold = time_cold(lambda: [c.prepared() for c in copies], n_cold, min(warmup, 3))
-                nW = max(2, -(-(512 << 20) // (W.numel() * W.element_size())))
+                per_dense = W.numel() * W.element_size() + (2 * layer.X.numel() * layer.X.element_size() if io else 0)
+                nW = max(2, -(-(512 << 20) // per_dense))
                 Ws = [W.clone() for _ in range(nW)]
-                dense_cold = time_cold(lambda: [B.prepared(B.dense_reference_forward, layer.X, w, Yd) for w in Ws], max(steps, nW), min(warmup, 3))
+                Xs = [layer.X.clone() if io else layer.X for _ in range(nW)]
+                Ys = [torch.empty_like(Yd) if io else Yd for _ in range(nW)]
+                dense_cold = time_cold(lambda: [B.prepared(B.dense_reference_forward, x, w, y) for x, w, y in zip(Xs, Ws, Ys)],
+                                       max(steps, nW), min(warmup, 3))
                 cold = {"ms": ms_cold, "dense_ms": dense_cold, "frac_of_floor": max(mem, mfma) / (ms_cold * 1e-3),
-                        "dense_frac_of_floor": max(dmem, dmfma) / (dense_cold * 1e-3), "factor_copies": len(copies)}
-                del copies, Ws
+                        "dense_frac_of_floor": max(dmem, dmfma) / (dense_cold * 1e-3), "factor_copies": len(copies),
+                        "rotated": "X, Y and factors" if io else "factors"}
+                del copies, Ws, Xs, Ys
             row = {"config": name, "op": cfg["op"], "T": T, "ms": ms, "tokens_per_s": T / (ms * 1e-3),
                    "bound": "hbm" if mem >= mfma else "mfma", "frac": max(mem, mfma) / (ms * 1e-3),
                    "floor_hbm_us": mem * 1e6, "floor_mfma_us": mfma * 1e6, "stage_ms": st,

@@ -609,11 +609,14 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 // Splitting pays when a call has too few tiles to keep the chip's memory pipes full: every
 // workgroup has a bounded number of bytes in flight, so the bandwidth a call can draw grows with
 // the number of workgroups. Parts of at least 8 steps; about 384 workgroups; at most 16 parts.
+// Only below 128 tiles: from there on one launch of the deep-step 64 x 64 kernel is faster than the parts
+// plus their sum (low-rank 4096 x 4096, r = 1024 at 128 tokens: 21.8 -> 17.7 us; 11008 -> 4096, r = 1488 at
+// 512 tokens: 66 -> 54 us); a threshold of 64 loses again (8192 -> 2048, r = 768 at 512 tokens: 30 -> 51 us).
 struct SplitPlan { int nsplit, kspan; };
 inline SplitPlan split_plan(int64_t ntiles, int K) {
     const int nk = (K + 31) / 32;
     SplitPlan sp{1, nk};
-    if (ntiles >= 256 || nk < 16) return sp;
+    if (ntiles >= 128 || nk < 16) return sp;
     int want = (int)((384 + ntiles - 1) / ntiles);
     if (want > 16) want = 16;
     if (want > nk / 8) want = nk / 8;
