@@ -12,6 +12,7 @@
 // contiguous range of tiles, walked in groups of 8 row-tiles per column-tile, so the operand
 // panels an XCD touches at one time fit its own L2.
 #include "blr_common.h"
+#include <cstdlib>
 
 namespace blr {
 namespace {
@@ -727,6 +728,16 @@ size_t gemm_split_scratch_bytes(int64_t M, int N, int K, int G) {
     return sp.nsplit > 1 ? (size_t)sp.nsplit * ntiles * 64 * 64 * sizeof(float) : 0;
 }
 
+// compute units of the current device (256 on the part this is written for; asked once)
+static int64_t compute_units() {
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        return cus;
+    }();
+    return n;
+}
+
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     if (d.c_fp8) {                                      // 8-bit C: the tile kernels only (no weight-streaming kernel, no split contraction)
         if (!gemm_fp8_store_supported(d)) return hipErrorInvalidValue;
@@ -743,7 +754,29 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // large problems: 256 x 256 tiles on 8 wavefronts (half the LDS and L2 traffic per FLOP of 128 x 128)
     // (from 160 tiles on: the same scan as for kFill below, on Monarch, BLAST and low-rank layers at
     // 300 ... 6144 tokens, had 160 ahead of 256 by 5-17 % at the token counts where they differ, and ahead of 128 and 96 on balance)
-    if (d.M > 128 && d.N > 128 && d.K > kSmallK && tiles(256, 256) >= 160) return launch_dma<256, 256, 2, 4>(d, s);
+    if (d.M > 128 && d.N > 128 && d.K > kSmallK && tiles(256, 256) >= 160) {
+        // The 256 x 256 tiles run one per compute unit, in rounds; a last round that fills only part of the chip
+        // costs a whole round. When that round would be at most 60 % full, the rows of tiles that fit the whole
+        // rounds go out here and the remaining rows as a product of their own on 128 x 128 tiles, provided those
+        // make a single round (two workgroups per compute unit; such a round takes 0.64 of a round of the large
+        // tiles). 4096 -> 11008 at 1536 / 3072 / 6144 tokens: dense 200 -> 148, 318 -> 265, 547 -> 498 us, Monarch
+        // stage 2 75 -> 58, 116 -> 106, 201 -> 193 us; remainders of two small rounds (2048, 8192 tokens) were 5 % slower.
+        const int64_t per_row = (int64_t)((d.N + 255) / 256) * d.G, rows = (d.M + 255) / 256;
+        const int64_t ncu = compute_units(), whole = rows * per_row / ncu, rest = rows * per_row % ncu;
+        const int64_t rows1 = whole * ncu / per_row;
+        const int64_t m2 = d.M - rows1 * 256;           // the remaining rows and their 128 x 128 tiles
+        const int64_t small = ((m2 + 127) / 128) * ((d.N + 127) / 128) * d.G;
+        if (whole >= 1 && rest > 0 && rest * 10 <= ncu * 6 && rows1 >= 1 && rows1 < rows && small <= 2 * ncu) {
+            GemmDesc d1 = d, d2 = d;
+            d1.M = rows1 * 256;
+            d2.M = d.M - d1.M;
+            d2.A = (const bf16_t*)d.A + d1.M * d.a_rs;
+            d2.C = (bf16_t*)d.C + d1.M * d.c_rs;
+            if (hipError_t e = launch_dma<256, 256, 2, 4>(d1, s); e != hipSuccess) return e;
+            return launch_dma<128, 128, 2, 2>(d2, s);
+        }
+        return launch_dma<256, 256, 2, 4>(d, s);
+    }
     // otherwise the largest tile that still gives every compute unit a workgroup
     // 160 of the 256 compute units: a scan of token counts 33 ... 4096 on eight weight shapes had 160
     // ahead of 200 by 10-30 % wherever the two differ (e.g. 11008 -> 4096 at 640 tokens: 144 -> 98 us,

@@ -136,8 +136,26 @@ def test_blast_whole_tensor_mid_size():
         assert err <= gu.TOL["bf16"]
 
 
+@pytest.mark.parametrize("name,T", [("C2b", 1536), ("C2b", 3000), ("C2a", 4352)])
+def test_monarch_rows_of_a_partial_last_round_sampled(name, T):
+    """Token counts at which the large tiles of a stage would end in a mostly empty round: the rows of that round
+    go out as a product of their own on smaller tiles. Rows on both sides of the cut, and the cut itself."""
+    gu = _gu()
+    cfg = bi.CONFIGS[name]
+    lay = bi.make_layer(cfg)
+    X = bi.activations(T, cfg["n_in"], "bf16")
+    cuts = [r for c in range(256, T, 256) for r in (c - 1, c)]
+    rows = np.array(sorted(set(_sample_rows(T).tolist()) | set(cuts[-12:])), dtype=np.int64)
+    for order, oflag in (("interleaved", oracle.OUT_INTERLEAVED), ("blocked", oracle.OUT_BLOCKED)):
+        Y = gu.run_monarch(X, lay, gu.B.MONARCH_OUT_BLOCKED if order == "blocked" else 0)
+        assert torch.isfinite(Y.float()).all()
+        err = gu.rel_err(gu.to_f64(Y[torch.from_numpy(rows).cuda()]), oracle.monarch_forward(X.f64[rows], lay.R.f64, lay.L.f64, oflag))
+        print(f"{name} T={T} {order}: {len(rows)} sampled rows, rel err {err:.3e}")
+        assert err <= gu.TOL["bf16"]
+
+
 @pytest.mark.parametrize("T,n_in,n_out", [(2048, 4096, 4096), (8192, 4096, 4096), (16, 4096, 11008), (128, 11008, 4096),
-                                          (512, 4096, 11008), (8192, 11008, 4096)])
+                                          (512, 4096, 11008), (8192, 11008, 4096), (1536, 4096, 11008), (4352, 4096, 4096)])
 def test_dense_llama_shape_sampled(T, n_in, n_out):
     gu = _gu()
     W = bi.dense_weight(n_in, n_out, "bf16")
@@ -145,7 +163,8 @@ def test_dense_llama_shape_sampled(T, n_in, n_out):
     Y = gu.empty_out(T, n_out, "bf16")
     gu.B.dense_reference_forward(gu.to_dev(X), gu.to_dev(W), Y)
     torch.cuda.synchronize()
-    rows = _sample_rows(T, 8)
+    rows = np.array(sorted(set(_sample_rows(T, 8).tolist()) | {max(T - 257, 0), max(T - 256, 0), max(T - 129, 0), max(T - 128, 0)}), dtype=np.int64)
+    assert torch.isfinite(Y.float()).all()
     err = gu.rel_err(gu.to_f64(Y[torch.from_numpy(rows).cuda()]), oracle.dense_forward(X.f64[rows], W.f64))
     print(f"dense {n_in}->{n_out} T={T}: rel err {err:.3e}")
     assert err <= gu.TOL["bf16"]
