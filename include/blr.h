@@ -70,6 +70,14 @@ typedef void* blr_stream;      /* a hipStream_t */
  * force one of them (mutually exclusive) so that tests and the benchmark can run both. */
 #define BLR_BLAST_FUSED_STAGE12     0x800u
 #define BLR_BLAST_THREE_KERNELS     0x1000u
+/* flag of blr_blast_forward: force the single-kernel execution for layers of FEW, WIDE blocks (the b = 3, 6, 9
+ * layers of the paper's layer-wise table): one workgroup per (32 tokens, output block, range of its outputs) runs
+ * stage 1 for every input block, accumulates the coupling in registers (Z is never rounded nor stored) and runs
+ * stage 3 on its range. bf16; needs 32 | n_in/b, n_in/b <= 256, 32 | r, r <= 256 and a 32-token tile of X within
+ * LDS, else BLR_ERR_UNSUPPORTED. By default the library takes this execution where it was measured faster than
+ * the three kernels (few hundred to a few thousand tokens). Not combinable with the other execution flags of
+ * blr_blast_forward nor with the stage flags of blr_measure.h. */
+#define BLR_BLAST_ONE_KERNEL        0x10000u
 /* flag of blr_blast_forward: quantised intermediate (the paper's "Limitation and Future Work": quantising the
  * intermediate activations). Runs execution (b) with Z = X_j V_j stored as 8-bit floats (OCP E4M3: 4 exponent
  * and 3 mantissa bits, round to nearest even from the fp32 accumulator, clamped to the largest finite value

@@ -31,6 +31,7 @@ BLAST_FUSED_STAGE12 = 0x800
 BLAST_THREE_KERNELS = 0x1000
 MONARCH_FUSED, MONARCH_TWO_KERNELS = 0x2000, 0x4000
 BLAST_Z_FP8 = 0x8000
+BLAST_ONE_KERNEL = 0x10000
 
 EXPORTS = ("blr_status_string", "blr_monarch_workspace_bytes", "blr_monarch_forward",
            "blr_blast_workspace_bytes", "blr_blast_forward", "blr_blast_packed_bytes",

@@ -68,7 +68,7 @@ PackLayout pack_layout(int n_in, int n_out, int b, int r) {
 
 // How a BLAST call is executed and where its temporaries live in the workspace.
 struct BlastPlan {
-    enum Path { GENERIC, MFMA_THREE, MFMA_STAGE12, MFMA_FULL } path;
+    enum Path { GENERIC, MFMA_THREE, MFMA_STAGE12, MFMA_FULL, MFMA_NARROW } path;
     int64_t chunk;                   // tokens per pass of the three-kernel path (its Z and A chunks stay cache-resident)
     size_t off_A, off_Z, off_pack, total;
 };
@@ -90,6 +90,25 @@ inline int64_t fused_min_tiles(int n_in, int b) {
 // MFMA coupling kernel would leave most of the chip idle).
 constexpr int64_t kSmallCouplingTokens = 128;
 
+// The single kernel for few, wide blocks: forced by its flag, else where it was measured ahead of the three kernels.
+bool blast_narrow_possible(int64_t T, int n_in, int n_out, int b, int r, unsigned flags) {
+    return !(flags & (BLR_BLAST_FUSED_STAGE12 | BLR_BLAST_THREE_KERNELS | BLR_BLAST_Z_FP8 | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE)) &&
+           blast_narrow_supported(T, n_in, n_out, b, r) && !pack_layout(n_in, n_out, b, r).full;
+}
+bool blast_takes_narrow(int64_t T, int n_in, int n_out, int b, int r, unsigned flags) {
+    if (!blast_narrow_possible(T, n_in, n_out, b, r, flags)) return false;
+    if (flags & BLR_BLAST_ONE_KERNEL) return true;
+    // Every workgroup streams all of V, so V has to be small (ViT-B / GPT2-S widths: 196 and 295 KB; with the
+    // 590 KB of the DiT layers the three kernels are 30 % ahead), and the launch a single round of workgroups:
+    // one per compute unit, or, with the smallest V, two where two fit LDS. Measured on the 768-wide layers of the
+    // paper's layer-wise table at 128 ... 8192 tokens: b = 3, r = 128: 9.5 / 11.6 / 14.3 us against 11.9 / 15.7 /
+    // 18.2 us on three kernels at 197 / 1024 / 2048 tokens, level at 3072 ... 4096; b = 6, r = 192: 15.5 against
+    // 17.5 us at 1024 tokens, level below, behind from 1536 tokens on (23.6 against 19.0 us).
+    if ((int64_t)n_in * r > 160 * 1024) return false;
+    const int64_t wgs = blast_narrow_workgroups(T, n_out, b);
+    return wgs <= 256 || (wgs <= 512 && (int64_t)n_in * r <= 100 * 1024 && blast_narrow_lds_bytes(T, n_in, n_out, b, r) <= 80 * 1024);
+}
+
 BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt, unsigned flags) {
     BlastPlan pl{};
     const int q = n_in / b;
@@ -105,6 +124,7 @@ BlastPlan blast_plan(int64_t T, int n_in, int n_out, int b, int r, blr_dtype dt,
     } else {
         if (flags & BLR_BLAST_Z_FP8) pl.path = BlastPlan::MFMA_THREE;      // (the caller has checked blast_z_fp8_ok)
         else if (blast_full_fusion_supported(T, n_in, n_out, b, r)) pl.path = BlastPlan::MFMA_FULL;
+        else if (blast_takes_narrow(T, n_in, n_out, b, r, flags)) pl.path = BlastPlan::MFMA_NARROW;
         else if (!(flags & BLR_BLAST_THREE_KERNELS) && blast_fused_supported(T, n_in, b, r) &&
                  ((flags & BLR_BLAST_FUSED_STAGE12) || blast_fused_tiles(T, r) >= fused_min_tiles(n_in, b))) pl.path = BlastPlan::MFMA_STAGE12;
         else pl.path = BlastPlan::MFMA_THREE;
@@ -326,6 +346,10 @@ static blr_status blast_run(const void* X, const void* U, const void* S, const v
     const void* Vt = pack + pk.off_Vt;
     if (pl.path == BlastPlan::MFMA_FULL)
         return from_hip(launch_blast_full(X, Sp, pack + pk.off_Vf, pack + pk.off_Uf, Y, T, n_in, n_out, b, r, s));
+    if (pl.path == BlastPlan::MFMA_NARROW) {
+        if (members != 1) return BLR_ERR_UNSUPPORTED;
+        return from_hip(launch_blast_narrow(X, Vt, pack + pk.off_Sc, U, Y, T, n_in, n_out, b, r, s));
+    }
     if (pl.path == BlastPlan::MFMA_STAGE12) {
         if (first) {
             blr_status st = from_hip(launch_blast_stage12(X, pack + pk.off_Va, Sp, Aws, T, n_in, b, r, s));
@@ -548,13 +572,15 @@ blr_status blr_blast_forward(const void* X, const void* U, const void* S, const 
                              void* workspace, size_t workspace_bytes, blr_stream stream) {
     if (!U || !V || (!S && !(flags & BLR_BLAST_PACKED))) return BLR_ERR_INVALID_ARG;
     if (!blast_shape_ok(T, n_in, n_out, b, r) || !dtype_ok(dt)) return BLR_ERR_INVALID_ARG;
-    if (flags & ~(BLR_BLAST_PACKED | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_BLAST_FUSED_STAGE12 | BLR_BLAST_THREE_KERNELS | BLR_BLAST_Z_FP8)) return BLR_ERR_INVALID_ARG;
+    if (flags & ~(BLR_BLAST_PACKED | BLR_BLAST_ONE_KERNEL | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE | BLR_BLAST_FUSED_STAGE12 | BLR_BLAST_THREE_KERNELS | BLR_BLAST_Z_FP8)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_BLAST_Z_FP8) && (flags & (BLR_BLAST_FUSED_STAGE12 | BLR_FORCE_GENERIC))) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_ONLY_FIRST_STAGE) && (flags & BLR_ONLY_LAST_STAGE)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_BLAST_FUSED_STAGE12) && (flags & BLR_BLAST_THREE_KERNELS)) return BLR_ERR_INVALID_ARG;
+    if ((flags & BLR_BLAST_ONE_KERNEL) && (flags & (BLR_BLAST_FUSED_STAGE12 | BLR_BLAST_THREE_KERNELS | BLR_BLAST_Z_FP8 | BLR_FORCE_GENERIC | BLR_ONLY_FIRST_STAGE | BLR_ONLY_LAST_STAGE))) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_BLAST_PACKED) && (dt != BLR_BF16 || b > 16 || (flags & BLR_FORCE_GENERIC))) return BLR_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(U) || !aligned16(S) || !aligned16(V) || !aligned16(Y) || !aligned16(workspace)) return BLR_ERR_INVALID_ARG;
     if ((flags & BLR_BLAST_Z_FP8) && !blast_z_fp8_ok(n_in, n_out, b, r, dt, flags)) return BLR_ERR_UNSUPPORTED;
+    if ((flags & BLR_BLAST_ONE_KERNEL) && (dt != BLR_BF16 || !blast_mfma_shape_ok(n_in, b, r) || !blast_narrow_possible(T > 0 ? T : 1, n_in, n_out, b, r, flags))) return BLR_ERR_UNSUPPORTED;
     if (T == 0) return BLR_OK;                      // X and Y of an empty batch may be null
     if (!X || !Y) return BLR_ERR_INVALID_ARG;
     return blast_run(X, U, S, V, Y, T, n_in, n_out, b, r, 1, dt, flags, workspace, workspace_bytes, (hipStream_t)stream);

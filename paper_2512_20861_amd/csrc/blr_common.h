@@ -157,6 +157,15 @@ size_t blast_uf_bytes(int n_out, int b, int r);
 hipError_t launch_blast_full(const void* X, const void* Sp, const void* Vf, const void* Uf, void* Y,
                              int64_t T, int n_in, int n_out, int b, int r, hipStream_t s);
 
+// BLAST: whole layer in one kernel for few, wide blocks (q = n_in/b <= 256, r <= 256, 32 | q, 32 | r): a workgroup owns
+// 32 tokens, one output block and a range of its outputs; the coupling is accumulated in registers.
+// Vt[b][r][q] (contraction index contiguous), canonical S[b][b][r], U[b][p][r].
+bool blast_narrow_supported(int64_t T, int n_in, int n_out, int b, int r);
+int64_t blast_narrow_workgroups(int64_t T, int n_out, int b);
+int blast_narrow_lds_bytes(int64_t T, int n_in, int n_out, int b, int r);   // of a supported call
+hipError_t launch_blast_narrow(const void* X, const void* Vt, const void* S, const void* U, void* Y,
+                               int64_t T, int n_in, int n_out, int b, int r, hipStream_t s);
+
 // stand-alone coupling reading the packed tiles Sp[r][16][16] (bf16)
 hipError_t launch_coupling_small(const void* Z, const void* S, void* A, int64_t T, int b, int r, hipStream_t s);   // few tokens; canonical S
 

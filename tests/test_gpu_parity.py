@@ -484,6 +484,54 @@ def test_blast_quantised_intermediate(shape):
     assert gu.rel_err(Y3, Yx) <= gu.TOL["bf16"]
 
 
+@pytest.mark.parametrize("shape", [
+    (197, 768, 2304, 3, 128),      # ViT-B attn_qkv of the paper's layer-wise table: 8 output ranges per block
+    (1024, 768, 3072, 6, 192),     # GPT2-S c_fc: one range per block, wavefronts with 2, 2, ..., 0 rank tiles
+    (256, 1152, 4608, 9, 256),     # DiT fc1: 9 blocks, q = 128
+    (45, 96, 120, 3, 32),          # one token tile with a ragged tail, a range that is not a multiple of 8 outputs (p = 40)
+    (1, 64, 80, 2, 32),            # a single token; p = 40: three 16-wide output tiles per block, the last one ragged
+    (333, 512, 1000, 2, 256),      # q = 256 and r = 256: the longest contraction indices it takes; p = 500
+    (2100, 768, 768, 4, 64),       # more workgroups than compute units: 4 wavefronts per workgroup
+])
+def test_blast_single_kernel_for_few_wide_blocks(shape):
+    """The whole-layer kernel for few, wide blocks (coupling accumulated in registers), forced by its flag, with
+    packed and with canonical factors, against the oracle; and the library's own choice for the same call."""
+    gu = _gu()
+    B = gu.B
+    T, n_in, n_out, b, r = shape
+    lay = bi.blast_layer(n_in, n_out, b, r, "bf16", seed=31)
+    X = bi.activations(T, n_in, "bf16", seed=32)
+    Yref = oracle.blast_forward(X.f64, lay.U.f64, lay.S.f64, lay.V.f64)
+    Yp = gu.to_f64(gu.run_blast(X, lay, B.BLAST_ONE_KERNEL, packed=True))
+    Yc = gu.to_f64(gu.run_blast(X, lay, B.BLAST_ONE_KERNEL, packed=False))
+    Yd = gu.to_f64(gu.run_blast(X, lay, 0, packed=True))
+    errs = [gu.rel_err(Y, Yref) for Y in (Yp, Yc, Yd)]
+    print(f"BLAST {n_in}->{n_out} b={b} r={r} T={T}: one kernel rel err {errs[0]:.3e} (packed) {errs[1]:.3e} (canonical), default {errs[2]:.3e}")
+    assert max(errs) <= gu.TOL["bf16"]
+    assert np.array_equal(Yp, Yc)
+
+
+def test_blast_single_kernel_status_codes():
+    gu = _gu()
+    B = gu.B
+    L = B.lib()
+    x = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    p = x.data_ptr()
+    one = B.BLAST_PACKED | B.BLAST_ONE_KERNEL
+    # input blocks longer than 256, a rank beyond 256 or not a multiple of 32, fp32: no such kernel
+    assert L.blr_blast_forward(p, p, None, p, p, 100, 3072, 768, 3, 128, B.BF16, one, p, 1 << 30, None) == B.ERR_UNSUPPORTED
+    assert L.blr_blast_forward(p, p, None, p, p, 100, 1152, 3456, 9, 384, B.BF16, one, p, 1 << 30, None) == B.ERR_UNSUPPORTED
+    assert L.blr_blast_forward(p, p, None, p, p, 100, 768, 2304, 3, 112, B.BF16, one, p, 1 << 30, None) == B.ERR_UNSUPPORTED
+    assert L.blr_blast_forward(p, p, p, p, p, 100, 768, 2304, 3, 128, B.F32, B.BLAST_ONE_KERNEL, p, 1 << 30, None) == B.ERR_UNSUPPORTED
+    # layers the kernel for many narrow blocks serves keep that kernel's packed layout
+    assert L.blr_blast_forward(p, p, None, p, p, 100, 768, 768, 16, 96, B.BF16, one, p, 1 << 30, None) == B.ERR_UNSUPPORTED
+    # one execution at a time, and no stages to select in a single kernel
+    for other in (B.BLAST_FUSED_STAGE12, B.BLAST_THREE_KERNELS, B.BLAST_Z_FP8, B.ONLY_FIRST_STAGE, B.ONLY_LAST_STAGE):
+        assert L.blr_blast_forward(p, p, None, p, p, 100, 768, 2304, 3, 128, B.BF16, one | other, p, 1 << 30, None) == B.ERR_INVALID_ARG
+    # with packed factors the forced single kernel needs no workspace at all
+    assert L.blr_blast_workspace_bytes(197, 768, 2304, 3, 128, B.BF16, one) == 0
+
+
 def test_blast_quantised_intermediate_status_codes():
     gu = _gu()
     B = gu.B
