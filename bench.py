@@ -552,11 +552,17 @@ def main():
         else:
             layer.forward()                             # the workspace holds an intermediate for a last-stage-only call
             fn = layer.prepared({"call": 0, "first": B.ONLY_FIRST_STAGE, "last": B.ONLY_LAST_STAGE}[args.profile_part])
-        # the same launch configuration as the timed runs: the steps captured once in a HIP graph, replayed
+        # the same launch configuration as the timed runs: the steps captured once in a HIP graph, replayed;
+        # with --eager a loop of separate launches instead (the profiler records every one of those, of a graph
+        # only one pass), four rounds of `steps` so that the clocks have settled
         torch.cuda.synchronize()
-        ms = time_graph(lambda: fn, args.steps, 2, replays=3)
+        if args.eager:
+            ms = [time_calls(fn, args.steps, 2) for _ in range(4)][-1]
+        else:
+            ms = time_graph(lambda: fn, args.steps, 2, replays=3)
         print(json.dumps({"profile_part": args.profile_part, "workload": args.workload, "T": T,
-                          "launches": f"{args.steps} per graph replay, 4 replays + 2 warm-up calls", "ms_per_launch": ms}), flush=True)
+                          "launches": f"{args.steps} per round, 4 rounds + warm-up calls, " + ("separate launches" if args.eager else "one HIP graph per round"),
+                          "ms_per_launch": ms}), flush=True)
         return
 
     # timed region: exactly `steps` forward calls, inputs resident, synchronised on both sides.
