@@ -115,6 +115,23 @@ def test_monarch_argument_checks():
     assert _monarch(wsb=16) == B.ERR_WORKSPACE
 
 
+def test_blast_single_kernel_flag_checks():
+    """The forced single kernel for few, wide blocks: decided on the host before anything is enqueued."""
+    one = B.BLAST_ONE_KERNEL
+    ok = dict(n_in=768, n_out=2304, b=3, r=128)
+    for other in (B.BLAST_FUSED_STAGE12, B.BLAST_THREE_KERNELS, B.BLAST_Z_FP8, B.FORCE_GENERIC, B.ONLY_FIRST_STAGE, B.ONLY_LAST_STAGE):
+        assert _blast(flags=one | other, **ok) == B.ERR_INVALID_ARG
+    assert _blast(flags=one, n_in=3072, n_out=768, b=3, r=128) == B.ERR_UNSUPPORTED      # input blocks longer than 256
+    assert _blast(flags=one, n_in=768, n_out=2304, b=3, r=112) == B.ERR_UNSUPPORTED      # 32 does not divide r
+    assert _blast(flags=one, n_in=1152, n_out=3456, b=9, r=384) == B.ERR_UNSUPPORTED     # r beyond 256
+    assert _blast(flags=one, dt=B.F32, **ok) == B.ERR_UNSUPPORTED
+    assert _blast(flags=one, n_in=768, n_out=768, b=16, r=96) == B.ERR_UNSUPPORTED       # served by the kernel for many narrow blocks
+    assert _blast(flags=one, T=0, **ok) == B.OK                                          # empty batch: nothing launched
+    # with packed factors it needs no workspace; with canonical ones only room for the packed copies
+    assert B.blast_workspace_bytes(197, 768, 2304, 3, 128, B.BF16, B.BLAST_PACKED | one) == 0
+    assert B.blast_workspace_bytes(197, 768, 2304, 3, 128, B.BF16, one) == B.blast_packed_bytes(768, 2304, 3, 128, B.BF16)
+
+
 def test_monarch_rect_argument_checks():
     L = B.lib()
     def call(T=4, n_in=60, n_out=64, b1=3, b2=4, rp=2, dt=B.BF16, flags=0, X=FAKE, R=FAKE, Lf=FAKE, Y=FAKE, ws=FAKE, wsb=1 << 20):
