@@ -288,6 +288,8 @@ def run_sweep(steps, warmup, names, variants=False, cpu_seconds=0.0, write=False
             st = stage_times(layer, steps, warmup)
             Yd = torch.empty_like(layer.Y)
             ms_dense = time_graph(lambda: B.prepared(B.dense_reference_forward, layer.X, W, Yd), steps, warmup)
+            # context only: the vendor library's GEMM on the same operands (never a denominator of a reported speed-up)
+            ms_vendor = time_graph(lambda: (lambda: torch.matmul(layer.X, W.t(), out=Yd)), steps, warmup) if variants else None
             sa = layer.shape_args()
             mem, mfma = rf.floors(cfg["op"], T, **sa)
             dmem, dmfma = rf.floors("dense", T, cfg["n_in"], cfg["n_out"])
@@ -325,6 +327,8 @@ def run_sweep(steps, warmup, names, variants=False, cpu_seconds=0.0, write=False
                    "floor_hbm_us": mem * 1e6, "floor_mfma_us": mfma * 1e6, "stage_ms": st,
                    "dense_ms": ms_dense, "dense_frac": max(dmem, dmfma) / (ms_dense * 1e-3),
                    "speedup_vs_dense": ms_dense / ms, "ms_variants": ms_alt, "cold": cold}
+            if ms_vendor is not None:
+                row["vendor_dense_ms"] = ms_vendor
             if cpu_seconds > 0:
                 cb = cpu_baseline(cfg, min(T, 64), cpu_seconds, host)
                 row["cpu_baseline"] = {"tokens_per_s": cb["value"], "cores": cb["cores"], "T_cpu": min(T, 64)}
