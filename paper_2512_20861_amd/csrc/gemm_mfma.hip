@@ -780,7 +780,10 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // Between the two, where the 256 x 256 tiles are too few: 256 x 128 on 8 wavefronts of 64 x 64, one workgroup per
     // compute unit; a quarter less operand traffic per FLOP than the 128 x 128 tile (4096 x 4096 at 2048 tokens:
     // 98.6 -> 85 us; 11008 -> 4096: 232 -> 197 us; Monarch 4096 x 4096 stages: 60 -> 53.5 us per call)
-    if (d.M > 128 && d.N > 64 && d.K > kSmallK && tiles(256, 128) >= 160) return launch_dma<256, 128, 4, 2>(d, s);
+    // (with steps of 64 contraction indices, whole cache lines per operand row, and three stages where the shape allows:
+    // another 2-7 %; the same change on the 256 x 256 tile leaves room for two stages only and loses up to 10 %)
+    if (d.M > 128 && d.N > 64 && d.K > kSmallK && tiles(256, 128) >= 160)
+        return d.K % 64 == 0 && deep_ok(d, 64) ? launch_deep<256, 128, 4, 2, 64, 3>(d, s) : launch_dma<256, 128, 4, 2>(d, s);
     // otherwise the largest tile that still gives every compute unit a workgroup
     // 160 of the 256 compute units: a scan of token counts 33 ... 4096 on eight weight shapes had 160
     // ahead of 200 by 10-30 % wherever the two differ (e.g. 11008 -> 4096 at 640 tokens: 144 -> 98 us,
