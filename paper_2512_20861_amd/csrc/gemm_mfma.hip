@@ -418,6 +418,42 @@ struct DeepCfg {
     static_assert((MI * 32 - 32) * RB < 65536 && (NI * 32 - 32) * RB < 65536, "fragment offsets are ds_read immediates");
 };
 
+// Direct load h of this wavefront fills stage rows RPL (LPW wave + h) .. + RPL - 1 (A rows first, then
+// B rows): lane l brings the piece that belongs in slot l % PPR of row l / PPR of those. Offsets are
+// bytes from Abase / Bbase; the launcher checks that they fit 32 bits, so the arithmetic is 32-bit.
+template <class C, int BM, bool TAIL>
+__device__ __forceinline__ void deep_load_offsets(const GemmDesc& d, int wave, int lane, int64_t m0, int n0, int nk,
+                                                  unsigned (&off)[C::LPW], bool (&bad)[C::LPW]) {
+    const int lrow = lane / C::PPR, slot = lane % C::PPR;
+    const int rows_m = d.M - m0 < BM ? (int)(d.M - m0) : BM;      // rows of this tile that exist
+    // B rows: n = n0 + row - BM walks upwards by RPL per load; its image under the row gather is kept as
+    // (remainder, quotient) and advanced without divisions
+    int bn = n0 + C::RPL * (C::LPW * wave) + lrow - BM;            // (negative while this wavefront is still on A rows)
+    int brem = 0, bquo = 0;
+    bool bstarted = false;
+#pragma unroll
+    for (int h = 0; h < C::LPW; ++h) {
+        const int row = C::RPL * (C::LPW * wave + h) + lrow;
+        const int piece = slot ^ ((row >> C::SH) & (C::PPR - 1));
+        if (C::RPL * (C::LPW * wave + h) < BM) {                   // uniform
+            const int mr = row < rows_m ? row : rows_m - 1;        // rows past the end re-read the last row; never stored
+            off[h] = ((unsigned)mr * (unsigned)d.a_rs + (unsigned)piece * 8u) * 2u;
+        } else {
+            int n = bn + C::RPL * h;
+            if (n > d.N - 1) n = d.N - 1;
+            unsigned nr = (unsigned)n;
+            if (d.b_div) {
+                if (!bstarted || n == d.N - 1) { brem = n % d.b_div; bquo = n / d.b_div; bstarted = true; }
+                nr = (unsigned)brem * (unsigned)d.b_mul + (unsigned)bquo;
+                brem += C::RPL;
+                while (brem >= d.b_div) { brem -= d.b_div; ++bquo; }
+            }
+            off[h] = (nr * (unsigned)d.b_rs + (unsigned)piece * 8u) * 2u;
+        }
+        bad[h] = TAIL && (nk - 1) * C::BK + piece * 8 >= d.K;       // in the last step this piece lies past K
+    }
+}
+
 template <int BM, int BN, int WGM, int WGN, int BKT, int NS, bool TAIL>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_deep_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int order) {
     using C = DeepCfg<BM, BN, WGM, WGN, BKT, NS>;
@@ -433,41 +469,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_deep_kernel(GemmDesc d, i
     const unsigned char* Bbase = (const unsigned char*)((const bf16_t*)d.B + (int64_t)g * d.b_gs);
     const int nk = (d.K + C::BK - 1) / C::BK;
 
-    // Direct load h of this wavefront fills stage rows RPL (LPW wave + h) .. + RPL - 1 (A rows first, then
-    // B rows): lane l brings the piece that belongs in slot l % PPR of row l / PPR of those. Offsets are
-    // bytes from Abase / Bbase; the launcher checks that they fit 32 bits, so the arithmetic is 32-bit.
     unsigned off[C::LPW];
     bool bad[C::LPW];
-    {
-        const int lrow = lane / C::PPR, slot = lane % C::PPR;
-        const int rows_m = d.M - m0 < BM ? (int)(d.M - m0) : BM;      // rows of this tile that exist
-        // B rows: n = n0 + row - BM walks upwards by RPL per load; its image under the row gather is kept as
-        // (remainder, quotient) and advanced without divisions
-        int bn = n0 + C::RPL * (C::LPW * wave) + lrow - BM;            // (negative while this wavefront is still on A rows)
-        int brem = 0, bquo = 0;
-        bool bstarted = false;
-#pragma unroll
-        for (int h = 0; h < C::LPW; ++h) {
-            const int row = C::RPL * (C::LPW * wave + h) + lrow;
-            const int piece = slot ^ ((row >> C::SH) & (C::PPR - 1));
-            if (C::RPL * (C::LPW * wave + h) < BM) {                   // uniform
-                const int mr = row < rows_m ? row : rows_m - 1;        // rows past the end re-read the last row; never stored
-                off[h] = ((unsigned)mr * (unsigned)d.a_rs + (unsigned)piece * 8u) * 2u;
-            } else {
-                int n = bn + C::RPL * h;
-                if (n > d.N - 1) n = d.N - 1;
-                unsigned nr = (unsigned)n;
-                if (d.b_div) {
-                    if (!bstarted || n == d.N - 1) { brem = n % d.b_div; bquo = n / d.b_div; bstarted = true; }
-                    nr = (unsigned)brem * (unsigned)d.b_mul + (unsigned)bquo;
-                    brem += C::RPL;
-                    while (brem >= d.b_div) { brem -= d.b_div; ++bquo; }
-                }
-                off[h] = (nr * (unsigned)d.b_rs + (unsigned)piece * 8u) * 2u;
-            }
-            bad[h] = TAIL && (nk - 1) * C::BK + piece * 8 >= d.K;       // in the last step this piece lies past K
-        }
-    }
+    deep_load_offsets<C, BM, TAIL>(d, wave, lane, m0, n0, nk, off, bad);
     int kf = 0;                                         // fetch cursor (uniform); stops at the last step
     int a_pos = 0;                                      // position inside the current segment of a segmented contraction index
     int64_t a_koff = 0;
@@ -560,6 +564,143 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_deep_kernel(GemmDesc d, i
         cstage = cstage + C::STAGE == C::NS * C::STAGE ? 0 : cstage + C::STAGE;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the repeated loads of the last steps have landed too
+    __syncthreads();
+    if (d.c_fp8) store_c_tile_fp8<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn);
+    else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The 256 x 256 tile in steps of 64 contraction indices. The L2 serves one request per channel and clock whether
+// it asks for 64 or for 128 bytes of a line (measured: 260 G requests/s over the chip either way), so the 32-deep
+// steps of gemm_dma_kernel, whose operand rows are half lines, cap the operand stream at 16.7 TB/s, which is what
+// the large tile needs at the matrix pipes' full rate. Whole lines need 64 KB per stage and LDS holds two:
+// the refill of the stage that was computed on in step s - 1 goes out at the START of step s, one load behind each
+// of the first MFMAs, and has the rest of the step to land; the wait for it and the step's one barrier sit in the
+// MIDDLE of the last MFMA burst, followed by the first fragment reads of the next stage, so that neither the
+// barrier nor the LDS latency after it meets an empty matrix pipe. The two wavefronts of a SIMD drift apart
+// (one runs MFMAs while the other issues memory instructions), and a wavefront's VALU instructions barely issue
+// while its sibling keeps the matrix pipe full (measured: an address add per load made the load phase three times
+// longer): the loop body therefore has NO vector ALU work besides the MFMAs - loads address as scalar base +
+// a fixed 32-bit lane offset, fragment reads use addresses computed once per stage and k16 step.
+template <bool TAIL>
+__global__ __launch_bounds__(512) void gemm_wide_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int order) {
+    constexpr int BM = 256, BN = 256, WGN = 4;
+    using C = DeepCfg<BM, BN, 2, WGN, 64, 2>;
+    static_assert(C::LPW <= C::MI * C::NI && BM % (C::RPL * C::LPW) == 0, "one load behind each MFMA of the first burst; a wavefront loads A rows or B rows");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    int g, tile_m, tile_n;
+    workgroup_tile(d, tiles_m, tiles_n, order, g, tile_m, tile_n);
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int n0 = tile_n * BN;
+    const unsigned char* Abase = (const unsigned char*)((const bf16_t*)d.A + (int64_t)g * d.a_gs + m0 * d.a_rs);
+    const unsigned char* Bbase = (const unsigned char*)((const bf16_t*)d.B + (int64_t)g * d.b_gs);
+    const int nk = (d.K + C::BK - 1) / C::BK;
+    unsigned off[C::LPW];
+    bool bad[C::LPW];
+    deep_load_offsets<C, BM, TAIL>(d, wave, lane, m0, n0, nk, off, bad);
+    const bool on_a = C::RPL * C::LPW * wave < BM;      // this wavefront's loads bring A rows (uniform)
+
+    int kf = 0;                                         // step under the fetch cursor (uniform)
+    int a_pos = 0;                                      // position inside the current segment of a segmented contraction index
+    int64_t a_koff = 0;
+    const unsigned char* src = on_a ? Abase : Bbase;    // this wavefront's operand at the cursor
+    auto issue = [&](int stage_off, auto H) {
+        constexpr int h = decltype(H)::value;
+        asm volatile("" : "+v"(off[h]));                // the 32-bit offset stays a register operand: scalar base + lane offset addressing, no address arithmetic
+        const unsigned char* p = src + off[h];
+        if (TAIL) p = (kf == nk - 1 && bad[h]) ? zero_piece : p;
+        __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 0);
+    };
+    auto advance = [&] {                                // (stops at the last step, which the last steps fetch again: never needed, always in bounds)
+        if (kf == nk - 1) return;
+        ++kf;
+        a_koff += C::RB;
+        if (d.a_seg) {
+            a_pos += C::BK;
+            if (a_pos == d.a_seg) { a_pos = 0; a_koff += (d.a_seg_stride - d.a_seg) * 2; }
+        }
+        src = on_a ? Abase + a_koff : Bbase + (size_t)kf * C::RB;
+    };
+
+    // fragment addresses, one per stage and k16 step (row m of a 32-row MFMA operand, k group kg), opaque to the
+    // compiler so that it keeps them instead of recomputing them in the loop
+    const int m = lane & 31, kg = lane >> 5;
+    const unsigned lds0 = (unsigned)(uintptr_t)BLR_LPTR(smem);
+    const unsigned swz = (unsigned)((m >> C::SH) & (C::PPR - 1));
+    unsigned fa[2][C::KS], fb[2][C::KS];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            const unsigned sw = (((unsigned)(2 * ks + kg)) ^ swz) * 16u + st * C::STAGE;
+            fa[st][ks] = lds0 + (wm * C::WTM + m) * C::RB + sw;
+            fb[st][ks] = lds0 + (BM + wn * C::WTN + m) * C::RB + sw;
+            asm volatile("" : "+v"(fa[st][ks]), "+v"(fb[st][ks]));
+        }
+
+    f32x16 acc[C::MI][C::NI];
+#pragma unroll
+    for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+        for (int j = 0; j < C::NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    bf16x8 af[2][C::MI], bfr[2][C::NI];                 // fragments of two k16 steps in rotation
+    auto read_frags = [&](auto ST, auto KSC) {
+        constexpr int st = decltype(ST)::value, ks = decltype(KSC)::value;
+        static_for<C::MI>([&](auto I) { af[ks & 1][decltype(I)::value] = lds_read_b128<decltype(I)::value * 32 * C::RB>(fa[st][ks]); });
+        static_for<C::NI>([&](auto J) { bfr[ks & 1][decltype(J)::value] = lds_read_b128<decltype(J)::value * 32 * C::RB>(fb[st][ks]); });
+    };
+    // one step on stage ST
+    auto step = [&](auto ST) {
+        constexpr int st = decltype(ST)::value;
+        static_for<C::KS>([&](auto KSC) {
+            constexpr int ks = decltype(KSC)::value, b = ks & 1;
+            if constexpr (ks + 1 < C::KS) {
+                read_frags(ST, std::integral_constant<int, ks + 1>{});
+                asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(C::MI + C::NI) : "memory");   // in order: k16 step ks has arrived
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < C::MI; ++i) asm volatile("" : "+v"(af[b][i]));         // tie the fragments to the preceding wait
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j) asm volatile("" : "+v"(bfr[b][j]));
+            static_for<C::MI * C::NI>([&](auto Q) {
+                constexpr int q = decltype(Q)::value, i = q / C::NI, j = q % C::NI;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b][j], af[b][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (ks == 0 && q < C::LPW) {
+                    issue((1 - st) * C::STAGE, std::integral_constant<int, q>{});
+                    if constexpr (q == C::LPW - 1) advance();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if constexpr (ks == C::KS - 1 && q == C::MI * C::NI / 2 - 1) {
+                    // every wavefront is past its last read of this stage; the other stage has landed (own loads: vmcnt; the others': barrier)
+                    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+                    read_frags(std::integral_constant<int, 1 - st>{}, std::integral_constant<int, 0>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            });
+        });
+    };
+
+    static_for<C::LPW>([&](auto H) { issue(0, H); });
+    advance();
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+#pragma unroll 1
+    for (int kt = 0; kt + 1 < nk; kt += 2) {            // (stages alternate: two steps per trip keep them compile-time constants)
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+    }
+    if (nk & 1) step(std::integral_constant<int, 0>{});
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the fragments read ahead behind the last step are not used
     __syncthreads();
     if (d.c_fp8) store_c_tile_fp8<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn);
     else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
@@ -704,6 +845,23 @@ hipError_t launch_deep(const GemmDesc& d, hipStream_t s) {
     return hipGetLastError();
 }
 
+hipError_t launch_wide(const GemmDesc& d, hipStream_t s) {
+    using C = DeepCfg<256, 256, 2, 4, 64, 2>;
+    static LdsLimitOnce lds_limit;
+    if (hipError_t e = lds_limit.set({(const void*)gemm_wide_kernel<false>, (const void*)gemm_wide_kernel<true>}, C::LDS_BYTES); e != hipSuccess) return e;
+    const int tiles_m = (int)((d.M + 255) / 256);
+    const int tiles_n = (d.N + 255) / 256;
+    const bool vec = c_map_vectorizes(d);
+    const bool gfast = !vec && d.G > 1;
+    dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * d.G), 1u, 1u);
+    const int order = tile_order(d, gfast);
+    if (d.K % 64)
+        hipLaunchKernelGGL((gemm_wide_kernel<true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
+    else
+        hipLaunchKernelGGL((gemm_wide_kernel<false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
+    return hipGetLastError();
+}
+
 // deep steps need the segments of a segmented contraction index to be whole steps
 inline bool deep_ok(const GemmDesc& d, int bk) { return d.a_seg == 0 || d.a_seg % bk == 0; }
 
@@ -739,10 +897,12 @@ static int64_t compute_units() {
 }
 
 hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
+    // the 256 x 256 tile: in whole-line steps of 64 unless a segmented contraction index has segments that are not whole steps
+    auto big = [&](const GemmDesc& dd) { return deep_ok(dd, 64) ? launch_wide(dd, s) : launch_dma<256, 256, 2, 4>(dd, s); };
     if (d.c_fp8) {                                      // 8-bit C: the tile kernels only (no weight-streaming kernel, no split contraction)
         if (!gemm_fp8_store_supported(d)) return hipErrorInvalidValue;
         auto tiles8 = [&](int bm, int bn) { return (int64_t)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.G; };
-        if (d.M > 128 && d.N > 128 && d.K > 128 && tiles8(256, 256) >= 160) return launch_dma<256, 256, 2, 4>(d, s);
+        if (d.M > 128 && d.N > 128 && d.K > 128 && tiles8(256, 256) >= 160) return big(d);
         if (d.M > 64 && d.N > 64 && tiles8(128, 128) >= 160) return launch_dma<128, 128, 2, 2>(d, s);
         if (d.M > 64 && tiles8(128, 64) >= 160) return launch_dma<128, 64, 2, 2>(d, s);
         return launch_dma<64, 64, 2, 2>(d, s);
@@ -772,10 +932,10 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
             d2.M = d.M - d1.M;
             d2.A = (const bf16_t*)d.A + d1.M * d.a_rs;
             d2.C = (bf16_t*)d.C + d1.M * d.c_rs;
-            if (hipError_t e = launch_dma<256, 256, 2, 4>(d1, s); e != hipSuccess) return e;
+            if (hipError_t e = big(d1); e != hipSuccess) return e;
             return launch_dma<128, 128, 2, 2>(d2, s);
         }
-        return launch_dma<256, 256, 2, 4>(d, s);
+        return big(d);
     }
     // Between the two, where the 256 x 256 tiles are too few: 256 x 128 on 8 wavefronts of 64 x 64, one workgroup per
     // compute unit; a quarter less operand traffic per FLOP than the 128 x 128 tile (4096 x 4096 at 2048 tokens:

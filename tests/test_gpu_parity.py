@@ -216,6 +216,23 @@ def test_dense_parity(T, n_in, n_out, dtype, generic):
     assert err <= gu.TOL[dtype]
 
 
+# enough 256 x 256 tiles for the large-tile kernel, whose steps are 64 contraction indices deep: an even and an odd
+# number of steps, a last step with 8 valid indices, ragged token and output counts (a last row of tiles with one row)
+@pytest.mark.parametrize("T,n_in,n_out", [(2561, 328, 4100), (2600, 456, 4096), (2560, 448, 4096), (2817, 192, 3848)])
+def test_dense_large_tile_short_and_partial_steps(T, n_in, n_out):
+    gu = _gu()
+    W = bi.dense_weight(n_in, n_out, "bf16")
+    X = bi.activations(T, n_in, "bf16")
+    Y = gu.empty_out(T, n_out, "bf16")
+    gu.B.dense_reference_forward(gu.to_dev(X), gu.to_dev(W), Y, 0)
+    torch.cuda.synchronize()
+    out = gu.to_f64(Y)
+    assert np.isfinite(out).all()
+    err = gu.rel_err(out, oracle.dense_forward(X.f64, W.f64))
+    print(f"dense {T}x{n_in}->{n_out} large tile: rel err {err:.3e}")
+    assert err <= gu.TOL["bf16"]
+
+
 # ---------------------------------------------------------------- Monarch, different block counts on the two sides
 # (T, n_in, n_out, b_in, b_out, r_block, dtype): MFMA-aligned and ragged shapes, few and many tokens
 MONARCH_RECT_CASES = [
