@@ -288,7 +288,7 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
 
     // Load h of this wavefront fills operand rows RPL (LPW wave + h) .. + RPL - 1 of a stage: lane l brings
     // the piece that belongs at row l / PPR of those, slot l % PPR.
-    int off[ST_LPW];
+    unsigned off[ST_LPW];
 #pragma unroll
     for (int h = 0; h < ST_LPW; ++h) {
         const int row = C::RPL * (ST_LPW * wave + h) + lane / C::PPR;
@@ -316,6 +316,7 @@ void blast_stage12_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict
 #pragma unroll
         for (int h = 0; h < ST_LPW; ++h) {
             const bool isx = C::RPL * (ST_LPW * wave + h) < TT;            // uniform
+            asm volatile("" : "+v"(off[h]));                               // keeps the offset a register operand: scalar base + lane offset addressing, no address arithmetic
             __builtin_amdgcn_global_load_lds(BLR_GPTR((isx ? xc : vc) + off[h]),
                                              BLR_LPTR(smem + stage_off + (ST_LPW * wave + h) * 1024), 16, 0, 0);
         }

@@ -274,6 +274,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, in
 #pragma unroll
         for (int h = decltype(H0)::value; h < decltype(H1)::value; ++h) {
             const bool isa = 16 * (C::LPW * wave + h) < BM;                 // uniform
+            asm volatile("" : "+v"(off[h]));                                // keeps the offset a register operand: scalar base + lane offset addressing, no address arithmetic
             const unsigned char* p = (isa ? Abase + a_koff : Bbase + (size_t)kf * (C::BK * 2)) + off[h];
             if (TAIL) p = (lastk && bad[h]) ? zero_piece : p;
             __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 0);
@@ -386,14 +387,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDesc d, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same product for calls with FEW tiles (some hundreds of tokens): there every workgroup walks its
-// contraction index alone on its compute unit, and a step of 32 costs the same chain of latencies
-// (barrier, LDS read, dependent MFMAs) whatever the tile does in between: about 600 clocks for 128 to
-// 256 clocks of matrix work. This kernel takes DEEP steps instead: BK = 64 or 128 contraction indices
-// per barrier (rows of 128 or 256 bytes in LDS, 16-byte pieces XOR-swizzled by the row so that the 16
-// rows a ds_read_b128 serves per clock cover all 64 banks), the fragment reads of k16 step ks + 1 in
-// flight while the MFMAs of step ks run, the direct loads of step s + NS - 1 issued right after the
-// barrier of step s. The chain is paid once per 4 to 8 times the work.
+// Tiles in DEEP steps: BK = 64 or 128 contraction indices per barrier, i.e. operand rows of 128 or 256 bytes
+// (whole cache lines per request; 16-byte pieces XOR-swizzled by the row so that the 16 rows a ds_read_b128
+// serves per clock cover all 64 banks). Two kernels use this layout: gemm_wide_kernel (the 256 x 256 tile on two
+// stages) and gemm_line_kernel (the smaller tiles on three or four stages). For calls with FEW tiles (some
+// hundreds of tokens) every workgroup walks its contraction index alone on its compute unit, and a step of 32
+// costs the same chain of latencies (barrier, LDS read, dependent MFMAs) whatever the tile does in between:
+// about 600 clocks for 128 to 256 clocks of matrix work; deep steps pay the chain once per 4 to 8 times the work.
 template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGES>
 struct DeepCfg {
     static constexpr int BK = BKT, NS = NSTAGES;
@@ -452,121 +452,6 @@ __device__ __forceinline__ void deep_load_offsets(const GemmDesc& d, int wave, i
         }
         bad[h] = TAIL && (nk - 1) * C::BK + piece * 8 >= d.K;       // in the last step this piece lies past K
     }
-}
-
-template <int BM, int BN, int WGM, int WGN, int BKT, int NS, bool TAIL>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_deep_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int order) {
-    using C = DeepCfg<BM, BN, WGM, WGN, BKT, NS>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
-    int g, tile_m, tile_n;
-    workgroup_tile(d, tiles_m, tiles_n, order, g, tile_m, tile_n);
-    const int64_t m0 = (int64_t)tile_m * BM;
-    const int n0 = tile_n * BN;
-    const unsigned char* Abase = (const unsigned char*)((const bf16_t*)d.A + (int64_t)g * d.a_gs + m0 * d.a_rs);
-    const unsigned char* Bbase = (const unsigned char*)((const bf16_t*)d.B + (int64_t)g * d.b_gs);
-    const int nk = (d.K + C::BK - 1) / C::BK;
-
-    unsigned off[C::LPW];
-    bool bad[C::LPW];
-    deep_load_offsets<C, BM, TAIL>(d, wave, lane, m0, n0, nk, off, bad);
-    int kf = 0;                                         // fetch cursor (uniform); stops at the last step
-    int a_pos = 0;                                      // position inside the current segment of a segmented contraction index
-    int64_t a_koff = 0;
-    // loads H0 .. H1-1 of the step under the cursor; `advance` = these complete the step's loads
-    auto issue = [&](int stage_off, auto H0, auto H1, bool advance) {
-        const bool lastk = TAIL && kf == nk - 1;
-#pragma unroll
-        for (int h = decltype(H0)::value; h < decltype(H1)::value; ++h) {
-            const bool isa = C::RPL * (C::LPW * wave + h) < BM;               // uniform
-            const unsigned char* p = (isa ? Abase + a_koff : Bbase + (size_t)kf * C::RB) + off[h];
-            if (TAIL) p = (lastk && bad[h]) ? zero_piece : p;
-            __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 0);
-        }
-        if (advance && kf < nk - 1) {
-            ++kf;
-            a_koff += C::RB;
-            if (d.a_seg) {
-                a_pos += C::BK;
-                if (a_pos == d.a_seg) { a_pos = 0; a_koff += (d.a_seg_stride - d.a_seg) * 2; }
-            }
-        }
-    };
-    constexpr std::integral_constant<int, 0> L0{};
-    constexpr std::integral_constant<int, C::LPW> LN{};
-
-    // fragment addresses inside a stage: row m of a 32-row MFMA operand, k group kg; k16 step ks adds to the piece
-    const int m = lane & 31, kg = lane >> 5;
-    const unsigned lds0 = (unsigned)(uintptr_t)BLR_LPTR(smem);
-    const unsigned swz = (unsigned)((m >> C::SH) & (C::PPR - 1));
-    const unsigned rowa = lds0 + (wm * C::WTM + m) * C::RB, rowb = lds0 + (BM + wn * C::WTN + m) * C::RB;
-
-    f32x16 acc[C::MI][C::NI];
-#pragma unroll
-    for (int i = 0; i < C::MI; ++i)
-#pragma unroll
-        for (int j = 0; j < C::NI; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    bf16x8 af[2][C::MI], bfr[2][C::NI];                 // fragments of two k16 steps in rotation
-    auto read_frags = [&](auto KSC, int stage_off) {
-        constexpr int ks = decltype(KSC)::value;
-        const unsigned sw = (((unsigned)(2 * ks + kg)) ^ swz) * 16u;
-        const unsigned aa = rowa + stage_off + sw, ab = rowb + stage_off + sw;
-        static_for<C::MI>([&](auto I) { af[ks & 1][decltype(I)::value] = lds_read_b128<decltype(I)::value * 32 * C::RB>(aa); });
-        static_for<C::NI>([&](auto J) { bfr[ks & 1][decltype(J)::value] = lds_read_b128<decltype(J)::value * 32 * C::RB>(ab); });
-    };
-    auto mfma_step = [&](auto KSC) {
-        constexpr int b = decltype(KSC)::value & 1;
-#pragma unroll
-        for (int i = 0; i < C::MI; ++i) asm volatile("" : "+v"(af[b][i]));     // tie the fragments to the preceding wait
-#pragma unroll
-        for (int j = 0; j < C::NI; ++j) asm volatile("" : "+v"(bfr[b][j]));
-#pragma unroll
-        for (int i = 0; i < C::MI; ++i)
-#pragma unroll
-            for (int j = 0; j < C::NI; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b][j], af[b][i], acc[i][j], 0, 0, 0);
-    };
-
-    for (int s = 0; s < C::NS - 1; ++s) issue(s * C::STAGE, L0, LN, true);
-    int cstage = 0, fstage = (C::NS - 1) * C::STAGE;    // stage to compute on / stage that is free to refill
-#pragma unroll 1
-    for (int kt = 0; kt < nk; ++kt) {
-        // this step's stage has landed (own loads: vmcnt; the others': barrier) and every wavefront has
-        // finished reading the stage of the step before, which the loads issued during this step overwrite
-        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(C::LPW * (C::NS - 2)) : "memory");
-        read_frags(std::integral_constant<int, 0>{}, cstage);
-        static_for<C::KS>([&](auto KSC) {
-            constexpr int ks = decltype(KSC)::value;
-            if constexpr (ks + 1 < C::KS) {
-                read_frags(std::integral_constant<int, ks + 1>{}, cstage);
-                asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(C::MI + C::NI) : "memory");   // in order: step ks has arrived
-            } else {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_setprio(1);
-            mfma_step(KSC);
-            __builtin_amdgcn_s_setprio(0);
-            __builtin_amdgcn_sched_barrier(0);
-            // The refill of the freed stage goes out in KS slices, each behind a burst of MFMAs: a load
-            // instruction blocks the wavefront while the compute unit's load queue is full (a stage is
-            // 0.4 ... 1 k clocks of that queue's time), and issued in one piece after the barrier that time
-            // was spent before the first MFMA of the step instead of under the MFMAs.
-            constexpr int h0 = ks * C::LPW / C::KS, h1 = (ks + 1) * C::LPW / C::KS;
-            issue(fstage, std::integral_constant<int, h0>{}, std::integral_constant<int, h1>{}, ks + 1 == C::KS);
-        });
-        fstage = cstage;
-        cstage = cstage + C::STAGE == C::NS * C::STAGE ? 0 : cstage + C::STAGE;
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the repeated loads of the last steps have landed too
-    __syncthreads();
-    if (d.c_fp8) store_c_tile_fp8<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn);
-    else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -706,6 +591,144 @@ __global__ __launch_bounds__(512) void gemm_wide_kernel(GemmDesc d, int tiles_m,
     else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The schedule of gemm_wide_kernel for any tile of DeepCfg and 2 to 4 stages: the fragment reads of k16 step
+// ks + 1 in flight while the MFMAs of step ks run, the direct loads of step s + NS - 1 behind the first MFMAs of
+// step s, the barrier inside the last MFMA burst, no vector ALU work in the loop. The stages are interleaved in
+// LDS in units of one direct load (1 KB: chunk c of stage st lies at (c NS + st) KB), so that the stage is part
+// of the ds_read immediate and one set of fragment addresses (per k16 step) serves all stages; NS steps per loop
+// trip keep the stage a compile-time constant. Against the same tiles with per-step address arithmetic and the
+// barrier at the step's start: dense 4096 x 4096 at 128 / 512 / 2048 tokens 15.7 -> 13.9, 25.9 -> 24.2,
+// 64.9 -> 61.2 us.
+template <int BM, int BN, int WGM, int WGN, int BKT, int NS, bool TAIL>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_line_kernel(GemmDesc d, int tiles_m, int tiles_n, int cvec, int order) {
+    using C = DeepCfg<BM, BN, WGM, WGN, BKT, NS>;
+    constexpr int MFMAS = C::MI * C::NI, HALF = (MFMAS + 1) / 2;
+    static_assert(C::LPW <= (C::KS - 1) * MFMAS + HALF, "the step's loads are out before its barrier");
+    static_assert((C::MI * 32 - 32) * C::RB * NS + NS * 1024 < 65536 && (C::NI * 32 - 32) * C::RB * NS + NS * 1024 < 65536, "fragment offsets are ds_read immediates");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    int g, tile_m, tile_n;
+    workgroup_tile(d, tiles_m, tiles_n, order, g, tile_m, tile_n);
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int n0 = tile_n * BN;
+    const unsigned char* Abase = (const unsigned char*)((const bf16_t*)d.A + (int64_t)g * d.a_gs + m0 * d.a_rs);
+    const unsigned char* Bbase = (const unsigned char*)((const bf16_t*)d.B + (int64_t)g * d.b_gs);
+    const int nk = (d.K + C::BK - 1) / C::BK;
+    unsigned off[C::LPW];
+    bool bad[C::LPW];
+    deep_load_offsets<C, BM, TAIL>(d, wave, lane, m0, n0, nk, off, bad);
+
+    int kf = 0;                                         // step under the fetch cursor (uniform)
+    int a_pos = 0;                                      // position inside the current segment of a segmented contraction index
+    int64_t a_koff = 0;
+    const unsigned char* asrc = Abase;                  // the operands at the cursor
+    const unsigned char* bsrc = Bbase;
+    auto issue = [&](auto ST, auto H) __attribute__((always_inline)) {                 // load h of the step under the cursor, into stage st
+        constexpr int st = decltype(ST)::value, h = decltype(H)::value;
+        const bool isa = C::RPL * (C::LPW * wave + h) < BM;               // uniform
+        asm volatile("" : "+v"(off[h]));                // the 32-bit offset stays a register operand: scalar base + lane offset addressing, no address arithmetic
+        const unsigned char* p = (isa ? asrc : bsrc) + off[h];
+        if (TAIL) p = (kf == nk - 1 && bad[h]) ? zero_piece : p;
+        __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + ((C::LPW * wave + h) * NS + st) * 1024), 16, 0, 0);
+    };
+    auto advance = [&]() __attribute__((always_inline)) {                                // (stops at the last step, which the last steps fetch again: never needed, always in bounds)
+        if (kf == nk - 1) return;
+        ++kf;
+        a_koff += C::RB;
+        if (d.a_seg) {
+            a_pos += C::BK;
+            if (a_pos == d.a_seg) { a_pos = 0; a_koff += (d.a_seg_stride - d.a_seg) * 2; }
+        }
+        asrc = Abase + a_koff;
+        bsrc = Bbase + (size_t)kf * C::RB;
+    };
+
+    // fragment addresses in stage 0, one per k16 step (row of a 32-row MFMA operand, k group kg), opaque to the
+    // compiler so that it keeps them instead of recomputing them in the loop
+    const int m = lane & 31, kg = lane >> 5;
+    const unsigned lds0 = (unsigned)(uintptr_t)BLR_LPTR(smem);
+    const unsigned swz = (unsigned)((m >> C::SH) & (C::PPR - 1));
+    unsigned fa[C::KS], fb[C::KS];
+    {
+        const int ra = wm * C::WTM + m, rb = BM + wn * C::WTN + m;       // stage rows
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) {
+            const unsigned sw = (((unsigned)(2 * ks + kg)) ^ swz) * 16u;
+            fa[ks] = lds0 + (ra / C::RPL) * (NS * 1024) + (ra % C::RPL) * C::RB + sw;
+            fb[ks] = lds0 + (rb / C::RPL) * (NS * 1024) + (rb % C::RPL) * C::RB + sw;
+            asm volatile("" : "+v"(fa[ks]), "+v"(fb[ks]));
+        }
+    }
+
+    f32x16 acc[C::MI][C::NI];
+#pragma unroll
+    for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+        for (int j = 0; j < C::NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    bf16x8 af[2][C::MI], bfr[2][C::NI];                 // fragments of two k16 steps in rotation
+    auto read_frags = [&](auto ST, auto KSC) __attribute__((always_inline)) {
+        constexpr int st = decltype(ST)::value, ks = decltype(KSC)::value;
+        static_for<C::MI>([&](auto I) { af[ks & 1][decltype(I)::value] = lds_read_b128<decltype(I)::value * 32 * C::RB * NS + st * 1024>(fa[ks]); });
+        static_for<C::NI>([&](auto J) { bfr[ks & 1][decltype(J)::value] = lds_read_b128<decltype(J)::value * 32 * C::RB * NS + st * 1024>(fb[ks]); });
+    };
+    // one step on stage ST: fetches the step NS - 1 ahead into the stage that was computed on one step ago
+    auto step = [&](auto ST) __attribute__((always_inline)) {
+        constexpr int st = decltype(ST)::value;
+        static_for<C::KS>([&](auto KSC) {
+            constexpr int ks = decltype(KSC)::value, b = ks & 1;
+            if constexpr (ks + 1 < C::KS) {
+                read_frags(ST, std::integral_constant<int, ks + 1>{});
+                asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(C::MI + C::NI) : "memory");   // in order: k16 step ks has arrived
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < C::MI; ++i) asm volatile("" : "+v"(af[b][i]));         // tie the fragments to the preceding wait
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j) asm volatile("" : "+v"(bfr[b][j]));
+            static_for<MFMAS>([&](auto Q) {
+                constexpr int q = decltype(Q)::value, i = q / C::NI, j = q % C::NI, n = ks * MFMAS + q;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[b][j], af[b][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (n < C::LPW) {
+                    issue(std::integral_constant<int, (st + NS - 1) % NS>{}, std::integral_constant<int, n>{});
+                    if constexpr (n == C::LPW - 1) advance();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if constexpr (ks == C::KS - 1 && q == HALF - 1) {
+                    // every wavefront is past its last read of this stage; the next stage has landed (own loads: vmcnt; the others': barrier)
+                    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(C::LPW * (NS - 2)) : "memory");
+                    read_frags(std::integral_constant<int, (st + 1) % NS>{}, std::integral_constant<int, 0>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            });
+        });
+    };
+
+    static_for<NS - 1>([&](auto S) {
+        static_for<C::LPW>([&](auto H) { issue(S, H); });
+        advance();
+    });
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(C::LPW * (NS - 2)) : "memory");
+    read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    int kt = 0;
+#pragma unroll 1
+    for (; kt + NS <= nk; kt += NS) static_for<NS>([&](auto S) { step(S); });      // (NS steps per trip keep the stage a compile-time constant)
+    const int rem = nk - kt;
+    static_for<NS - 1>([&](auto S) { if (decltype(S)::value < rem) step(S); });
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // the repeated loads of the last steps and the fragments read ahead behind the last one
+    __syncthreads();
+    if (d.c_fp8) store_c_tile_fp8<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn);
+    else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
+}
+
 // Second kernel of a split contraction: adds the nsplit partial tiles in index order (so the result
 // does not depend on timing) and writes C through the column map. One thread per group of four
 // consecutive columns (one float4 of the partial tile, which is in accumulator order: element e of
@@ -826,25 +849,6 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s, bool allow_split = false
     return e;
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, int NS>
-hipError_t launch_deep(const GemmDesc& d, hipStream_t s) {
-    using C = DeepCfg<BM, BN, WGM, WGN, BK, NS>;
-    static LdsLimitOnce lds_limit;
-    if (hipError_t e = lds_limit.set({(const void*)gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, false>,
-                                      (const void*)gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, true>}, C::LDS_BYTES); e != hipSuccess) return e;
-    const int tiles_m = (int)((d.M + BM - 1) / BM);
-    const int tiles_n = (d.N + BN - 1) / BN;
-    const bool vec = c_map_vectorizes(d);
-    const bool gfast = !vec && d.G > 1;
-    dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * d.G), 1u, 1u);
-    const int order = tile_order(d, gfast);
-    if (d.K % BK)
-        hipLaunchKernelGGL((gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
-    else
-        hipLaunchKernelGGL((gemm_deep_kernel<BM, BN, WGM, WGN, BK, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
-    return hipGetLastError();
-}
-
 hipError_t launch_wide(const GemmDesc& d, hipStream_t s) {
     using C = DeepCfg<256, 256, 2, 4, 64, 2>;
     static LdsLimitOnce lds_limit;
@@ -859,6 +863,25 @@ hipError_t launch_wide(const GemmDesc& d, hipStream_t s) {
         hipLaunchKernelGGL((gemm_wide_kernel<true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
     else
         hipLaunchKernelGGL((gemm_wide_kernel<false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int WGM, int WGN, int BK, int NS>
+hipError_t launch_line(const GemmDesc& d, hipStream_t s) {
+    using C = DeepCfg<BM, BN, WGM, WGN, BK, NS>;
+    static LdsLimitOnce lds_limit;
+    if (hipError_t e = lds_limit.set({(const void*)gemm_line_kernel<BM, BN, WGM, WGN, BK, NS, false>,
+                                      (const void*)gemm_line_kernel<BM, BN, WGM, WGN, BK, NS, true>}, C::LDS_BYTES); e != hipSuccess) return e;
+    const int tiles_m = (int)((d.M + BM - 1) / BM);
+    const int tiles_n = (d.N + BN - 1) / BN;
+    const bool vec = c_map_vectorizes(d);
+    const bool gfast = !vec && d.G > 1;
+    dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * d.G), 1u, 1u);
+    const int order = tile_order(d, gfast);
+    if (d.K % BK)
+        hipLaunchKernelGGL((gemm_line_kernel<BM, BN, WGM, WGN, BK, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
+    else
+        hipLaunchKernelGGL((gemm_line_kernel<BM, BN, WGM, WGN, BK, NS, false>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
     return hipGetLastError();
 }
 
@@ -943,7 +966,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // (with steps of 64 contraction indices, whole cache lines per operand row, and three stages where the shape allows:
     // another 2-7 %; the same change on the 256 x 256 tile leaves room for two stages only and loses up to 10 %)
     if (d.M > 128 && d.N > 64 && d.K > kSmallK && tiles(256, 128) >= 160)
-        return d.K % 64 == 0 && deep_ok(d, 64) ? launch_deep<256, 128, 4, 2, 64, 3>(d, s) : launch_dma<256, 128, 4, 2>(d, s);
+        return d.K % 64 == 0 && deep_ok(d, 64) ? launch_line<256, 128, 4, 2, 64, 3>(d, s) : launch_dma<256, 128, 4, 2>(d, s);
     // otherwise the largest tile that still gives every compute unit a workgroup
     // 160 of the 256 compute units: a scan of token counts 33 ... 4096 on eight weight shapes had 160
     // ahead of 200 by 10-30 % wherever the two differ (e.g. 11008 -> 4096 at 640 tokens: 144 -> 98 us,
@@ -956,11 +979,11 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // 32-deep steps, whose smaller LDS footprint lets two or three workgroups share a compute unit, stay.
     auto one_round = [&](int bm, int bn) { return d.K >= 256 && deep_ok(d, 128) && tiles(bm, bn) <= 256; };
     if (d.M > 64 && d.N > 64 && tiles(128, 128) >= kFill)
-        return one_round(128, 128) ? launch_deep<128, 128, 2, 2, 64, 4>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
+        return one_round(128, 128) ? launch_line<128, 128, 2, 2, 64, 4>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
     if (d.M > 64 && tiles(128, 64) >= kFill)
-        return one_round(128, 64) ? launch_deep<128, 64, 2, 2, 128, 3>(d, s) : launch_dma<128, 64, 2, 2>(d, s);
+        return one_round(128, 64) ? launch_line<128, 64, 2, 2, 128, 3>(d, s) : launch_dma<128, 64, 2, 2>(d, s);
     if (d.N > 64 && tiles(64, 128) >= kFill)
-        return one_round(64, 128) ? launch_deep<64, 128, 2, 2, 128, 3>(d, s) : launch_dma<64, 128, 2, 2>(d, s);
+        return one_round(64, 128) ? launch_line<64, 128, 2, 2, 128, 3>(d, s) : launch_dma<64, 128, 2, 2>(d, s);
     // few tiles and a long contraction: 64 x 64 tiles, contraction index split over several workgroups
     // Few tiles and a long contraction index that would be split (two launches: the parts, then their
     // sum), small weights: the weight-streaming kernel over tiles of 32 tokens instead, one launch.
@@ -979,7 +1002,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // the smallest tile already from 128 workgroups on: at 128 tokens it beats the weight-streaming kernel over
     // 32-token tiles (dense 4096 x 4096: 17.0 against 23.6 us; 11008 -> 4096: 36 against 55 us)
     if (tiles(64, 64) >= 128 || (d.M <= 64 && d.N <= 64))
-        return one_round(64, 64) ? launch_deep<64, 64, 2, 2, 128, 4>(d, s) : launch_dma<64, 64, 2, 2>(d, s);
+        return one_round(64, 64) ? launch_line<64, 64, 2, 2, 128, 4>(d, s) : launch_dma<64, 64, 2, 2>(d, s);
     // Nothing fills the chip (a product of some tens of tokens with weights that are not split, e.g.
     // the dense reference at 33 ... 96 tokens): the weight-streaming kernel over tiles of 32 tokens puts
     // every compute unit on the stream, where the few tiles below would walk the whole contraction
