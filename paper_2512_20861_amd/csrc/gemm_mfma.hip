@@ -495,9 +495,15 @@ __global__ __launch_bounds__(512) void gemm_wide_kernel(GemmDesc d, int tiles_m,
     auto issue = [&](int stage_off, auto H) {
         constexpr int h = decltype(H)::value;
         asm volatile("" : "+v"(off[h]));                // the 32-bit offset stays a register operand: scalar base + lane offset addressing, no address arithmetic
-        const unsigned char* p = src + off[h];
-        if (TAIL) p = (kf == nk - 1 && bad[h]) ? zero_piece : p;
-        __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 0);
+        if (TAIL && kf == nk - 1) {
+            // A branch, not a select: only the fetch of the last step pays for the per-lane choice. (The non-temporal
+            // hint does no harm there and keeps the compiler from merging the two loads into one with a selected address.)
+            unsigned o = off[h];
+            asm volatile("" : "+v"(o));                 // (its own copy: a common address would be computed ahead of the branch, in vector registers)
+            __builtin_amdgcn_global_load_lds(BLR_GPTR(bad[h] ? zero_piece : src + o), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 2);
+        } else {
+            __builtin_amdgcn_global_load_lds(BLR_GPTR(src + off[h]), BLR_LPTR(smem + stage_off + (C::LPW * wave + h) * 1024), 16, 0, 0);
+        }
     };
     auto advance = [&] {                                // (stops at the last step, which the last steps fetch again: never needed, always in bounds)
         if (kf == nk - 1) return;
@@ -630,9 +636,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_line_kernel(GemmDesc d, i
         constexpr int st = decltype(ST)::value, h = decltype(H)::value;
         const bool isa = C::RPL * (C::LPW * wave + h) < BM;               // uniform
         asm volatile("" : "+v"(off[h]));                // the 32-bit offset stays a register operand: scalar base + lane offset addressing, no address arithmetic
-        const unsigned char* p = (isa ? asrc : bsrc) + off[h];
-        if (TAIL) p = (kf == nk - 1 && bad[h]) ? zero_piece : p;
-        __builtin_amdgcn_global_load_lds(BLR_GPTR(p), BLR_LPTR(smem + ((C::LPW * wave + h) * NS + st) * 1024), 16, 0, 0);
+        const unsigned char* base = isa ? asrc : bsrc;
+        if (TAIL && kf == nk - 1) {                     // (a branch, a different cache hint and its own copy of the offset, as in gemm_wide_kernel)
+            unsigned o = off[h];
+            asm volatile("" : "+v"(o));
+            __builtin_amdgcn_global_load_lds(BLR_GPTR(bad[h] ? zero_piece : base + o), BLR_LPTR(smem + ((C::LPW * wave + h) * NS + st) * 1024), 16, 0, 2);
+        } else {
+            __builtin_amdgcn_global_load_lds(BLR_GPTR(base + off[h]), BLR_LPTR(smem + ((C::LPW * wave + h) * NS + st) * 1024), 16, 0, 0);
+        }
     };
     auto advance = [&]() __attribute__((always_inline)) {                                // (stops at the last step, which the last steps fetch again: never needed, always in bounds)
         if (kf == nk - 1) return;
