@@ -937,9 +937,10 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
         if (!gemm_fp8_store_supported(d)) return hipErrorInvalidValue;
         auto tiles8 = [&](int bm, int bn) { return (int64_t)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.G; };
         if (d.M > 128 && d.N > 128 && d.K > 128 && tiles8(256, 256) >= 160) return big(d);
-        if (d.M > 64 && d.N > 64 && tiles8(128, 128) >= 160) return launch_dma<128, 128, 2, 2>(d, s);
-        if (d.M > 64 && tiles8(128, 64) >= 160) return launch_dma<128, 64, 2, 2>(d, s);
-        return launch_dma<64, 64, 2, 2>(d, s);
+        const bool deep8 = d.K >= 256 && deep_ok(d, 64);     // (as for the 16-bit C below)
+        if (d.M > 64 && d.N > 64 && tiles8(128, 128) >= 160) return deep8 ? launch_line<128, 128, 2, 2, 64, 2>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
+        if (d.M > 64 && tiles8(128, 64) >= 160) return deep8 ? launch_line<128, 64, 2, 2, 64, 2>(d, s) : launch_dma<128, 64, 2, 2>(d, s);
+        return deep8 ? launch_line<64, 64, 2, 2, 64, 2>(d, s) : launch_dma<64, 64, 2, 2>(d, s);
     }
     if (skinny_gemm_supported(d)) return launch_gemm_skinny(d, c_map_vectorizes(d), s);
     constexpr int kSmallK = 128;     // very short contractions: 128 x 128 tiles, two workgroups per CU overlap prologue and epilogue
@@ -967,7 +968,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
             d2.A = (const bf16_t*)d.A + d1.M * d.a_rs;
             d2.C = (bf16_t*)d.C + d1.M * d.c_rs;
             if (hipError_t e = big(d1); e != hipSuccess) return e;
-            return launch_dma<128, 128, 2, 2>(d2, s);
+            return d2.K >= 256 && deep_ok(d2, 64) ? launch_line<128, 128, 2, 2, 64, 2>(d2, s) : launch_dma<128, 128, 2, 2>(d2, s);
         }
         return big(d);
     }
@@ -977,7 +978,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // (with steps of 64 contraction indices, whole cache lines per operand row, and three stages where the shape allows:
     // another 2-7 %; the same change on the 256 x 256 tile leaves room for two stages only and loses up to 10 %)
     if (d.M > 128 && d.N > 64 && d.K > kSmallK && tiles(256, 128) >= 160)
-        return d.K % 64 == 0 && deep_ok(d, 64) ? launch_line<256, 128, 4, 2, 64, 3>(d, s) : launch_dma<256, 128, 4, 2>(d, s);
+        return deep_ok(d, 64) ? launch_line<256, 128, 4, 2, 64, 3>(d, s) : launch_dma<256, 128, 4, 2>(d, s);
     // otherwise the largest tile that still gives every compute unit a workgroup
     // 160 of the 256 compute units: a scan of token counts 33 ... 4096 on eight weight shapes had 160
     // ahead of 200 by 10-30 % wherever the two differ (e.g. 11008 -> 4096 at 640 tokens: 144 -> 98 us,
@@ -989,12 +990,16 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // 256 ... 2048 tokens: 5-25 % faster for one round; with more workgroups than compute units the
     // 32-deep steps, whose smaller LDS footprint lets two or three workgroups share a compute unit, stay.
     auto one_round = [&](int bm, int bn) { return d.K >= 256 && deep_ok(d, 128) && tiles(bm, bn) <= 256; };
+    // With more workgroups than that: steps of 64 on two stages, whose 32 ... 64 KB of LDS let two or three workgroups
+    // share a compute unit as the 32-deep kernel's do, in whole cache lines and on the schedule of gemm_line_kernel
+    // (768 x 768 at 6304 tokens: 19.1 -> 14.4 us; 3072 -> 768: 58.6 -> 40.8 us; 1152 x 1152 at 1024 tokens: 10.9 -> 8.0 us)
+    const bool rounds_deep = d.K >= 256 && deep_ok(d, 64);
     if (d.M > 64 && d.N > 64 && tiles(128, 128) >= kFill)
-        return one_round(128, 128) ? launch_line<128, 128, 2, 2, 64, 4>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
+        return one_round(128, 128) ? launch_line<128, 128, 2, 2, 64, 4>(d, s) : rounds_deep ? launch_line<128, 128, 2, 2, 64, 2>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
     if (d.M > 64 && tiles(128, 64) >= kFill)
-        return one_round(128, 64) ? launch_line<128, 64, 2, 2, 128, 3>(d, s) : launch_dma<128, 64, 2, 2>(d, s);
+        return one_round(128, 64) ? launch_line<128, 64, 2, 2, 128, 3>(d, s) : rounds_deep ? launch_line<128, 64, 2, 2, 64, 2>(d, s) : launch_dma<128, 64, 2, 2>(d, s);
     if (d.N > 64 && tiles(64, 128) >= kFill)
-        return one_round(64, 128) ? launch_line<64, 128, 2, 2, 128, 3>(d, s) : launch_dma<64, 128, 2, 2>(d, s);
+        return one_round(64, 128) ? launch_line<64, 128, 2, 2, 128, 3>(d, s) : rounds_deep ? launch_line<64, 128, 2, 2, 64, 2>(d, s) : launch_dma<64, 128, 2, 2>(d, s);
     // few tiles and a long contraction: 64 x 64 tiles, contraction index split over several workgroups
     // Few tiles and a long contraction index that would be split (two launches: the parts, then their
     // sum), small weights: the weight-streaming kernel over tiles of 32 tokens instead, one launch.
@@ -1013,7 +1018,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // the smallest tile already from 128 workgroups on: at 128 tokens it beats the weight-streaming kernel over
     // 32-token tiles (dense 4096 x 4096: 17.0 against 23.6 us; 11008 -> 4096: 36 against 55 us)
     if (tiles(64, 64) >= 128 || (d.M <= 64 && d.N <= 64))
-        return one_round(64, 64) ? launch_line<64, 64, 2, 2, 128, 4>(d, s) : launch_dma<64, 64, 2, 2>(d, s);
+        return one_round(64, 64) ? launch_line<64, 64, 2, 2, 128, 4>(d, s) : rounds_deep ? launch_line<64, 64, 2, 2, 64, 2>(d, s) : launch_dma<64, 64, 2, 2>(d, s);
     // Nothing fills the chip (a product of some tens of tokens with weights that are not split, e.g.
     // the dense reference at 33 ... 96 tokens): the weight-streaming kernel over tiles of 32 tokens puts
     // every compute unit on the stream, where the few tiles below would walk the whole contraction
