@@ -592,6 +592,10 @@ __global__ __launch_bounds__(512) void gemm_wide_kernel(GemmDesc d, int tiles_m,
     }
     if (nk & 1) step(std::integral_constant<int, 0>{});
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the fragments read ahead behind the last step are not used
+#pragma unroll
+    for (int i = 0; i < C::MI; ++i) asm volatile("" :: "v"(af[0][i]));     // (their registers stay theirs until they have arrived)
+#pragma unroll
+    for (int j = 0; j < C::NI; ++j) asm volatile("" :: "v"(bfr[0][j]));
     __syncthreads();
     if (d.c_fp8) store_c_tile_fp8<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn);
     else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
@@ -735,6 +739,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_line_kernel(GemmDesc d, i
     const int rem = nk - kt;
     static_for<NS - 1>([&](auto S) { if (decltype(S)::value < rem) step(S); });
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // the repeated loads of the last steps and the fragments read ahead behind the last one
+#pragma unroll
+    for (int i = 0; i < C::MI; ++i) asm volatile("" :: "v"(af[0][i]));     // (their registers stay theirs until they have arrived)
+#pragma unroll
+    for (int j = 0; j < C::NI; ++j) asm volatile("" :: "v"(bfr[0][j]));
     __syncthreads();
     if (d.c_fp8) store_c_tile_fp8<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn);
     else store_c_tile<BM, BN, C::WTM, C::WTN, C::MI, C::NI, C::CSTR, C::THREADS>(d, acc, smem, m0, n0, g, wm, wn, cvec);
