@@ -233,6 +233,24 @@ def test_dense_large_tile_short_and_partial_steps(T, n_in, n_out):
     assert err <= gu.TOL["bf16"]
 
 
+# more workgroups than one round on each of the four small tiles (128x128, 128x64, 64x128, 64x64 by the dispatch
+# rules), which take 64-deep steps on two stages: whole steps and a partial last step, odd and even step counts
+@pytest.mark.parametrize("T,n_out", [(6304, 768), (2800, 768), (64, 40960), (1400, 768)])
+@pytest.mark.parametrize("n_in", [320, 328, 448])
+def test_dense_multi_round_small_tiles(T, n_in, n_out):
+    gu = _gu()
+    W = bi.dense_weight(n_in, n_out, "bf16")
+    X = bi.activations(T, n_in, "bf16")
+    Y = gu.empty_out(T, n_out, "bf16")
+    gu.B.dense_reference_forward(gu.to_dev(X), gu.to_dev(W), Y, 0)
+    torch.cuda.synchronize()
+    out = gu.to_f64(Y)
+    assert np.isfinite(out).all()
+    err = gu.rel_err(out, oracle.dense_forward(X.f64, W.f64))
+    print(f"dense {T}x{n_in}->{n_out} small tiles, several rounds: rel err {err:.3e}")
+    assert err <= gu.TOL["bf16"]
+
+
 # ---------------------------------------------------------------- Monarch, different block counts on the two sides
 # (T, n_in, n_out, b_in, b_out, r_block, dtype): MFMA-aligned and ragged shapes, few and many tokens
 MONARCH_RECT_CASES = [
