@@ -945,7 +945,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
         if (!gemm_fp8_store_supported(d)) return hipErrorInvalidValue;
         auto tiles8 = [&](int bm, int bn) { return (int64_t)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.G; };
         if (d.M > 128 && d.N > 128 && d.K > 128 && tiles8(256, 256) >= 160) return big(d);
-        const bool deep8 = d.K >= 256 && deep_ok(d, 64);     // (as for the 16-bit C below)
+        const bool deep8 = d.K >= 128 && deep_ok(d, 64);     // (as for the 16-bit C below)
         if (d.M > 64 && d.N > 64 && tiles8(128, 128) >= 160) return deep8 ? launch_line<128, 128, 2, 2, 64, 2>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
         if (d.M > 64 && tiles8(128, 64) >= 160) return deep8 ? launch_line<128, 64, 2, 2, 64, 2>(d, s) : launch_dma<128, 64, 2, 2>(d, s);
         return deep8 ? launch_line<64, 64, 2, 2, 64, 2>(d, s) : launch_dma<64, 64, 2, 2>(d, s);
@@ -976,7 +976,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
             d2.A = (const bf16_t*)d.A + d1.M * d.a_rs;
             d2.C = (bf16_t*)d.C + d1.M * d.c_rs;
             if (hipError_t e = big(d1); e != hipSuccess) return e;
-            return d2.K >= 256 && deep_ok(d2, 64) ? launch_line<128, 128, 2, 2, 64, 2>(d2, s) : launch_dma<128, 128, 2, 2>(d2, s);
+            return deep_ok(d2, 64) ? launch_line<128, 128, 2, 2, 64, 2>(d2, s) : launch_dma<128, 128, 2, 2>(d2, s);
         }
         return big(d);
     }
@@ -1001,7 +1001,7 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
     // With more workgroups than that: steps of 64 on two stages, whose 32 ... 64 KB of LDS let two or three workgroups
     // share a compute unit as the 32-deep kernel's do, in whole cache lines and on the schedule of gemm_line_kernel
     // (768 x 768 at 6304 tokens: 19.1 -> 14.4 us; 3072 -> 768: 58.6 -> 40.8 us; 1152 x 1152 at 1024 tokens: 10.9 -> 8.0 us)
-    const bool rounds_deep = d.K >= 256 && deep_ok(d, 64);
+    const bool rounds_deep = d.K >= 128 && deep_ok(d, 64);   // (from two steps on: 128 -> 2304 at 32768 tokens 53.7 -> 46.0 us; 192 -> 768 at 6304 tokens 8.4 -> 7.4 us)
     if (d.M > 64 && d.N > 64 && tiles(128, 128) >= kFill)
         return one_round(128, 128) ? launch_line<128, 128, 2, 2, 64, 4>(d, s) : rounds_deep ? launch_line<128, 128, 2, 2, 64, 2>(d, s) : launch_dma<128, 128, 2, 2>(d, s);
     if (d.M > 64 && tiles(128, 64) >= kFill)
