@@ -496,7 +496,9 @@ def test_monarch_group_first_factor_and_grouped_call(dtype):
         assert gu.rel_err(Yh[:, m * n_out:(m + 1) * n_out], ref) <= gu.TOL[dtype]
 
 
-@pytest.mark.parametrize("shape", [(700, 1024, 512, 16, 256), (333, 2048, 1024, 16, 512), (2100, 768, 3072, 6, 192), (64, 1024, 1024, 8, 128)])
+# (the last shape: enough tokens for the 256 x 256 tile with the 8-bit epilogue, and a second, short chunk of tokens)
+@pytest.mark.parametrize("shape", [(700, 1024, 512, 16, 256), (333, 2048, 1024, 16, 512), (2100, 768, 3072, 6, 192), (64, 1024, 1024, 8, 128),
+                                   (6200, 4096, 512, 16, 256)])
 def test_blast_quantised_intermediate(shape):
     """BLAST with Z stored as E4M3 between the stage-1 product and the coupling (the paper's future work on
     quantised intermediate activations) against the oracle that rounds Z the same way, at the stated bf16
