@@ -818,11 +818,25 @@ inline int tile_order(const GemmDesc& d, bool gfast) {
     return 0;
 }
 
+// The order for a launch whose output stores are vectorised (vec) or element-wise.
+// Column maps that scatter runs shorter than a 128-byte line: the batches whose runs share lines run
+// side by side (batch index fastest). Element-wise stores always; vector stores only when the
+// output is larger than the 256 MB memory-side cache, where the parts of a line would otherwise
+// reach HBM one by one (stage 1 of Monarch with 16 to 48 ranks per block at 16 k and more tokens:
+// 17-24 % faster; with a cache-resident output the batch-major order is up to 20 % faster).
+inline int launch_tile_order(const GemmDesc& d, bool vec);
+
 // can 8 consecutive (8-aligned) tile columns be stored as one 16-byte vector?
 inline bool c_map_vectorizes(const GemmDesc& d) {
     if (!aligned16(d.C) || d.c_rs % 8 || d.N % 8 || d.c_gs % 8) return false;
     if (d.c_div == 1) return d.c_hi == 1;
     return d.c_div % 8 == 0 && d.c_lo == 1 && d.c_hi % 8 == 0;
+}
+
+inline int launch_tile_order(const GemmDesc& d, bool vec) {
+    const bool runs_share_lines = vec && d.c_div > 1 && d.c_div < 64 && d.c_hi != d.c_div &&
+                                  (int64_t)d.M * d.c_rs * 2 >= (256ll << 20);
+    return tile_order(d, (!vec || runs_share_lines) && d.G > 1);
 }
 
 // per-lane source offsets are 32-bit; operands further apart than that take the portable kernel
@@ -840,20 +854,12 @@ hipError_t launch_dma(const GemmDesc& d, hipStream_t s, bool allow_split = false
     const int tiles_m = (int)((d.M + BM - 1) / BM);
     const int tiles_n = (d.N + BN - 1) / BN;
     const bool vec = c_map_vectorizes(d);
-    // Column maps that scatter runs shorter than a 128-byte line: the batches whose runs share lines run
-    // side by side (batch index fastest). Element-wise stores always; vector stores only when the
-    // output is larger than the 256 MB memory-side cache, where the parts of a line would otherwise
-    // reach HBM one by one (stage 1 of Monarch with 16 to 48 ranks per block at 16 k and more tokens:
-    // 17-24 % faster; with a cache-resident output the batch-major order is up to 20 % faster).
-    const bool runs_share_lines = vec && d.c_div > 1 && d.c_div < 64 && d.c_hi != d.c_div &&
-                                  (int64_t)d.M * d.c_rs * 2 >= (256ll << 20);
-    const bool gfast = (!vec || runs_share_lines) && d.G > 1;
     const int64_t ntiles = (int64_t)tiles_m * tiles_n * d.G;
     SplitPlan sp = split_plan(ntiles, d.K);
     if (!allow_split || !d.split_scratch || (size_t)sp.nsplit * ntiles * BM * BN * sizeof(float) > d.split_scratch_bytes)
         sp = SplitPlan{1, (d.K + C::BK - 1) / C::BK};
     dim3 grid((unsigned)ntiles, 1u, (unsigned)sp.nsplit);
-    const int order = tile_order(d, gfast);
+    const int order = launch_tile_order(d, vec);
     if (d.K % C::BK)
         hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order, sp.kspan);
     else
@@ -875,9 +881,8 @@ hipError_t launch_wide(const GemmDesc& d, hipStream_t s) {
     const int tiles_m = (int)((d.M + 255) / 256);
     const int tiles_n = (d.N + 255) / 256;
     const bool vec = c_map_vectorizes(d);
-    const bool gfast = !vec && d.G > 1;
     dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * d.G), 1u, 1u);
-    const int order = tile_order(d, gfast);
+    const int order = launch_tile_order(d, vec);
     if (d.K % 64)
         hipLaunchKernelGGL((gemm_wide_kernel<true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
     else
@@ -894,9 +899,8 @@ hipError_t launch_line(const GemmDesc& d, hipStream_t s) {
     const int tiles_m = (int)((d.M + BM - 1) / BM);
     const int tiles_n = (d.N + BN - 1) / BN;
     const bool vec = c_map_vectorizes(d);
-    const bool gfast = !vec && d.G > 1;
     dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * d.G), 1u, 1u);
-    const int order = tile_order(d, gfast);
+    const int order = launch_tile_order(d, vec);
     if (d.K % BK)
         hipLaunchKernelGGL((gemm_line_kernel<BM, BN, WGM, WGN, BK, NS, true>), grid, dim3(C::THREADS), C::LDS_BYTES, s, d, tiles_m, tiles_n, vec ? 1 : 0, order);
     else
