@@ -982,6 +982,29 @@ hipError_t launch_gemm_mfma(const GemmDesc& d, hipStream_t s) {
             if (hipError_t e = big(d1); e != hipSuccess) return e;
             return deep_ok(d2, 64) ? launch_line<128, 128, 2, 2, 64, 2>(d2, s) : launch_dma<128, 128, 2, 2>(d2, s);
         }
+        // The same along the columns, where the weight rows are not gathered and the column map is linear in whole
+        // column tiles: the column tiles that fill whole rounds go out on the large tile, the remaining columns as a
+        // product of their own (one round of smaller tiles by the rules below). Stage 2 of the 4096 -> 11008 Monarch
+        // layer at 8192 tokens is 32 x 11 x 4 = 1408 tiles, 5.5 rounds paid as 6: 10 of the 11 column tiles are exactly
+        // 5 rounds, the last 192 columns one round of 256 x 128 tiles (no gain there: that round costs 30 of the 34 us
+        // it replaces); dense 4096 -> 11008 at 2048 / 5120 / 8192 tokens: 172 -> 148, 381 -> 365, 593 -> 576 us; no
+        // shape of a scan over six layer shapes and ten token counts slower.
+        const int64_t per_col = rows * d.G, cols = (d.N + 255) / 256;
+        const int64_t cols1 = whole * ncu / per_col;
+        const int64_t n1 = cols1 * 256;
+        if (whole >= 1 && rest > 0 && rest * 10 <= ncu * 6 && cols1 >= 1 && cols1 < cols && d.b_div == 0 && !d.c_fp8 &&
+            (d.c_div == 1 || n1 % d.c_div == 0)) {
+            GemmDesc d1 = d, d2 = d;
+            d1.N = (int)n1;
+            d2.N = d.N - (int)n1;
+            d2.B = (const bf16_t*)d.B + n1 * d.b_rs;
+            d2.C = (bf16_t*)d.C + (d.c_div == 1 ? n1 * d.c_hi : (n1 / d.c_div) * d.c_hi);
+            const int64_t t256 = rows * ((d2.N + 127) / 128) * d.G, t128 = ((d.M + 127) / 128) * ((d2.N + 127) / 128) * d.G;
+            if (t256 <= ncu || t128 <= 2 * ncu) {
+                if (hipError_t e = big(d1); e != hipSuccess) return e;
+                return launch_gemm_mfma(d2, s);
+            }
+        }
         return big(d);
     }
     // Between the two, where the 256 x 256 tiles are too few: 256 x 128 on 8 wavefronts of 64 x 64, one workgroup per

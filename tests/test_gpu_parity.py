@@ -218,7 +218,9 @@ def test_dense_parity(T, n_in, n_out, dtype, generic):
 
 # enough 256 x 256 tiles for the large-tile kernel, whose steps are 64 contraction indices deep: an even and an odd
 # number of steps, a last step with 8 valid indices, ragged token and output counts (a last row of tiles with one row)
-@pytest.mark.parametrize("T,n_in,n_out", [(2561, 328, 4100), (2600, 456, 4096), (2560, 448, 4096), (2817, 192, 3848)])
+# (the last case: 8 x 43 tiles are one round and a third; the column tiles that fill the round and the remaining
+# 2816 columns go out as two products)
+@pytest.mark.parametrize("T,n_in,n_out", [(2561, 328, 4100), (2600, 456, 4096), (2560, 448, 4096), (2817, 192, 3848), (2048, 256, 11008)])
 def test_dense_large_tile_short_and_partial_steps(T, n_in, n_out):
     gu = _gu()
     W = bi.dense_weight(n_in, n_out, "bf16")
