@@ -264,6 +264,7 @@ MONARCH_RECT_CASES = [
     (130, 60, 84, 3, 4, 5, "bf16"),
     (33, 60, 84, 5, 2, 3, "f32"),
     (200, 1152, 3456, 9, 3, 24, "bf16"),
+    (3000, 1024, 2048, 4, 4, 72, "bf16"),   # several rounds of the deep-step tiles: gathered weight rows with a ragged column count (288), a partial last step (K = 288)
 ]
 
 
