@@ -47,6 +47,33 @@ def test_dense_random_shape(T, n_in, n_out):
     assert err <= gu.TOL["bf16"], (T, n_in, n_out, err)
 
 
+def _dense_large_shapes():
+    """Enough tiles for the large-tile rules: several rounds of workgroups, a last round split off along rows or columns,
+    ragged token and column counts, contraction lengths with a partial last step of 64."""
+    rng = np.random.default_rng(4096)
+    out = []
+    for _ in range(12):
+        M = int(rng.integers(1500, 9000))
+        N = int(rng.integers(128, 750)) * 8
+        K = int(rng.integers(17, 88)) * 8
+        out.append((M, K, N))
+    return out
+
+
+@pytest.mark.parametrize("T,n_in,n_out", _dense_large_shapes())
+def test_dense_random_large_shape(T, n_in, n_out):
+    gu = _gu()
+    W = bi.dense_weight(n_in, n_out, "bf16", seed=T * 7 + n_out)
+    X = bi.activations(T, n_in, "bf16", seed=n_in)
+    Y = gu.empty_out(T, n_out, "bf16")
+    gu.B.dense_reference_forward(gu.to_dev(X), gu.to_dev(W), Y)
+    torch.cuda.synchronize()
+    out = gu.to_f64(Y)
+    assert np.isfinite(out).all()
+    err = gu.rel_err(out, oracle.dense_forward(X.f64, W.f64))
+    assert err <= gu.TOL["bf16"], (T, n_in, n_out, err)
+
+
 def _monarch_shapes():
     rng = np.random.default_rng(7)
     out = []
