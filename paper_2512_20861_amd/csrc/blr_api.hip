@@ -86,9 +86,10 @@ inline int64_t fused_min_tiles(int n_in, int b) {
     const int q = n_in / b;
     return q <= 128 ? 80 : q <= 256 ? 120 : 224;
 }
-// Up to this many tokens the coupling runs as one thread per 8 outputs (the 64-token tiles of the
-// MFMA coupling kernel would leave most of the chip idle).
-constexpr int64_t kSmallCouplingTokens = 128;
+// Up to this many tokens the coupling runs as one thread per 8 outputs; from there on the MFMA coupling kernel on its
+// 16-token tiles is ahead (BLAST 4096 x 4096, r = 640: 13.6 against 14.4 us at 33 tokens, 16.5 against 15.9 at 64,
+// 17.4 against 15.5 at 100, 19.0 against 16.3 at 128).
+constexpr int64_t kSmallCouplingTokens = 48;
 
 // The single kernel for few, wide blocks: forced by its flag, else where it was measured ahead of the three kernels.
 bool blast_narrow_possible(int64_t T, int n_in, int n_out, int b, int r, unsigned flags) {
@@ -368,7 +369,7 @@ static blr_status blast_run(const void* X, const void* U, const void* S, const v
             s1.M = tc;
             blr_status st = run_gemm(s1, dt, true, s);
             if (st != BLR_OK) return st;
-            // few tokens: the 64-token tiles of the MFMA coupling would be mostly padding; one thread per output element then
+            // few tokens: one thread per 8 outputs
             st = from_hip(z8 ? launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s, true)
                           : tc <= kSmallCouplingTokens ? launch_coupling_small(Zws, pack + pk.off_Sc, Aws, tc, b, r, s)
                                                        : launch_blast_coupling(Zws, Sp, Aws, tc, b, r, s));
