@@ -2,8 +2,11 @@
 //
 // A workgroup of WGM x WGN wavefronts owns a BM x BN output tile; each wavefront owns
 // (BM/WGM) x (BN/WGN) as a grid of 32x32 v_mfma_f32_32x32x16_bf16 tiles with fp32 accumulators.
-// Operand tiles (BM x 32 of A, BN x 32 of B, both with the contraction index contiguous) stream
-// global -> LDS directly (global_load_lds), four stages deep, one barrier per step.
+// Operand tiles (both with the contraction index contiguous) stream global -> LDS directly
+// (global_load_lds), one barrier per step. Three kernels share the layout conventions and the epilogue:
+// gemm_wide_kernel (256 x 256 tile, steps of 64 contraction indices = whole cache lines per operand row, two
+// stages), gemm_line_kernel (the smaller tiles in steps of 64 or 128, two to four stages) and gemm_dma_kernel
+// (steps of 32, four stages: short contractions, split contraction index, problems that do not fill the chip).
 // The weight tile is the FIRST MFMA operand: an accumulator lane then holds four consecutive
 // output columns of one token, which go to an LDS copy of the C tile as 8-byte writes and from
 // there to global memory as 16-byte row-contiguous stores (or element-wise through the column map
